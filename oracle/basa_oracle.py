@@ -1,0 +1,309 @@
+"""CPU oracle for Block Approximate Sparse Attention (BA-Att).
+
+TEST INFRASTRUCTURE ONLY.  This module is a plain, slow, fp64 numpy statement of
+what the method computes.  It is imported by tests, by the smoke check and by the
+benchmark's CPU-baseline leg, never by the product path, and it shares no code,
+tables or helpers with the HIP library.
+
+Every function names the passage of the paper it follows (section, equation or
+algorithm).  Where the paper leaves a choice open the choice is stated in the
+docstring ("Reading:").
+
+Conventions: one (batch, head) at a time; Q is [L_q, d], K and V are [L_k, d];
+all arithmetic is float64 on the exact input values; block g of a (sorted)
+sequence is positions [g*B, min((g+1)*B, L)).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+SORT_NONE, SORT_Q, SORT_K, SORT_QK = 0, 1, 2, 3
+
+
+# --------------------------------------------------------------------------- #
+# Budget
+# --------------------------------------------------------------------------- #
+def kappa_from_sparsity(n_k: int, sparsity: float) -> int:
+    """Per-query-block budget kappa (Alg. 1, inputs) from a target sparsity.
+
+    Reading: the paper links kappa and sparsity by no formula.  A sparsity s drops
+    floor(s * N_k) key blocks from every row and keeps the rest, at least one:
+    kappa = max(1, N_k - floor(s*N_k + 1e-9)).  The 1e-9 guards products such as
+    0.6*590 that land a hair below an integer in binary.
+    """
+    if not (0.0 <= sparsity < 1.0):
+        raise ValueError("sparsity must lie in [0, 1)")
+    dropped = int(math.floor(float(sparsity) * n_k + 1e-9))
+    return max(1, n_k - dropped)
+
+
+def num_blocks(L: int, B: int) -> int:
+    """N = ceil(L / B) (Sec. 2 defines N = L/B for L divisible by B).
+
+    Reading: a ragged tail forms one short last block."""
+    return (L + B - 1) // B
+
+
+# --------------------------------------------------------------------------- #
+# Norm-based ranking (Sec. 3.3, Eq. 9-10; Alg. 1 steps 1-2)
+# --------------------------------------------------------------------------- #
+def token_sort_keys(x: np.ndarray) -> np.ndarray:
+    """Sort key of every token: its squared L2 norm (Eq. 9 up to a monotone map).
+
+    Reading: the paper does not fix the precision of the norm.  The key is the
+    fp64 sum of squares rounded once to fp32; equal fp32 keys are ties.  Squaring
+    keeps the order of the norms and avoids a square root.
+    """
+    x64 = np.asarray(x, dtype=np.float64)
+    return (x64 * x64).sum(axis=-1).astype(np.float32)
+
+
+def norm_sort(x: np.ndarray, window: int = 0) -> np.ndarray:
+    """Permutation pi with keys non-decreasing along pi (Eq. 10).
+
+    Reading: ties keep the original order (stable sort).  "(windowed) sort" of
+    Alg. 1 step 1 is not defined in the paper; window = 0 is one sort over the
+    whole sequence, window = W sorts each run of W consecutive tokens by itself.
+    """
+    keys = token_sort_keys(x)
+    L = keys.shape[0]
+    W = L if not window else int(window)
+    perm = np.empty(L, dtype=np.int64)
+    for w0 in range(0, L, W):
+        seg = keys[w0:w0 + W]
+        perm[w0:w0 + W] = w0 + np.argsort(seg, kind="stable")
+    return perm
+
+
+def identity_perm(L: int) -> np.ndarray:
+    return np.arange(L, dtype=np.int64)
+
+
+# --------------------------------------------------------------------------- #
+# Block statistics (Sec. 3.1 mean pooling; Sec. 3.4 variances; Alg. 1 steps 3-4)
+# --------------------------------------------------------------------------- #
+def block_stats(x_sorted: np.ndarray, B: int):
+    """Per-block mean and per-dimension variance of an already ordered sequence.
+
+    Reading: Sigma = E[delta delta^T] over the block's tokens, so the variance is
+    the population one (divide by the number of tokens in the block); a ragged
+    last block uses its true token count.
+    Returns (mean [N, d], var [N, d]).
+    """
+    x = np.asarray(x_sorted, dtype=np.float64)
+    L, d = x.shape
+    N = num_blocks(L, B)
+    mean = np.zeros((N, d), dtype=np.float64)
+    var = np.zeros((N, d), dtype=np.float64)
+    for g in range(N):
+        blk = x[g * B:min((g + 1) * B, L)]
+        mean[g] = blk.sum(axis=0) / blk.shape[0]
+        dev = blk - mean[g]
+        var[g] = (dev * dev).sum(axis=0) / blk.shape[0]
+    return mean, var
+
+
+# --------------------------------------------------------------------------- #
+# Block logits (Eq. 2), diagonal-variance compensation (Eq. 14), Alg. 1 steps 5-7
+# --------------------------------------------------------------------------- #
+def baseline_logits(q_mean: np.ndarray, k_mean: np.ndarray) -> np.ndarray:
+    """l[g_q, g_k] = (Qbar . Kbar) / sqrt(d)   (Eq. 2, first line)."""
+    d = q_mean.shape[1]
+    return (q_mean @ k_mean.T) / math.sqrt(d)
+
+
+def diag_compensation(q_mean, q_var, k_mean, k_var) -> np.ndarray:
+    """Delta^[g_q, g_k] of Eq. 14: the three additive variance terms over d.
+
+    Reading: Alg. 1 step 6 names Eq. 14, so all three printed terms are used,
+    with the 1/d prefactor."""
+    d = q_mean.shape[1]
+    t1 = q_var @ (k_mean * k_mean).T       # Var[Q_t] * Kbar_t^2
+    t2 = (q_mean * q_mean) @ k_var.T       # Var[K_t] * Qbar_t^2
+    t3 = q_var @ k_var.T                   # Var[Q_t] * Var[K_t]
+    return (t1 + t2 + t3) / d
+
+
+def block_logits(q_mean, q_var, k_mean, k_var, beta: float = 1.0) -> np.ndarray:
+    """l' = l + beta * Delta^   (Eq. 13 with Eq. 14; Alg. 1 step 7)."""
+    l = baseline_logits(q_mean, k_mean)
+    if beta == 0.0:
+        return l
+    return l + beta * diag_compensation(q_mean, q_var, k_mean, k_var)
+
+
+def row_softmax(logits: np.ndarray) -> np.ndarray:
+    """m' = softmax over key blocks of every query-block row (Eq. 2, second line)."""
+    z = logits - logits.max(axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+# --------------------------------------------------------------------------- #
+# Selection (Alg. 1 steps 8-11)
+# --------------------------------------------------------------------------- #
+def select_top_kappa(m: np.ndarray, kappa: int):
+    """Keep the kappa key blocks of largest m' in every row.
+
+    Reading: equal values are ranked by lower key-block index first.
+    Returns dict(mask [N_q, N_k] bool, cols [N_q, kappa] ascending int64,
+    mass [N_q], theta [N_q] (smallest kept m'), next [N_q] (largest dropped m',
+    -inf when nothing is dropped)).
+    """
+    n_q, n_k = m.shape
+    kappa = min(int(kappa), n_k)
+    mask = np.zeros((n_q, n_k), dtype=bool)
+    cols = np.zeros((n_q, kappa), dtype=np.int64)
+    mass = np.zeros(n_q)
+    theta = np.zeros(n_q)
+    nxt = np.full(n_q, -np.inf)
+    for r in range(n_q):
+        order = np.argsort(-m[r], kind="stable")      # descending, ties -> lower index
+        keep = order[:kappa]
+        mask[r, keep] = True
+        cols[r] = np.sort(keep)
+        mass[r] = m[r, keep].sum()
+        theta[r] = m[r, order[kappa - 1]]
+        if kappa < n_k:
+            nxt[r] = m[r, order[kappa]]
+    return dict(mask=mask, cols=cols, mass=mass, theta=theta, next=nxt)
+
+
+# --------------------------------------------------------------------------- #
+# Attention (Eq. 1; Sec. 2 block-sparse attention; Alg. 1 step 12)
+# --------------------------------------------------------------------------- #
+def dense_attention(Q, K, V, return_lse: bool = False):
+    """softmax(Q K^T / sqrt(d)) V, every query against every key (Eq. 1)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(d)
+    mx = S.max(axis=1, keepdims=True)
+    P = np.exp(S - mx)
+    den = P.sum(axis=1, keepdims=True)
+    O = (P / den) @ V
+    if return_lse:
+        return O, (mx[:, 0] + np.log(den[:, 0]))
+    return O
+
+
+def attention_matrix(Q, K) -> np.ndarray:
+    """A of Eq. 1 as an explicit L_q x L_k matrix (tiny inputs only)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    S = (Q @ K.T) / math.sqrt(Q.shape[1])
+    P = np.exp(S - S.max(axis=1, keepdims=True))
+    return P / P.sum(axis=1, keepdims=True)
+
+
+def sparse_attention_block(Q, K, V, perm_q, perm_k, g_q: int, cols_row, B: int):
+    """Output rows of ONE query block g_q of the sorted order (Alg. 1 step 12).
+
+    The block's queries Q'[i] = Q[perm_q[i]] attend to the tokens of the listed key
+    blocks of K' = K[perm_k], V' = V[perm_k] only.
+    Reading: the softmax is normalised over the kept tokens (Sec. 2: only the
+    selected blocks' logits are computed).
+    Returns (rows_original [n], O_rows [n, d], lse [n]).
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    L_q, d = Q.shape
+    L_k = K.shape[0]
+    qpos = np.arange(g_q * B, min((g_q + 1) * B, L_q))
+    rows = np.asarray(perm_q)[qpos]
+    kpos = np.concatenate([np.arange(c * B, min((c + 1) * B, L_k)) for c in cols_row])
+    krows = np.asarray(perm_k)[kpos]
+    S = (Q[rows] @ K[krows].T) / math.sqrt(d)
+    mx = S.max(axis=1, keepdims=True)
+    P = np.exp(S - mx)
+    den = P.sum(axis=1, keepdims=True)
+    O = (P / den) @ V[krows]
+    return rows, O, mx[:, 0] + np.log(den[:, 0])
+
+
+def sparse_attention(Q, K, V, perm_q, perm_k, cols, B: int, return_lse: bool = False):
+    """Block-sparse attention over all query blocks, rows back in original order
+    (Alg. 1 step 12: the inverse of pi_q is applied by writing row pi_q[i])."""
+    L_q, d = np.asarray(Q).shape
+    O = np.zeros((L_q, d), dtype=np.float64)
+    lse = np.zeros(L_q, dtype=np.float64)
+    for g in range(num_blocks(L_q, B)):
+        rows, o, l = sparse_attention_block(Q, K, V, perm_q, perm_k, g, cols[g], B)
+        O[rows] = o
+        lse[rows] = l
+    return (O, lse) if return_lse else O
+
+
+# --------------------------------------------------------------------------- #
+# The whole operator (Alg. 1)
+# --------------------------------------------------------------------------- #
+def select(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK,
+           window: int = 0):
+    """Alg. 1 steps 1-11 for one head: permutations, block statistics, compensated
+    logits, row distribution, top-kappa mask.  Returns a dict with every
+    intermediate."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    perm_q = norm_sort(Q, window) if sort in (SORT_Q, SORT_QK) else identity_perm(Q.shape[0])
+    perm_k = norm_sort(K, window) if sort in (SORT_K, SORT_QK) else identity_perm(K.shape[0])
+    q_mean, q_var = block_stats(Q[perm_q], B)
+    k_mean, k_var = block_stats(K[perm_k], B)
+    logits = block_logits(q_mean, q_var, k_mean, k_var, beta)
+    m = row_softmax(logits)
+    kappa = kappa_from_sparsity(k_mean.shape[0], sparsity)
+    sel = select_top_kappa(m, kappa)
+    out = dict(perm_q=perm_q, perm_k=perm_k, q_mean=q_mean, q_var=q_var, k_mean=k_mean,
+               k_var=k_var, logits=logits, m=m, kappa=kappa)
+    out.update(sel)
+    return out
+
+
+def ba_att(Q, K, V, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK,
+           window: int = 0):
+    """Alg. 1 end to end for one head.  Returns (O [L_q, d], selection dict)."""
+    sel = select(Q, K, B, sparsity, beta, sort, window)
+    O = sparse_attention(Q, K, V, sel["perm_q"], sel["perm_k"], sel["cols"], B)
+    return O, sel
+
+
+# --------------------------------------------------------------------------- #
+# Analysis quantities (Sec. 3.1 Eq. 3; Sec. 3.2 Eq. 5-8).  Tiny inputs only.
+# --------------------------------------------------------------------------- #
+def oracle_block_mass(Q, K, B: int) -> np.ndarray:
+    """m_hat[g_q, g_k] (Eq. 3): mean over the block's query rows of the summed
+    dense attention weight falling into key block g_k."""
+    A = attention_matrix(Q, K)
+    L_q, L_k = A.shape
+    n_q, n_k = num_blocks(L_q, B), num_blocks(L_k, B)
+    m_hat = np.zeros((n_q, n_k))
+    for gq in range(n_q):
+        rows = A[gq * B:min((gq + 1) * B, L_q)]
+        for gk in range(n_k):
+            m_hat[gq, gk] = rows[:, gk * B:min((gk + 1) * B, L_k)].sum() / rows.shape[0]
+    return m_hat
+
+
+def block_norm_metrics(x, B: int):
+    """Radius R and max norm M of every block (Eq. 7)."""
+    x = np.asarray(x, dtype=np.float64)
+    mean, _ = block_stats(x, B)
+    N = mean.shape[0]
+    R = np.zeros(N)
+    M = np.zeros(N)
+    for g in range(N):
+        blk = x[g * B:min((g + 1) * B, x.shape[0])]
+        R[g] = np.sqrt(((blk - mean[g]) ** 2).sum(axis=1)).max()
+        M[g] = np.sqrt((blk ** 2).sum(axis=1)).max()
+    return R, M
+
+
+def deviation_bound(Q, K, B: int) -> np.ndarray:
+    """U[g_q, g_k] = (R^Q M^K + M^Q R^K + R^Q R^K) / sqrt(d)   (Eq. 8)."""
+    d = np.asarray(Q).shape[1]
+    Rq, Mq = block_norm_metrics(Q, B)
+    Rk, Mk = block_norm_metrics(K, B)
+    return (np.outer(Rq, Mk) + np.outer(Mq, Rk) + np.outer(Rq, Rk)) / math.sqrt(d)

@@ -1,0 +1,407 @@
+"""Pins for the CPU oracle: each test ties one oracle function to something the
+paper or the mathematics fixes independently of the oracle's own code
+(definitions written out by brute force in pure Python loops, closed forms,
+invariants, special cases).  No GPU, no HIP library."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import basa_oracle as o
+
+RNG = np.random.default_rng(20260519)
+
+
+def rand(L, d, scale=1.0):
+    return RNG.standard_normal((L, d)) * scale
+
+
+# ---------------------------------------------------------------- brute force helpers
+def loop_dense_attention(Q, K, V):
+    """Eq. 1 with explicit Python loops (no matmul, no broadcasting)."""
+    L_q, d = Q.shape
+    L_k = K.shape[0]
+    O = np.zeros((L_q, V.shape[1]))
+    A = np.zeros((L_q, L_k))
+    for i in range(L_q):
+        s = [sum(Q[i, t] * K[j, t] for t in range(d)) / math.sqrt(d) for j in range(L_k)]
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        den = sum(e)
+        for j in range(L_k):
+            A[i, j] = e[j] / den
+            for t in range(V.shape[1]):
+                O[i, t] += A[i, j] * V[j, t]
+    return O, A
+
+
+# ---------------------------------------------------------------- kappa
+@pytest.mark.parametrize("n,s,expect", [
+    (16, 0.5, 8), (512, 0.5, 256), (591, 0.5, 296), (591, 0.75, 148),
+    (1024, 0.0, 1024), (1024, 0.5, 512), (1024, 0.75, 256), (1024, 0.9, 103),
+    (590, 0.6, 236), (3, 0.99, 1), (1, 0.5, 1)])
+def test_kappa_spot_values(n, s, expect):
+    # kept = N - floor(s N), never below one block; every row keeps >= (1-s) N blocks
+    k = o.kappa_from_sparsity(n, s)
+    assert k == expect
+    assert k >= (1 - s) * n - 1e-9 and k >= 1
+
+
+def test_kappa_rejects_bad_sparsity():
+    for s in (-0.1, 1.0, 1.5):
+        with pytest.raises(ValueError):
+            o.kappa_from_sparsity(10, s)
+
+
+# ---------------------------------------------------------------- dense attention (Eq. 1)
+def test_dense_attention_matches_python_loops():
+    Q, K, V = rand(7, 5), rand(9, 5), rand(9, 3)
+    O_loop, A_loop = loop_dense_attention(Q, K, V)
+    np.testing.assert_allclose(o.dense_attention(Q, K, V), O_loop, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(o.attention_matrix(Q, K), A_loop, rtol=0, atol=1e-14)
+
+
+def test_dense_attention_closed_forms():
+    # all keys equal -> uniform weights -> output is the mean of V
+    K = np.tile(rand(1, 4), (6, 1))
+    V = rand(6, 4)
+    np.testing.assert_allclose(o.dense_attention(rand(3, 4), K, V),
+                               np.tile(V.mean(0), (3, 1)), atol=1e-14)
+    # two keys, d=1: weight of key 0 is the logistic function of q (k0-k1)
+    Q = np.array([[0.7]]); K = np.array([[1.5], [-0.5]]); V = np.array([[1.0], [0.0]])
+    expect = 1.0 / (1.0 + math.exp(-0.7 * 2.0))
+    assert abs(o.dense_attention(Q, K, V)[0, 0] - expect) < 1e-15
+    # lse closed form for zero queries: log(L_k)
+    _, lse = o.dense_attention(np.zeros((2, 3)), rand(5, 3), rand(5, 3), return_lse=True)
+    np.testing.assert_allclose(lse, math.log(5), atol=1e-15)
+
+
+# ---------------------------------------------------------------- P1: sparsity 0 == dense
+@pytest.mark.parametrize("sort", [o.SORT_NONE, o.SORT_Q, o.SORT_K, o.SORT_QK])
+@pytest.mark.parametrize("L,B", [(48, 8), (45, 8)])
+def test_zero_sparsity_equals_dense_for_every_sort_mode(sort, L, B):
+    Q, K, V = rand(L, 6), rand(L, 6), rand(L, 6)
+    O, sel = o.ba_att(Q, K, V, B, 0.0, 1.0, sort)
+    assert sel["mask"].all()
+    O_loop, _ = loop_dense_attention(Q, K, V)
+    np.testing.assert_allclose(O, O_loop, rtol=0, atol=1e-12)
+
+
+def test_zero_sparsity_equals_dense_cross_lengths():
+    Q, K, V = rand(20, 4), rand(37, 4), rand(37, 4)     # L_q != L_k, ragged key tail
+    O, _ = o.ba_att(Q, K, V, 8, 0.0)
+    np.testing.assert_allclose(O, o.dense_attention(Q, K, V), atol=1e-12)
+
+
+# ---------------------------------------------------------------- P7: norm sort
+def test_norm_sort_is_sorted_stable_permutation():
+    x = rand(200, 8)
+    x[50] = x[10]; x[120] = x[10]; x[11] = -x[10]        # constructed ties (same norm)
+    perm = o.norm_sort(x)
+    assert sorted(perm.tolist()) == list(range(200))
+    norms = [math.sqrt(sum(float(v) ** 2 for v in x[i])) for i in perm]
+    assert all(norms[i] <= norms[i + 1] * (1 + 1e-7) for i in range(199))
+    pos = {int(t): i for i, t in enumerate(perm)}
+    assert pos[10] < pos[11] < pos[50] < pos[120]        # ties keep original order
+    assert pos[11] == pos[10] + 1 and pos[50] == pos[10] + 2 and pos[120] == pos[10] + 3
+
+
+def test_norm_sort_matches_python_sorted():
+    x = rand(97, 3)
+    keys = [np.float32(sum(float(v) * float(v) for v in row)) for row in x]
+    expect = sorted(range(97), key=lambda i: (keys[i], i))
+    assert o.norm_sort(x).tolist() == expect
+
+
+def test_windowed_sort_stays_in_window():
+    x = rand(100, 4)
+    perm = o.norm_sort(x, window=32)
+    for w0 in range(0, 100, 32):
+        seg = perm[w0:w0 + 32]
+        assert sorted(seg.tolist()) == list(range(w0, min(w0 + 32, 100)))
+        k = o.token_sort_keys(x)[seg]
+        assert (np.diff(k) >= 0).all()
+    assert o.norm_sort(x, window=0).tolist() == o.norm_sort(x, window=100).tolist()
+
+
+def test_sort_key_is_fp32_rounded_squared_norm():
+    x = np.array([[3.0, 4.0], [1e-3, 0.0]])
+    k = o.token_sort_keys(x)
+    assert k.dtype == np.float32 and k[0] == np.float32(25.0) and k[1] == np.float32(1e-6)
+
+
+# ---------------------------------------------------------------- block stats (mean pooling, Sec. 3.1; variances Sec. 3.4)
+def test_block_stats_against_loops_and_ragged_tail():
+    x = rand(21, 3)
+    mean, var = o.block_stats(x, 8)
+    assert mean.shape == (3, 3)
+    for g, (a, b) in enumerate([(0, 8), (8, 16), (16, 21)]):
+        n = b - a
+        for t in range(3):
+            mu = sum(x[i, t] for i in range(a, b)) / n
+            vv = sum((x[i, t] - mu) ** 2 for i in range(a, b)) / n
+            assert abs(mean[g, t] - mu) < 1e-14 and abs(var[g, t] - vv) < 1e-14
+    # deviations from the block mean average to zero (Sec. 3.4, below Eq. 11)
+    assert np.abs((x[:8] - mean[0]).mean(0)).max() < 1e-15
+    # single-token block: zero variance
+    m1, v1 = o.block_stats(rand(9, 2), 8)
+    assert (v1[1] == 0).all()
+
+
+# ---------------------------------------------------------------- P2: Eq. 3 oracle distribution
+def test_oracle_block_mass_is_pooled_dense_attention():
+    L, B, d = 6, 2, 3            # the shape of the paper's Fig. 1 illustration
+    Q, K = rand(L, d), rand(L, d)
+    _, A = loop_dense_attention(Q, K, np.zeros((L, 1)))
+    m_hat = o.oracle_block_mass(Q, K, B)
+    for gq, gk in itertools.product(range(3), range(3)):
+        acc = 0.0
+        for i in range(gq * B, (gq + 1) * B):
+            for j in range(gk * B, (gk + 1) * B):
+                acc += A[i, j]
+        assert abs(m_hat[gq, gk] - acc / B) < 1e-14
+    np.testing.assert_allclose(m_hat.sum(1), 1.0, atol=1e-14)
+    assert (m_hat >= 0).all()
+
+
+# ---------------------------------------------------------------- P3: homogeneous blocks (Sec. 3.2 interpretation)
+def test_homogeneous_blocks_make_pre_and_post_downsample_agree():
+    B, nb, d = 4, 5, 6
+    Q = np.repeat(rand(nb, d), B, axis=0)
+    K = np.repeat(rand(nb, d), B, axis=0)
+    sel = o.select(Q, K, B, 0.4, 1.0, o.SORT_NONE)
+    assert np.abs(sel["q_var"]).max() == 0 and np.abs(sel["k_var"]).max() == 0
+    assert np.abs(o.diag_compensation(sel["q_mean"], sel["q_var"], sel["k_mean"], sel["k_var"])).max() == 0
+    assert np.abs(o.deviation_bound(Q, K, B)).max() < 1e-14
+    np.testing.assert_allclose(sel["m"], o.oracle_block_mass(Q, K, B), atol=1e-14)
+
+
+# ---------------------------------------------------------------- P4: Eq. 5 decomposition and Eq. 8 bound
+def test_logit_decomposition_and_deviation_bound():
+    L, B, d = 24, 6, 5
+    Q, K = rand(L, d, 1.3), rand(L, d, 0.8)
+    qm, _ = o.block_stats(Q, B)
+    km, _ = o.block_stats(K, B)
+    l = o.baseline_logits(qm, km)
+    U = o.deviation_bound(Q, K, B)
+    for i in range(L):
+        for j in range(L):
+            gq, gk = i // B, j // B
+            lhat = float(Q[i] @ K[j]) / math.sqrt(d)
+            dq, dk = Q[i] - qm[gq], K[j] - km[gk]
+            rhs = (dq @ km[gk] + qm[gq] @ dk + dq @ dk) / math.sqrt(d)
+            assert abs((lhat - l[gq, gk]) - rhs) < 1e-13          # Eq. 5 / Eq. 11
+            assert abs(lhat - l[gq, gk]) <= U[gq, gk] + 1e-13       # Eq. 8
+
+
+def test_baseline_logits_loop():
+    qm, km = rand(3, 4), rand(5, 4)
+    l = o.baseline_logits(qm, km)
+    for a in range(3):
+        for b in range(5):
+            assert abs(l[a, b] - sum(qm[a, t] * km[b, t] for t in range(4)) / 2.0) < 1e-14
+
+
+# ---------------------------------------------------------------- P5: Eq. 14 == variance of token logits under diagonal covariance
+def test_compensation_is_token_logit_variance_for_d1():
+    # d = 1: covariances are scalars, so the diagonal form of Eq. 14 is exact and must
+    # equal the population variance of the n_q*n_k token logits of the block pair.
+    L, B = 12, 4
+    Q, K = rand(L, 1), rand(L, 1)
+    qm, qv = o.block_stats(Q, B)
+    km, kv = o.block_stats(K, B)
+    delta = o.diag_compensation(qm, qv, km, kv)
+    for gq in range(3):
+        for gk in range(3):
+            logits = [Q[i, 0] * K[j, 0] for i in range(gq * B, gq * B + B)
+                      for j in range(gk * B, gk * B + B)]
+            mu = sum(logits) / len(logits)
+            var = sum((x - mu) ** 2 for x in logits) / len(logits)
+            assert abs(delta[gq, gk] - var) < 1e-13
+
+
+def test_compensation_with_axis_aligned_blocks():
+    # tokens of a block vary along one coordinate axis at a time (different axis per
+    # token pair, symmetric +-), so the block covariance is exactly diagonal for any d.
+    d, B = 4, 8
+    def axis_block(center, amps):
+        rows = []
+        for t in range(d):
+            e = np.zeros(d); e[t] = amps[t]
+            rows += [center + e, center - e]
+        return np.array(rows)
+    Qb = axis_block(rand(1, d)[0], [0.5, 1.0, 0.2, 0.7])
+    Kb = axis_block(rand(1, d)[0], [0.3, 0.1, 0.9, 0.4])
+    qm, qv = o.block_stats(Qb, B)
+    km, kv = o.block_stats(Kb, B)
+    cov_q = (Qb - qm[0]).T @ (Qb - qm[0]) / B
+    assert np.abs(cov_q - np.diag(np.diag(cov_q))).max() < 1e-15
+    logits = np.array([[Qb[i] @ Kb[j] / math.sqrt(d) for j in range(B)] for i in range(B)])
+    var = ((logits - logits.mean()) ** 2).mean()
+    assert abs(o.diag_compensation(qm, qv, km, kv)[0, 0] - var) < 1e-13
+
+
+def test_compensation_terms_by_loops_and_beta():
+    qm, qv, km, kv = rand(2, 3), np.abs(rand(2, 3)), rand(4, 3), np.abs(rand(4, 3))
+    delta = o.diag_compensation(qm, qv, km, kv)
+    for a in range(2):
+        for b in range(4):
+            acc = 0.0
+            for t in range(3):
+                acc += qv[a, t] * km[b, t] ** 2 + kv[b, t] * qm[a, t] ** 2 + qv[a, t] * kv[b, t]
+            assert abs(delta[a, b] - acc / 3) < 1e-14
+    base = o.baseline_logits(qm, km)
+    np.testing.assert_allclose(o.block_logits(qm, qv, km, kv, 0.0), base, atol=0)
+    np.testing.assert_allclose(o.block_logits(qm, qv, km, kv, 0.5), base + 0.5 * delta, atol=1e-15)
+    np.testing.assert_allclose(o.block_logits(qm, qv, km, kv, 1.0), base + delta, atol=1e-15)
+
+
+def test_single_contraction_form_of_compensated_logits():
+    # l' is one dot product of length 3d between per-block feature vectors
+    d = 6
+    qm, qv, km, kv = rand(3, d), np.abs(rand(3, d)), rand(5, d), np.abs(rand(5, d))
+    beta = 0.7
+    fq = np.concatenate([qm / math.sqrt(d), beta * qv / d, beta * qm ** 2 / d], axis=1)
+    fk = np.concatenate([km, km ** 2 + kv, kv], axis=1)
+    np.testing.assert_allclose(fq @ fk.T, o.block_logits(qm, qv, km, kv, beta), atol=1e-12)
+
+
+# ---------------------------------------------------------------- softmax (Eq. 2)
+def test_row_softmax():
+    l = rand(4, 7, 3.0)
+    m = o.row_softmax(l)
+    for r in range(4):
+        den = sum(math.exp(v) for v in l[r])
+        for c in range(7):
+            assert abs(m[r, c] - math.exp(l[r, c]) / den) < 1e-14
+    np.testing.assert_allclose(o.row_softmax(l + 1000.0), m, atol=1e-12)   # shift invariant, no overflow
+
+
+# ---------------------------------------------------------------- P6: selection
+def test_selection_properties_and_bruteforce():
+    m = o.row_softmax(rand(9, 13, 2.0))
+    for kappa in (1, 4, 13):
+        sel = o.select_top_kappa(m, kappa)
+        assert (sel["mask"].sum(1) == kappa).all()
+        for r in range(9):
+            ranked = sorted(range(13), key=lambda c: (-m[r, c], c))[:kappa]
+            assert sorted(ranked) == sel["cols"][r].tolist()
+            assert set(np.flatnonzero(sel["mask"][r]).tolist()) == set(ranked)
+            kept = m[r, sel["mask"][r]]
+            assert abs(sel["mass"][r] - kept.sum()) < 1e-15
+            assert sel["mass"][r] >= kappa / 13 - 1e-15          # top-kappa mass >= uniform share
+            assert sel["theta"][r] == kept.min()
+            if kappa < 13:
+                assert kept.min() >= m[r, ~sel["mask"][r]].max() == sel["next"][r]
+
+
+def test_selection_ties_prefer_lower_block_index():
+    m = np.array([[0.2, 0.2, 0.2, 0.2, 0.2], [0.1, 0.3, 0.3, 0.2, 0.1]])
+    sel = o.select_top_kappa(m, 2)
+    assert sel["cols"].tolist() == [[0, 1], [1, 2]]
+    sel = o.select_top_kappa(m, 3)
+    assert sel["cols"].tolist() == [[0, 1, 2], [1, 2, 3]]
+
+
+def test_selection_is_nested_in_sparsity():
+    Q, K = rand(96, 8), rand(96, 8)
+    prev = None
+    for s in (0.0, 0.25, 0.5, 0.75, 0.9):
+        mask = o.select(Q, K, 8, s)["mask"]
+        if prev is not None:
+            assert (prev | mask == prev).all()
+        prev = mask
+
+
+# ---------------------------------------------------------------- P8: sparse attention
+def _tiny_case(L=40, d=4, B=8, s=0.5, sort=o.SORT_QK):
+    Q, K, V = rand(L, d), rand(L, d), rand(L, d)
+    sel = o.select(Q, K, B, s, 1.0, sort)
+    return Q, K, V, sel
+
+
+def test_sparse_attention_against_python_loops():
+    # literal masked softmax over the tokens of the kept blocks, rows put back by pi_q
+    L, d, B = 22, 3, 4                                   # ragged tails on both sides
+    Q, K, V, sel = _tiny_case(L, d, B, 0.5)
+    O = o.sparse_attention(Q, K, V, sel["perm_q"], sel["perm_k"], sel["cols"], B)
+    Qs, Ks, Vs = Q[sel["perm_q"]], K[sel["perm_k"]], V[sel["perm_k"]]
+    for i in range(L):
+        gq = i // B
+        js = [j for j in range(L) if sel["mask"][gq, j // B]]
+        s = [sum(Qs[i, t] * Ks[j, t] for t in range(d)) / math.sqrt(d) for j in js]
+        mx = max(s); e = [math.exp(x - mx) for x in s]; den = sum(e)
+        for t in range(d):
+            acc = sum(e[n] / den * Vs[j, t] for n, j in enumerate(js))
+            assert abs(O[sel["perm_q"][i], t] - acc) < 1e-13
+
+
+def test_sparse_attention_constant_values_and_linearity():
+    Q, K, V, sel = _tiny_case()
+    args = (sel["perm_q"], sel["perm_k"], sel["cols"], 8)
+    c = np.tile(rand(1, 4), (40, 1))
+    np.testing.assert_allclose(o.sparse_attention(Q, K, c, *args), c, atol=1e-14)
+    V2 = rand(40, 4)
+    lhs = o.sparse_attention(Q, K, 2.0 * V - 3.0 * V2, *args)
+    rhs = 2.0 * o.sparse_attention(Q, K, V, *args) - 3.0 * o.sparse_attention(Q, K, V2, *args)
+    np.testing.assert_allclose(lhs, rhs, atol=1e-13)
+
+
+def test_kappa_one_is_dense_attention_inside_one_block():
+    L, B = 32, 8
+    Q, K, V = rand(L, 4), rand(L, 4), rand(L, 4)
+    sel = o.select(Q, K, B, 0.99)
+    assert sel["kappa"] == 1
+    O = o.sparse_attention(Q, K, V, sel["perm_q"], sel["perm_k"], sel["cols"], B)
+    for g in range(L // B):
+        rows = sel["perm_q"][g * B:(g + 1) * B]
+        c = int(sel["cols"][g, 0])
+        kr = sel["perm_k"][c * B:(c + 1) * B]
+        np.testing.assert_allclose(O[rows], o.dense_attention(Q[rows], K[kr], V[kr]), atol=1e-13)
+
+
+def test_sparse_lse_ties_selection_to_oracle_block_mass():
+    # exp(lse_sparse - lse_dense) is the dense attention mass that falls on the kept
+    # tokens; its mean over a query block is the sum of m_hat (Eq. 3) over kept blocks.
+    L, B = 48, 8
+    Q, K, V, sel = _tiny_case(L, 4, B, 0.5)
+    _, lse_s = o.sparse_attention(Q, K, V, sel["perm_q"], sel["perm_k"], sel["cols"], B, True)
+    _, lse_d = o.dense_attention(Q, K, V, return_lse=True)
+    ratio = np.exp(lse_s - lse_d)
+    assert ((ratio > 0) & (ratio <= 1 + 1e-14)).all()
+    m_hat_sorted = o.oracle_block_mass(Q[sel["perm_q"]], K[sel["perm_k"]], B)
+    for g in range(L // B):
+        rows = sel["perm_q"][g * B:(g + 1) * B]
+        assert abs(ratio[rows].mean() - m_hat_sorted[g, sel["mask"][g]].sum()) < 1e-13
+
+
+def test_key_permutation_invariance_and_query_equivariance():
+    # permuting keys together with values leaves bidirectional attention unchanged;
+    # permuting queries permutes output rows.
+    Q, K, V = rand(16, 4), rand(16, 4), rand(16, 4)
+    pk, pq = RNG.permutation(16), RNG.permutation(16)
+    base = o.dense_attention(Q, K, V)
+    np.testing.assert_allclose(o.dense_attention(Q, K[pk], V[pk]), base, atol=1e-14)
+    np.testing.assert_allclose(o.dense_attention(Q[pq], K, V), base[pq], atol=1e-14)
+
+
+# ---------------------------------------------------------------- P10: generator sanity on the tiny workload
+def test_tiny_workload_selection_is_not_flat():
+    from paper_2605_19726_amd import synth
+    w = synth.CONFIGS[0]
+    Q, K, V = synth.make_qkv(w)
+    q, k = Q[0, 0].double().numpy(), K[0, 0].double().numpy()
+    sel = o.select(q, k, w.block, 0.5)
+    assert sel["kappa"] == 8
+    # the shifted ("salient") key tokens carry the largest norms: they fill the last
+    # sorted key blocks, which every query block keeps
+    norms = np.sqrt((k ** 2).sum(1))
+    salient_tokens = np.argsort(norms)[-3 * w.block:]
+    last_blocks = sel["perm_k"][-3 * w.block:]
+    assert len(set(salient_tokens.tolist()) & set(last_blocks.tolist())) == 3 * w.block
+    assert sel["mask"][:, -3:].all()
+    assert sel["mass"].min() > 0.5
+    # without sorting, different query blocks keep different key blocks
+    sel_ns = o.select(q, k, w.block, 0.5, 1.0, o.SORT_NONE)
+    assert len({tuple(r) for r in sel_ns["cols"].tolist()}) > 4
