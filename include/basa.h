@@ -1,0 +1,164 @@
+/*
+ * basa.h — C ABI of the MI355X (gfx950) Block Approximate Sparse Attention library.
+ *
+ * The library implements the operator of the paper's Alg. 1 ("Norm-Rank Attention
+ * with Covariance Compensation") in three stages plus a dense baseline:
+ *   1. norm ranking and block pooling      (Sec. 3.3 Eq. 9-10; Sec. 3.1; Sec. 3.4)
+ *   2. compensated block-score map, row distribution and top-kappa block selection
+ *                                           (Eq. 2, Eq. 13-14, Alg. 1 steps 5-11)
+ *   3. bidirectional block-sparse attention over the kept blocks
+ *                                           (Sec. 2, Alg. 1 step 12)
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer unless a comment says "host".
+ *     Descriptor structs (basa_tensor, basa_params) are read on the HOST.
+ *   - The caller owns every buffer, including workspaces.  The library never
+ *     allocates or frees device memory and never synchronises: all work is
+ *     enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Functions return a basa_status.  Arguments are validated on the host before
+ *     any kernel is launched; on error nothing has been enqueued.  A human-readable
+ *     reason is kept per thread and returned by basa_last_error().
+ *   - Tensors are [batch, heads, L, d] with d contiguous; strides are in elements.
+ *     Supported: d in {64, 128}; dtype f32 or bf16; block B in {64, 128}.
+ *     Query head h reads KV head h / (heads_q / heads_kv).
+ *   - Blocks: block g of a sorted sequence holds sorted positions
+ *     [g*B, min((g+1)*B, L)); N = ceil(L/B); a ragged last block is allowed.
+ */
+#ifndef BASA_H
+#define BASA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BASA_OK = 0,
+  BASA_ERR_INVALID_ARG = 1,  /* null pointer, bad shape, bad parameter value            */
+  BASA_ERR_UNSUPPORTED = 2,  /* legal request this build has no kernel for               */
+  BASA_ERR_WORKSPACE = 3,    /* workspace pointer null or smaller than required          */
+  BASA_ERR_HIP = 4           /* a HIP runtime call failed; see basa_last_error()         */
+} basa_status;
+
+typedef enum { BASA_F32 = 0, BASA_BF16 = 1 } basa_dtype;
+
+/* Which sequences are norm-sorted before blocking (the four rows of Tab. 7). */
+typedef enum { BASA_SORT_NONE = 0, BASA_SORT_Q = 1, BASA_SORT_K = 2, BASA_SORT_QK = 3 } basa_sort;
+
+typedef struct {
+  const void* ptr;           /* device                                                    */
+  int32_t dtype;             /* basa_dtype                                                */
+  int32_t batch, heads, L, d;
+  int64_t stride_b, stride_h, stride_l;   /* in elements; the d axis has stride 1        */
+} basa_tensor;
+
+typedef struct {
+  int32_t block;             /* B: 64 or 128 (Tab. 1 caption; Sec. 4.1 uses 128)          */
+  int32_t sort;              /* basa_sort; the full method is BASA_SORT_QK                */
+  int32_t window;            /* 0: one sort per head (Sec. 3.3); W>0: every run of W
+                                consecutive tokens is sorted by itself (Alg. 1 step 1,
+                                "(windowed) sort"); W must be a multiple of B             */
+  float beta;                /* compensation weight of Eq. 13 (default 1; 0 = plain Eq. 2) */
+  double sparsity;           /* s in [0,1): every query block keeps
+                                kappa = max(1, N_k - floor(s*N_k + 1e-9)) key blocks       */
+} basa_params;
+
+/* Host helper: the per-query-block budget kappa (Alg. 1 input) for n_k key blocks at
+ * sparsity s, by the formula above.  Returns -1 if s is outside [0,1) or n_k < 1. */
+int32_t basa_kappa(int32_t n_k, double sparsity);
+
+/* Bytes of workspace basa_select needs for these shapes (0 on invalid arguments). */
+size_t basa_select_workspace_size(const basa_tensor* q, const basa_tensor* k, const basa_params* p);
+/* Bytes of workspace basa_sparse_attn / basa_dense_attn need (0 on invalid arguments). */
+size_t basa_attn_workspace_size(const basa_tensor* q, const basa_tensor* k, const basa_params* p);
+/* Bytes of workspace basa_norm_sort needs for x. */
+size_t basa_sort_workspace_size(const basa_tensor* x, const basa_params* p);
+
+/*
+ * Norm ranking of one tensor (Sec. 3.3, Eq. 9-10; Alg. 1 steps 1-2).
+ * The sort key of a token is its squared L2 norm, accumulated in fp64 and rounded
+ * once to fp32; tokens are ordered by non-decreasing key, equal keys by original
+ * index; p->window selects windowed sorting.
+ *   perm      out [batch, heads, L] int32: perm[i] = original index of the token at
+ *             sorted position i.
+ *   keys_out  out, nullable, [batch, heads, L] float: the fp32 keys, original order.
+ *   ws        workspace of basa_sort_workspace_size() bytes.
+ */
+basa_status basa_norm_sort(const basa_tensor* x, const basa_params* p, int32_t* perm,
+                           float* keys_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Block pooling (Sec. 3.1 mean pooling; Sec. 3.4 "blockwise first/second moments";
+ * Alg. 1 steps 3-4): per block of the ordered sequence x[perm], the mean and the
+ * per-dimension population variance (divide by the block's token count).
+ *   perm   nullable [batch, heads, L] int32; NULL = original order.
+ *   mean   out [batch, heads, N, d] float.
+ *   var    out, nullable, [batch, heads, N, d] float.
+ */
+basa_status basa_downsample(const basa_tensor* x, const int32_t* perm, const basa_params* p,
+                            float* mean, float* var, void* stream);
+
+/*
+ * Block selection (Alg. 1 steps 1-11): norm ranking of Q and/or K (p->sort), block
+ * statistics, compensated block logits l' = Qbar.Kbar/sqrt(d) + beta*Delta^ with
+ * Delta^ of Eq. 14, row softmax m' (Eq. 2) and the kappa largest m' per row (equal
+ * values: lower key-block index first).
+ *   mask_bits  out, nullable, [batch, heads_q, N_q, ceil(N_k/32)] uint32, bit (g_k%32)
+ *              of word g_k/32 set iff block pair (g_q, g_k) is kept.
+ *   row_count  out [batch, heads_q, N_q] int32: number of kept key blocks (= kappa).
+ *   row_cols   out [batch, heads_q, N_q, kappa] int32: kept key blocks, ascending.
+ *   perm_q     out [batch, heads_q, L_q] int32 (identity when Q is not sorted).
+ *   perm_k     out [batch, heads_kv, L_k] int32 (identity when K is not sorted).
+ *   row_mass   out, nullable, [batch, heads_q, N_q] float: sum of kept m'.
+ *   scores     out, nullable, [batch, heads_q, N_q, N_k] float: the logits l'.
+ *   ws         workspace of basa_select_workspace_size() bytes.
+ */
+basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_params* p,
+                        uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols,
+                        int32_t* perm_q, int32_t* perm_k, float* row_mass, float* scores,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Block-sparse attention (Sec. 2; Alg. 1 step 12).  For every query block g_q of the
+ * ordered queries Q' = Q[perm_q], softmax attention (Eq. 1) restricted to the tokens
+ * of the listed key blocks of K' = K[perm_k], V' = V[perm_k], normalised over those
+ * tokens; the row of sorted position i is written to out row perm_q[i].
+ * bf16 tensors: bf16 MFMA with fp32 accumulation and fp32 softmax state (d = 128);
+ * f32 tensors: fp32 throughout.
+ *   row_count    [batch, heads_q, N_q] int32, each in [1, N_k].
+ *   row_cols     [batch, heads_q, N_q, cols_stride] int32, ascending, each in [0, N_k).
+ *                NULL means every key block for every row (dense).
+ *   perm_q/_k    nullable (NULL = identity).
+ *   out          [batch, heads_q, L_q, d] contiguous, dtype of q.
+ *   lse          out, nullable, [batch, heads_q, L_q] float: log-sum-exp of the kept
+ *                logits of every query (original order).
+ *   ws           workspace of basa_attn_workspace_size() bytes.
+ */
+basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
+                             const int32_t* row_count, const int32_t* row_cols,
+                             int32_t cols_stride, const int32_t* perm_q, const int32_t* perm_k,
+                             const basa_params* p, void* out, float* lse, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/*
+ * Dense bidirectional attention (Eq. 1) through the same kernels with every key
+ * block listed and no permutation: the baseline sparse runs are compared with.
+ * Only p->block is read.
+ */
+basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
+                            const basa_params* p, void* out, float* lse, void* ws,
+                            size_t ws_bytes, void* stream);
+
+const char* basa_status_string(basa_status s);
+/* Reason of the last non-OK status returned on this thread (host string, owned by the
+ * library, valid until the next failing call on the thread). */
+const char* basa_last_error(void);
+/* Library version, e.g. "basa 0.1 gfx950". */
+const char* basa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BASA_H */

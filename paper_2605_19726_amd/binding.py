@@ -1,0 +1,247 @@
+"""ctypes binding of libbasa.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (include/basa.h).  torch is
+used to allocate device buffers and to supply the current HIP stream; every
+computation runs in the library's kernels.  If the library is missing or cannot be
+loaded the first call raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbasa.so")
+_lib = None
+
+BASA_OK = 0
+SORT_NONE, SORT_Q, SORT_K, SORT_QK = 0, 1, 2, 3
+F32, BF16 = 0, 1
+
+EXPORTS = (
+    "basa_kappa", "basa_select_workspace_size", "basa_attn_workspace_size",
+    "basa_sort_workspace_size", "basa_norm_sort", "basa_downsample", "basa_select",
+    "basa_sparse_attn", "basa_dense_attn", "basa_status_string", "basa_last_error",
+    "basa_version",
+)
+
+
+class BasaTensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("dtype", C.c_int32), ("batch", C.c_int32),
+                ("heads", C.c_int32), ("L", C.c_int32), ("d", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_l", C.c_int64)]
+
+
+class BasaParams(C.Structure):
+    _fields_ = [("block", C.c_int32), ("sort", C.c_int32), ("window", C.c_int32),
+                ("beta", C.c_float), ("sparsity", C.c_double)]
+
+
+class BasaError(RuntimeError):
+    def __init__(self, status: int, name: str, reason: str):
+        super().__init__(f"{name}: {reason}")
+        self.status = status
+        self.status_name = name
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Open libbasa.so (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} not found: build it with "
+                           "`python -m paper_2605_19726_amd.build` (no fallback path exists)")
+    lib = C.CDLL(_LIB_PATH)
+    T, P, V = C.POINTER(BasaTensor), C.POINTER(BasaParams), C.c_void_p
+    lib.basa_kappa.restype = C.c_int32
+    lib.basa_kappa.argtypes = [C.c_int32, C.c_double]
+    for n in ("basa_select_workspace_size", "basa_attn_workspace_size"):
+        getattr(lib, n).restype = C.c_size_t
+        getattr(lib, n).argtypes = [T, T, P]
+    lib.basa_sort_workspace_size.restype = C.c_size_t
+    lib.basa_sort_workspace_size.argtypes = [T, P]
+    lib.basa_norm_sort.restype = C.c_int
+    lib.basa_norm_sort.argtypes = [T, P, V, V, V, C.c_size_t, V]
+    lib.basa_downsample.restype = C.c_int
+    lib.basa_downsample.argtypes = [T, V, P, V, V, V]
+    lib.basa_select.restype = C.c_int
+    lib.basa_select.argtypes = [T, T, P, V, V, V, V, V, V, V, V, C.c_size_t, V]
+    lib.basa_sparse_attn.restype = C.c_int
+    lib.basa_sparse_attn.argtypes = [T, T, T, V, V, C.c_int32, V, V, P, V, V, V, C.c_size_t, V]
+    lib.basa_dense_attn.restype = C.c_int
+    lib.basa_dense_attn.argtypes = [T, T, T, P, V, V, V, C.c_size_t, V]
+    lib.basa_status_string.restype = C.c_char_p
+    lib.basa_status_string.argtypes = [C.c_int]
+    lib.basa_last_error.restype = C.c_char_p
+    lib.basa_last_error.argtypes = []
+    lib.basa_version.restype = C.c_char_p
+    lib.basa_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != BASA_OK:
+        lib = load()
+        raise BasaError(status, lib.basa_status_string(status).decode(),
+                        lib.basa_last_error().decode())
+
+
+def tensor_desc(x: torch.Tensor) -> BasaTensor:
+    """Descriptor of a [batch, heads, L, d] tensor (no copy; d must be contiguous)."""
+    if x.dim() != 4:
+        raise ValueError("expected a [batch, heads, L, d] tensor")
+    if x.stride(3) != 1:
+        raise ValueError("the head dimension must be contiguous")
+    if x.dtype == torch.float32:
+        dt = F32
+    elif x.dtype == torch.bfloat16:
+        dt = BF16
+    else:
+        raise ValueError(f"unsupported dtype {x.dtype}")
+    return BasaTensor(x.data_ptr(), dt, x.shape[0], x.shape[1], x.shape[2], x.shape[3],
+                      x.stride(0), x.stride(1), x.stride(2))
+
+
+def params(block: int, sparsity: float = 0.0, beta: float = 1.0, sort: int = SORT_QK,
+           window: int = 0) -> BasaParams:
+    return BasaParams(int(block), int(sort), int(window), float(beta), float(sparsity))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(x: torch.Tensor):
+    return C.c_void_p(torch.cuda.current_stream(x.device).cuda_stream)
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def basa_version() -> str:
+    return load().basa_version().decode()
+
+
+def basa_kappa(n_k: int, sparsity: float) -> int:
+    return int(load().basa_kappa(int(n_k), float(sparsity)))
+
+
+def n_blocks(L: int, block: int) -> int:
+    return (L + block - 1) // block
+
+
+def basa_norm_sort(x: torch.Tensor, block: int, window: int = 0, return_keys: bool = False, ws=None):
+    lib = load()
+    xd, p = tensor_desc(x), params(block, window=window)
+    b, h, L, _ = x.shape
+    perm = torch.empty((b, h, L), dtype=torch.int32, device=x.device)
+    keys = torch.empty((b, h, L), dtype=torch.float32, device=x.device) if return_keys else None
+    need = lib.basa_sort_workspace_size(C.byref(xd), C.byref(p))
+    ws = _ws(need, x.device) if ws is None else ws
+    _check(lib.basa_norm_sort(C.byref(xd), C.byref(p), _ptr(perm), _ptr(keys), _ptr(ws),
+                              ws.numel(), _stream(x)))
+    return (perm, keys) if return_keys else perm
+
+
+def basa_downsample(x: torch.Tensor, block: int, perm: Optional[torch.Tensor] = None,
+                    want_var: bool = True):
+    lib = load()
+    xd, p = tensor_desc(x), params(block)
+    b, h, L, d = x.shape
+    N = n_blocks(L, block)
+    mean = torch.empty((b, h, N, d), dtype=torch.float32, device=x.device)
+    var = torch.empty((b, h, N, d), dtype=torch.float32, device=x.device) if want_var else None
+    _check(lib.basa_downsample(C.byref(xd), _ptr(perm), C.byref(p), _ptr(mean), _ptr(var), _stream(x)))
+    return mean, var
+
+
+class Selection:
+    """Outputs of basa_select (device tensors)."""
+    __slots__ = ("mask_bits", "row_count", "row_cols", "perm_q", "perm_k", "row_mass", "scores",
+                 "kappa", "n_q", "n_k")
+
+
+def select_workspace_size(q, k, p: BasaParams) -> int:
+    lib = load()
+    qd, kd = tensor_desc(q), tensor_desc(k)
+    return int(lib.basa_select_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)))
+
+
+def attn_workspace_size(q, k, p: BasaParams) -> int:
+    lib = load()
+    qd, kd = tensor_desc(q), tensor_desc(k)
+    return int(lib.basa_attn_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)))
+
+
+def basa_select(q: torch.Tensor, k: torch.Tensor, block: int, sparsity: float, beta: float = 1.0,
+                sort: int = SORT_QK, window: int = 0, want_mask: bool = True,
+                want_mass: bool = True, want_scores: bool = False, ws=None, out: Selection = None):
+    lib = load()
+    qd, kd = tensor_desc(q), tensor_desc(k)
+    p = params(block, sparsity, beta, sort, window)
+    b, hq, Lq, _ = q.shape
+    hk, Lk = k.shape[1], k.shape[2]
+    n_q, n_k = n_blocks(Lq, block), n_blocks(Lk, block)
+    kappa = basa_kappa(n_k, sparsity)
+    if kappa < 0:
+        raise BasaError(1, "BASA_ERR_INVALID_ARG", f"sparsity {sparsity} outside [0, 1)")
+    dev = q.device
+    s = out
+    if s is None:
+        s = Selection()
+        s.mask_bits = torch.empty((b, hq, n_q, (n_k + 31) // 32), dtype=torch.int32, device=dev) if want_mask else None
+        s.row_count = torch.empty((b, hq, n_q), dtype=torch.int32, device=dev)
+        s.row_cols = torch.empty((b, hq, n_q, kappa), dtype=torch.int32, device=dev)
+        s.perm_q = torch.empty((b, hq, Lq), dtype=torch.int32, device=dev)
+        s.perm_k = torch.empty((b, hk, Lk), dtype=torch.int32, device=dev)
+        s.row_mass = torch.empty((b, hq, n_q), dtype=torch.float32, device=dev) if want_mass else None
+        s.scores = torch.empty((b, hq, n_q, n_k), dtype=torch.float32, device=dev) if want_scores else None
+        s.kappa, s.n_q, s.n_k = kappa, n_q, n_k
+    if ws is None:
+        ws = _ws(lib.basa_select_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)), dev)
+    _check(lib.basa_select(C.byref(qd), C.byref(kd), C.byref(p), _ptr(s.mask_bits), _ptr(s.row_count),
+                           _ptr(s.row_cols), _ptr(s.perm_q), _ptr(s.perm_k), _ptr(s.row_mass),
+                           _ptr(s.scores), _ptr(ws), ws.numel(), _stream(q)))
+    return s
+
+
+def basa_sparse_attn(q, k, v, row_count, row_cols, block: int, perm_q=None, perm_k=None,
+                     want_lse: bool = False, ws=None, out=None):
+    lib = load()
+    qd, kd, vd = tensor_desc(q), tensor_desc(k), tensor_desc(v)
+    p = params(block)
+    b, hq, Lq, d = q.shape
+    if out is None:
+        out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)
+    lse = torch.empty((b, hq, Lq), dtype=torch.float32, device=q.device) if want_lse else None
+    if ws is None:
+        ws = _ws(lib.basa_attn_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)), q.device)
+    stride = 0 if row_cols is None else int(row_cols.shape[-1])
+    _check(lib.basa_sparse_attn(C.byref(qd), C.byref(kd), C.byref(vd), _ptr(row_count), _ptr(row_cols),
+                                stride, _ptr(perm_q), _ptr(perm_k), C.byref(p), _ptr(out), _ptr(lse),
+                                _ptr(ws), ws.numel(), _stream(q)))
+    return (out, lse) if want_lse else out
+
+
+def basa_dense_attn(q, k, v, block: int = 128, want_lse: bool = False, ws=None, out=None):
+    lib = load()
+    qd, kd, vd = tensor_desc(q), tensor_desc(k), tensor_desc(v)
+    p = params(block)
+    b, hq, Lq, d = q.shape
+    if out is None:
+        out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)
+    lse = torch.empty((b, hq, Lq), dtype=torch.float32, device=q.device) if want_lse else None
+    if ws is None:
+        ws = _ws(lib.basa_attn_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)), q.device)
+    _check(lib.basa_dense_attn(C.byref(qd), C.byref(kd), C.byref(vd), C.byref(p), _ptr(out), _ptr(lse),
+                               _ptr(ws), ws.numel(), _stream(q)))
+    return (out, lse) if want_lse else out

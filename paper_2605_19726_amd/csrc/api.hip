@@ -1,0 +1,281 @@
+// extern "C" boundary of the basa library: host-side validation, workspace carving and
+// the order in which the stage kernels are enqueued.  Nothing here allocates device
+// memory or synchronises.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include "common.hpp"
+
+namespace basa {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+basa_status hip_fail(hipError_t e, const char* what) {
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return BASA_ERR_HIP;
+}
+
+namespace {
+
+int kappa_of(int n_k, double s) {
+  if (!(s >= 0.0 && s < 1.0) || n_k < 1) return -1;
+  const int dropped = (int)std::floor(s * (double)n_k + 1e-9);
+  const int k = n_k - dropped;
+  return k < 1 ? 1 : k;
+}
+
+basa_status check_tensor(const basa_tensor* t, const char* name) {
+  if (!t) { set_error("%s: null tensor descriptor", name); return BASA_ERR_INVALID_ARG; }
+  if (!t->ptr) { set_error("%s: null data pointer", name); return BASA_ERR_INVALID_ARG; }
+  if (t->dtype != BASA_F32 && t->dtype != BASA_BF16) {
+    set_error("%s: dtype %d is neither f32 nor bf16", name, t->dtype); return BASA_ERR_INVALID_ARG;
+  }
+  if (t->batch < 1 || t->heads < 1 || t->L < 1) {
+    set_error("%s: batch, heads and L must be >= 1 (got %d, %d, %d)", name, t->batch, t->heads, t->L);
+    return BASA_ERR_INVALID_ARG;
+  }
+  if (t->d != 64 && t->d != 128) {
+    set_error("%s: head dimension %d not supported (64 or 128)", name, t->d); return BASA_ERR_UNSUPPORTED;
+  }
+  const int per16 = t->dtype == BASA_BF16 ? 8 : 4;
+  if (t->stride_l < t->d || t->stride_l % per16 || t->stride_h % per16 || t->stride_b % per16 ||
+      t->stride_h < 0 || t->stride_b < 0) {
+    set_error("%s: strides must be non-negative multiples of 16 bytes with stride_l >= d", name);
+    return BASA_ERR_INVALID_ARG;
+  }
+  if (reinterpret_cast<uintptr_t>(t->ptr) % 16) {
+    set_error("%s: data pointer must be 16-byte aligned", name); return BASA_ERR_INVALID_ARG;
+  }
+  if ((int64_t)t->batch * t->heads > 65535) {
+    set_error("%s: batch*heads exceeds 65535", name); return BASA_ERR_UNSUPPORTED;
+  }
+  return BASA_OK;
+}
+
+basa_status check_params(const basa_params* p, bool need_sparsity) {
+  if (!p) { set_error("null basa_params"); return BASA_ERR_INVALID_ARG; }
+  if (p->block != 64 && p->block != 128) {
+    set_error("block size %d not supported (64 or 128)", p->block); return BASA_ERR_UNSUPPORTED;
+  }
+  if (p->sort < BASA_SORT_NONE || p->sort > BASA_SORT_QK) {
+    set_error("sort mode %d out of range", p->sort); return BASA_ERR_INVALID_ARG;
+  }
+  if (p->window < 0 || (p->window % p->block) != 0) {
+    set_error("window %d must be 0 or a positive multiple of the block size", p->window);
+    return BASA_ERR_INVALID_ARG;
+  }
+  if (need_sparsity && !(p->sparsity >= 0.0 && p->sparsity < 1.0)) {
+    set_error("sparsity %g outside [0, 1)", p->sparsity); return BASA_ERR_INVALID_ARG;
+  }
+  if (!(p->beta == p->beta) || std::isinf(p->beta)) {
+    set_error("beta must be finite"); return BASA_ERR_INVALID_ARG;
+  }
+  return BASA_OK;
+}
+
+basa_status check_qk(const basa_tensor* q, const basa_tensor* k) {
+  basa_status s;
+  if ((s = check_tensor(q, "q")) != BASA_OK) return s;
+  if ((s = check_tensor(k, "k")) != BASA_OK) return s;
+  if (q->dtype != k->dtype || q->d != k->d || q->batch != k->batch) {
+    set_error("q and k must agree in dtype, head dimension and batch"); return BASA_ERR_INVALID_ARG;
+  }
+  if (q->heads % k->heads != 0) {
+    set_error("query heads (%d) must be a multiple of kv heads (%d)", q->heads, k->heads);
+    return BASA_ERR_INVALID_ARG;
+  }
+  return BASA_OK;
+}
+
+basa_status check_qkv(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v) {
+  basa_status s;
+  if ((s = check_qk(q, k)) != BASA_OK) return s;
+  if ((s = check_tensor(v, "v")) != BASA_OK) return s;
+  if (v->dtype != k->dtype || v->d != k->d || v->batch != k->batch || v->heads != k->heads || v->L != k->L) {
+    set_error("v must have the shape and dtype of k"); return BASA_ERR_INVALID_ARG;
+  }
+  return BASA_OK;
+}
+
+struct SelectWs {
+  size_t sort_off, featq_off, featk_off, scores_off, total;
+};
+
+SelectWs carve_select(const basa_tensor* q, const basa_tensor* k, const basa_params* p) {
+  const int BHq = q->batch * q->heads, BHk = k->batch * k->heads;
+  const int Nq = ceil_div(q->L, p->block), Nk = ceil_div(k->L, p->block);
+  SelectWs w;
+  size_t o = 0;
+  w.sort_off = o;
+  o += sort_workspace_bytes(BHq > BHk ? BHq : BHk, q->L > k->L ? q->L : k->L);
+  w.featq_off = o; o += align_up((size_t)BHq * Nq * 3 * q->d * sizeof(float), 256);
+  w.featk_off = o; o += align_up((size_t)BHk * Nk * 3 * k->d * sizeof(float), 256);
+  w.scores_off = o; o += align_up((size_t)BHq * Nq * Nk * sizeof(float), 256);
+  w.total = o;
+  return w;
+}
+
+bool use_mfma(const basa_tensor* q) { return q->dtype == BASA_BF16 && q->d == 128; }
+
+basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
+                        const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,
+                        const int32_t* perm_q, const int32_t* perm_k, int B, void* out, float* lse,
+                        void* ws, size_t ws_bytes, void* stream) {
+  if (!out) { set_error("null output pointer"); return BASA_ERR_INVALID_ARG; }
+  if (reinterpret_cast<uintptr_t>(out) % 16) { set_error("out must be 16-byte aligned"); return BASA_ERR_INVALID_ARG; }
+  AttnArgs a;
+  a.q = view_of(*q); a.k = view_of(*k); a.v = view_of(*v);
+  a.row_count = row_count; a.row_cols = row_cols; a.cols_stride = cols_stride;
+  a.perm_q = perm_q; a.perm_k = perm_k; a.B = B; a.out = out; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (use_mfma(q)) {
+    const size_t need = attn_mfma_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L, q->d, B);
+    if (!ws || ws_bytes < need) {
+      set_error("attention workspace too small: need %zu bytes, got %zu", need, ws ? ws_bytes : (size_t)0);
+      return BASA_ERR_WORKSPACE;
+    }
+    if (reinterpret_cast<uintptr_t>(ws) % 256) { set_error("workspace must be 256-byte aligned"); return BASA_ERR_INVALID_ARG; }
+    return launch_attn_mfma(a, st);
+  }
+  return launch_attn_simple(a, st);
+}
+
+}  // namespace
+}  // namespace basa
+
+using namespace basa;
+
+extern "C" {
+
+int32_t basa_kappa(int32_t n_k, double sparsity) { return kappa_of(n_k, sparsity); }
+
+size_t basa_sort_workspace_size(const basa_tensor* x, const basa_params* p) {
+  if (check_tensor(x, "x") != BASA_OK || check_params(p, false) != BASA_OK) return 0;
+  return sort_workspace_bytes(x->batch * x->heads, x->L);
+}
+
+size_t basa_select_workspace_size(const basa_tensor* q, const basa_tensor* k, const basa_params* p) {
+  if (check_qk(q, k) != BASA_OK || check_params(p, true) != BASA_OK) return 0;
+  return carve_select(q, k, p).total;
+}
+
+size_t basa_attn_workspace_size(const basa_tensor* q, const basa_tensor* k, const basa_params* p) {
+  if (check_qk(q, k) != BASA_OK || check_params(p, false) != BASA_OK) return 0;
+  if (!use_mfma(q)) return 256;   // the fp32 path needs none; keep the size non-zero for callers
+  return attn_mfma_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L, q->d, p->block);
+}
+
+basa_status basa_norm_sort(const basa_tensor* x, const basa_params* p, int32_t* perm, float* keys_out,
+                           void* ws, size_t ws_bytes, void* stream) {
+  basa_status s;
+  if ((s = check_tensor(x, "x")) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  if (!perm) { set_error("null perm output"); return BASA_ERR_INVALID_ARG; }
+  const size_t need = sort_workspace_bytes(x->batch * x->heads, x->L);
+  if (!ws || ws_bytes < need) {
+    set_error("sort workspace too small: need %zu bytes, got %zu", need, ws ? ws_bytes : (size_t)0);
+    return BASA_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(ws) % 256) { set_error("workspace must be 256-byte aligned"); return BASA_ERR_INVALID_ARG; }
+  return launch_norm_sort(view_of(*x), p->window, perm, keys_out, ws, reinterpret_cast<hipStream_t>(stream));
+}
+
+basa_status basa_downsample(const basa_tensor* x, const int32_t* perm, const basa_params* p, float* mean,
+                            float* var, void* stream) {
+  basa_status s;
+  if ((s = check_tensor(x, "x")) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  if (!mean) { set_error("null mean output"); return BASA_ERR_INVALID_ARG; }
+  return launch_block_stats(view_of(*x), perm, p->block, mean, var, nullptr, 0, 0.f,
+                            reinterpret_cast<hipStream_t>(stream));
+}
+
+basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_params* p,
+                        uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols, int32_t* perm_q,
+                        int32_t* perm_k, float* row_mass, float* scores, void* ws, size_t ws_bytes,
+                        void* stream) {
+  basa_status s;
+  if ((s = check_qk(q, k)) != BASA_OK) return s;
+  if ((s = check_params(p, true)) != BASA_OK) return s;
+  if (!row_count || !row_cols || !perm_q || !perm_k) {
+    set_error("row_count, row_cols, perm_q and perm_k outputs are required"); return BASA_ERR_INVALID_ARG;
+  }
+  const SelectWs w = carve_select(q, k, p);
+  if (!ws || ws_bytes < w.total) {
+    set_error("select workspace too small: need %zu bytes, got %zu", w.total, ws ? ws_bytes : (size_t)0);
+    return BASA_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(ws) % 256) { set_error("workspace must be 256-byte aligned"); return BASA_ERR_INVALID_ARG; }
+  const int B = p->block;
+  const int BHq = q->batch * q->heads, BHk = k->batch * k->heads;
+  const int Nq = ceil_div(q->L, B), Nk = ceil_div(k->L, B);
+  if (Nk > 4096) { set_error("more than 4096 key blocks per row (%d) not supported", Nk); return BASA_ERR_UNSUPPORTED; }
+  const int kappa = kappa_of(Nk, p->sparsity);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* base = reinterpret_cast<char*>(ws);
+  void* sort_ws = base + w.sort_off;
+  float* featq = reinterpret_cast<float*>(base + w.featq_off);
+  float* featk = reinterpret_cast<float*>(base + w.featk_off);
+  float* sc = scores ? scores : reinterpret_cast<float*>(base + w.scores_off);
+  const TensorView qv = view_of(*q), kv = view_of(*k);
+
+  const bool sort_q = p->sort == BASA_SORT_Q || p->sort == BASA_SORT_QK;
+  const bool sort_k = p->sort == BASA_SORT_K || p->sort == BASA_SORT_QK;
+  if (sort_q) s = launch_norm_sort(qv, p->window, perm_q, nullptr, sort_ws, st);
+  else s = launch_iota_perm(perm_q, BHq, q->L, st);
+  if (s != BASA_OK) return s;
+  if (sort_k) s = launch_norm_sort(kv, p->window, perm_k, nullptr, sort_ws, st);
+  else s = launch_iota_perm(perm_k, BHk, k->L, st);
+  if (s != BASA_OK) return s;
+
+  if ((s = launch_block_stats(qv, sort_q ? perm_q : nullptr, B, nullptr, nullptr, featq, 1, p->beta, st)) != BASA_OK) return s;
+  if ((s = launch_block_stats(kv, sort_k ? perm_k : nullptr, B, nullptr, nullptr, featk, 0, p->beta, st)) != BASA_OK) return s;
+  const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
+  if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
+  return launch_row_select(sc, BHq * Nq, Nk, kappa, mask_bits, row_count, row_cols, row_mass, st);
+}
+
+basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
+                             const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,
+                             const int32_t* perm_q, const int32_t* perm_k, const basa_params* p, void* out,
+                             float* lse, void* ws, size_t ws_bytes, void* stream) {
+  basa_status s;
+  if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  if (row_cols && !row_count) { set_error("row_cols given without row_count"); return BASA_ERR_INVALID_ARG; }
+  if (row_cols && cols_stride < 1) { set_error("cols_stride must be >= 1"); return BASA_ERR_INVALID_ARG; }
+  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, out, lse, ws,
+                     ws_bytes, stream);
+}
+
+basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
+                            const basa_params* p, void* out, float* lse, void* ws, size_t ws_bytes,
+                            void* stream) {
+  basa_status s;
+  if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, out, lse, ws, ws_bytes, stream);
+}
+
+const char* basa_status_string(basa_status s) {
+  switch (s) {
+    case BASA_OK: return "BASA_OK";
+    case BASA_ERR_INVALID_ARG: return "BASA_ERR_INVALID_ARG";
+    case BASA_ERR_UNSUPPORTED: return "BASA_ERR_UNSUPPORTED";
+    case BASA_ERR_WORKSPACE: return "BASA_ERR_WORKSPACE";
+    case BASA_ERR_HIP: return "BASA_ERR_HIP";
+  }
+  return "BASA_ERR_UNKNOWN";
+}
+
+const char* basa_last_error(void) { return g_err; }
+const char* basa_version(void) { return "basa 0.1 gfx950"; }
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Shared host/device declarations of the basa library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "basa.h"
+
+namespace basa {
+
+constexpr int kWave = 64;
+
+// A [batch, heads, L, d] tensor as the kernels see it (passed by value).
+struct TensorView {
+  const void* ptr;
+  int32_t dtype;  // basa_dtype
+  int32_t batch, heads, L, d;
+  int64_t stride_b, stride_h, stride_l;
+  __host__ __device__ inline int64_t head_offset(int bh) const {
+    int b = bh / heads, h = bh - b * heads;
+    return (int64_t)b * stride_b + (int64_t)h * stride_h;
+  }
+};
+
+inline TensorView view_of(const basa_tensor& t) {
+  return TensorView{t.ptr, t.dtype, t.batch, t.heads, t.L, t.d, t.stride_b, t.stride_h, t.stride_l};
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Thread-local error text behind basa_last_error().
+void set_error(const char* fmt, ...);
+basa_status hip_fail(hipError_t e, const char* what);
+
+#define BASA_HIP_CHECK_LAUNCH(what)                          \
+  do {                                                       \
+    hipError_t e__ = hipGetLastError();                      \
+    if (e__ != hipSuccess) return ::basa::hip_fail(e__, what); \
+  } while (0)
+
+// ---- stage launchers (each validates nothing: the C entry points do) -------------
+
+// Sort keys + segmented sort.  Writes perm[bh][L]; optional keys_out[bh][L].
+size_t sort_workspace_bytes(int BH, int L);
+basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
+                             void* ws, hipStream_t st);
+basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
+
+// Block statistics.  Any of the outputs may be null.
+//   mean/var : [BH][N][d]
+//   feat     : [BH][N][3d] selection features (layout depends on `feat_is_query`):
+//              query side (Qbar/sqrt(d), beta*VarQ/d, beta*Qbar^2/d),
+//              key side   (Kbar, Kbar^2+VarK, VarK)
+basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
+                               float* var, float* feat, int feat_is_query, float beta,
+                               hipStream_t st);
+
+// Block logits: scores[BHq][Nq][Nk] = featQ . featK over `kdim` features.
+basa_status launch_block_scores(const float* featQ, const float* featK, float* scores, int BHq,
+                                int group, int Nq, int Nk, int kdim_used, int feat_stride,
+                                hipStream_t st);
+
+// Row softmax mass + top-kappa selection from a score map.
+basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
+                              uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols,
+                              float* row_mass, hipStream_t st);
+
+// Attention.
+struct AttnArgs {
+  TensorView q, k, v;
+  const int32_t* row_count;   // [BHq][Nq]
+  const int32_t* row_cols;    // [BHq][Nq][cols_stride] or null (= all blocks)
+  int32_t cols_stride;
+  const int32_t* perm_q;      // [BHq][Lq] or null
+  const int32_t* perm_k;      // [BHkv][Lk] or null
+  int B;
+  void* out;                  // [BHq][Lq][d] contiguous, dtype of q
+  float* lse;                 // [BHq][Lq] or null
+  void* ws;
+  size_t ws_bytes;
+};
+size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B);
+basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st);
+basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st);
+
+// ---- device helpers ------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// Load 16 bytes of a row as floats: 8 bf16 or 4 f32 values.
+template <bool kBf16>
+struct Chunk16 {
+  static constexpr int kElems = kBf16 ? 8 : 4;
+  float v[kElems];
+  __device__ __forceinline__ void load(const void* row_base, int chunk) {
+    uint4 raw = reinterpret_cast<const uint4*>(row_base)[chunk];
+    if constexpr (kBf16) {
+      uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
+    } else {
+      v[0] = __uint_as_float(raw.x); v[1] = __uint_as_float(raw.y);
+      v[2] = __uint_as_float(raw.z); v[3] = __uint_as_float(raw.w);
+    }
+  }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) v[i] = 0.f;
+  }
+};
+#endif
+
+}  // namespace basa

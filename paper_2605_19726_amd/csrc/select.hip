@@ -1,0 +1,201 @@
+// Compensated block-score map and per-row top-kappa selection
+// (Eq. 2, Eq. 13-14; Alg. 1 steps 5-11).
+//
+// Scores: with the per-block features written by the pooling kernel the logit l' of a
+// block pair is a dot product, so the N_q x N_k map of a head is a small fp32 GEMM.
+// It runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32); each wave owns a 64x64
+// output tile and streams its 128 feature rows straight from L2 into registers.
+//
+// Selection: one wave per row of the map.  The kappa-th largest logit is found by a
+// 32-step bisection on an order-preserving integer image of the floats (ballot +
+// popcount per step), then the kept columns are compacted in ascending order; among
+// logits equal to the threshold the lower block indices win.  Softmax is monotone, so
+// ranking by l' is ranking by m'; the softmax is evaluated only for the kept mass.
+#include "common.hpp"
+
+namespace basa {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------
+// scores[bhq][gq][gk] = sum_k featQ[bhq][gq][k] * featK[bhq/group][gk][k], k < K
+// MFMA 32x32x2 operand roles: A[i][kk] lives in lane (i, kk), kk = lane/32; the k range
+// is split in halves, lanes 0-31 walk k in [0, K/2), lanes 32-63 walk [K/2, K).
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void block_scores_kernel(const float* __restrict__ featQ,
+                                                           const float* __restrict__ featK,
+                                                           float* __restrict__ scores, int group,
+                                                           int Nq, int Nk, int K, int S) {
+  const int bhq = blockIdx.z;
+  const int bhk = bhq / group;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int li = lane & 31, h = lane >> 5;
+  const int row0 = blockIdx.y * 128 + (wave >> 1) * 64;
+  const int col0 = blockIdx.x * 128 + (wave & 1) * 64;
+  if (row0 >= Nq || col0 >= Nk) return;
+
+  const int half = K >> 1;
+  const float* a0 = featQ + ((int64_t)bhq * Nq + min(row0 + li, Nq - 1)) * S + h * half;
+  const float* a1 = featQ + ((int64_t)bhq * Nq + min(row0 + 32 + li, Nq - 1)) * S + h * half;
+  const float* b0 = featK + ((int64_t)bhk * Nk + min(col0 + li, Nk - 1)) * S + h * half;
+  const float* b1 = featK + ((int64_t)bhk * Nk + min(col0 + 32 + li, Nk - 1)) * S + h * half;
+
+  floatx16 c00 = {0}, c01 = {0}, c10 = {0}, c11 = {0};
+#pragma unroll 2
+  for (int k = 0; k < half; k += 4) {
+    const float4 va0 = *reinterpret_cast<const float4*>(a0 + k);
+    const float4 va1 = *reinterpret_cast<const float4*>(a1 + k);
+    const float4 vb0 = *reinterpret_cast<const float4*>(b0 + k);
+    const float4 vb1 = *reinterpret_cast<const float4*>(b1 + k);
+    const float xa0[4] = {va0.x, va0.y, va0.z, va0.w};
+    const float xa1[4] = {va1.x, va1.y, va1.z, va1.w};
+    const float xb0[4] = {vb0.x, vb0.y, vb0.z, vb0.w};
+    const float xb1[4] = {vb1.x, vb1.y, vb1.z, vb1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      c00 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa0[e], xb0[e], c00, 0, 0, 0);
+      c01 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa0[e], xb1[e], c01, 0, 0, 0);
+      c10 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb0[e], c10, 0, 0, 0);
+      c11 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb1[e], c11, 0, 0, 0);
+    }
+  }
+  // accumulator register r of lane (j, h) holds row 8*(r/4) + 4*h + r%4, column j
+  float* out = scores + (int64_t)bhq * Nq * Nk;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int ri = 8 * (r >> 2) + 4 * h + (r & 3);
+    const int rA = row0 + ri, rB = row0 + 32 + ri;
+    const int cA = col0 + li, cB = col0 + 32 + li;
+    if (rA < Nq) {
+      if (cA < Nk) out[(int64_t)rA * Nk + cA] = c00[r];
+      if (cB < Nk) out[(int64_t)rA * Nk + cB] = c01[r];
+    }
+    if (rB < Nq) {
+      if (cA < Nk) out[(int64_t)rB * Nk + cA] = c10[r];
+      if (cB < Nk) out[(int64_t)rB * Nk + cB] = c11[r];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t ordered_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <int MAXI>
+__global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ scores,
+                                                         int rows_total, int Nk, int kappa,
+                                                         uint32_t* __restrict__ mask_bits,
+                                                         int32_t* __restrict__ row_count,
+                                                         int32_t* __restrict__ row_cols,
+                                                         float* __restrict__ row_mass) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows_total) return;
+  const float* src = scores + (int64_t)row * Nk;
+  float l[MAXI];
+  uint32_t u[MAXI];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    const int idx = i * 64 + lane;
+    if (idx < Nk) {
+      l[i] = src[idx] + 0.0f;          // -0 -> +0 so that equal values have equal images
+      u[i] = ordered_bits(l[i]);
+      mx = fmaxf(mx, l[i]);
+    } else {
+      l[i] = -INFINITY;
+      u[i] = 0u;                        // below the image of every float
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+
+  // T = kappa-th largest image
+  uint32_t T = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = T | (1u << bit);
+    int cnt = 0;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) cnt += __popcll(__ballot(u[i] >= cand));
+    if (cnt >= kappa) T = cand;
+  }
+  int n_gt = 0;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) n_gt += __popcll(__ballot(u[i] > T));
+  const int need_eq = kappa - n_gt;      // >= 1 by construction of T
+
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int words = (Nk + 31) >> 5;
+  int32_t* cols = row_cols ? row_cols + (int64_t)row * kappa : nullptr;
+  uint32_t* mrow = mask_bits ? mask_bits + (int64_t)row * words : nullptr;
+  int emitted = 0, eq_seen = 0;
+  float sum_all = 0.f, sum_sel = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    if (i * 64 < Nk) {
+      const bool eq = (u[i] == T);
+      const uint64_t beq = __ballot(eq);
+      const int eq_rank = eq_seen + __popcll(beq & lt_mask);
+      const bool sel = (u[i] > T) || (eq && eq_rank < need_eq);
+      const uint64_t bsel = __ballot(sel);
+      const float e = (i * 64 + lane < Nk) ? expf(l[i] - mx) : 0.f;
+      sum_all += e;
+      if (sel) {
+        sum_sel += e;
+        if (cols) cols[emitted + __popcll(bsel & lt_mask)] = i * 64 + lane;
+      }
+      if (mrow && lane < 2 && 2 * i + lane < words)
+        mrow[2 * i + lane] = (uint32_t)(bsel >> (32 * lane));
+      emitted += __popcll(bsel);
+      eq_seen += __popcll(beq);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    sum_all += __shfl_xor(sum_all, off);
+    sum_sel += __shfl_xor(sum_sel, off);
+  }
+  if (lane == 0) {
+    if (row_count) row_count[row] = emitted;
+    if (row_mass) row_mass[row] = sum_sel / sum_all;
+  }
+}
+
+}  // namespace
+
+basa_status launch_block_scores(const float* featQ, const float* featK, float* scores, int BHq,
+                                int group, int Nq, int Nk, int kdim_used, int feat_stride,
+                                hipStream_t st) {
+  if (BHq == 0 || Nq == 0 || Nk == 0) return BASA_OK;
+  dim3 grid(ceil_div(Nk, 128), ceil_div(Nq, 128), BHq);
+  hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), 0, st, featQ, featK, scores, group, Nq,
+                     Nk, kdim_used, feat_stride);
+  BASA_HIP_CHECK_LAUNCH("block_scores_kernel");
+  return BASA_OK;
+}
+
+basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
+                              uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols,
+                              float* row_mass, hipStream_t st) {
+  if (rows_total == 0) return BASA_OK;
+  dim3 grid(ceil_div(rows_total, 4));
+#define BASA_SEL(M)                                                                            \
+  hipLaunchKernelGGL((row_select_kernel<M>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
+                     kappa, mask_bits, row_count, row_cols, row_mass)
+  if (Nk <= 256) BASA_SEL(4);
+  else if (Nk <= 1024) BASA_SEL(16);
+  else if (Nk <= 2048) BASA_SEL(32);
+  else if (Nk <= 4096) BASA_SEL(64);
+  else {
+    set_error("row selection supports at most 4096 key blocks per row (got %d)", Nk);
+    return BASA_ERR_UNSUPPORTED;
+  }
+#undef BASA_SEL
+  BASA_HIP_CHECK_LAUNCH("row_select_kernel");
+  return BASA_OK;
+}
+
+}  // namespace basa

@@ -1,0 +1,238 @@
+// Norm ranking (Sec. 3.3, Eq. 9-10; Alg. 1 steps 1-2): sort keys and a segmented
+// merge sort of (key, index) pairs, one segment per (head, window).
+//
+// Key of a token = fp32 rounding of the fp64 sum of squares of its d values.  Each
+// pair is packed into one 64-bit word, key bits high and token index low: keys are
+// non-negative floats, whose bit patterns order like the values, so an unsigned
+// compare of the packed words orders by key and breaks ties by lower index, which
+// also makes every word of a segment distinct (no stability concerns in the sort).
+#include "common.hpp"
+
+namespace basa {
+namespace {
+
+constexpr int kSortThreads = 256;
+constexpr int kTile = 4096;          // elements sorted per workgroup in LDS (32 KB)
+constexpr int kMergeItems = 8;       // outputs per thread in a merge pass
+constexpr int kMergeChunk = kSortThreads * kMergeItems;   // 2048 outputs per workgroup
+
+// ---------------------------------------------------------------------------------
+// Keys.  A row of d elements is 16-byte chunks spread over LPR adjacent lanes.
+// ---------------------------------------------------------------------------------
+template <bool kBf16, int kD>
+__global__ __launch_bounds__(256) void norm_keys_kernel(TensorView x, uint64_t* __restrict__ packed,
+                                                        float* __restrict__ keys_out) {
+  constexpr int kElem = kBf16 ? 2 : 4;
+  constexpr int LPR = kD * kElem / 16;          // lanes per row: 8, 16 or 32
+  constexpr int kRowsPerIter = 256 / LPR;
+  constexpr int kIters = 8;
+  const int bh = blockIdx.y;
+  const int L = x.L;
+  const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * kElem;
+  const int sub = threadIdx.x % LPR;
+  const int rig = threadIdx.x / LPR;
+  const int row0 = blockIdx.x * (kRowsPerIter * kIters) + rig;
+
+  Chunk16<kBf16> c[kIters];
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    int row = row0 + it * kRowsPerIter;
+    if (row < L) c[it].load(base + (int64_t)row * x.stride_l * kElem, sub);
+    else c[it].zero();
+  }
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    double acc = 0.0;
+#pragma unroll
+    for (int e = 0; e < Chunk16<kBf16>::kElems; ++e) {
+      double v = (double)c[it].v[e];
+      acc += v * v;
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, LPR);
+    int row = row0 + it * kRowsPerIter;
+    if (sub == 0 && row < L) {
+      float key = (float)acc;
+      packed[(int64_t)bh * L + row] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)row;
+      if (keys_out) keys_out[(int64_t)bh * L + row] = key;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Tile sort: bitonic network over kTile packed words in LDS.
+// Segment s of a head covers [s*W, min((s+1)*W, L)); tiles never straddle segments.
+// ---------------------------------------------------------------------------------
+struct SegGeom {
+  int L, W, segs, tiles_per_seg;
+};
+
+__global__ __launch_bounds__(kSortThreads) void tile_sort_kernel(const uint64_t* __restrict__ in,
+                                                                 uint64_t* __restrict__ out,
+                                                                 int32_t* __restrict__ perm_out,
+                                                                 SegGeom g) {
+  __shared__ uint64_t buf[kTile];
+  const int bh = blockIdx.y;
+  const int seg = blockIdx.x / g.tiles_per_seg;
+  const int tile = blockIdx.x - seg * g.tiles_per_seg;
+  const int seg_end = min((seg + 1) * g.W, g.L);
+  const int start = seg * g.W + tile * kTile;
+  if (start >= seg_end) return;
+  const int n = min(kTile, seg_end - start);
+  const int64_t hb = (int64_t)bh * g.L;
+
+  for (int i = threadIdx.x; i < kTile; i += kSortThreads)
+    buf[i] = (i < n) ? in[hb + start + i] : ~0ull;
+  __syncthreads();
+
+  for (int k = 2; k <= kTile; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int p = threadIdx.x; p < kTile / 2; p += kSortThreads) {
+        int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));
+        int l = i | j;
+        uint64_t a = buf[i], b = buf[l];
+        bool up = (i & k) == 0;
+        if ((a > b) == up) { buf[i] = b; buf[l] = a; }
+      }
+      __syncthreads();
+    }
+  }
+  if (perm_out) {
+    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[hb + start + i] = (int32_t)(uint32_t)buf[i];
+  } else {
+    for (int i = threadIdx.x; i < n; i += kSortThreads) out[hb + start + i] = buf[i];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Merge pass: sorted runs of `run` elements are merged pairwise inside each segment.
+// One workgroup produces kMergeChunk consecutive outputs of one pair, located with a
+// merge-path search on the pair's two runs.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ int merge_path(const uint64_t* A, int na, const uint64_t* Bv, int nb, int diag) {
+  int lo = max(0, diag - nb), hi = min(diag, na);
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (A[mid] < Bv[diag - 1 - mid]) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t* __restrict__ in,
+                                                                  uint64_t* __restrict__ out,
+                                                                  int32_t* __restrict__ perm_out,
+                                                                  SegGeom g, int run,
+                                                                  int chunks_per_pair, int pairs_per_seg) {
+  __shared__ uint64_t buf[kMergeChunk];
+  __shared__ int split[2];
+  const int bh = blockIdx.y;
+  int id = blockIdx.x;
+  const int chunk = id % chunks_per_pair; id /= chunks_per_pair;
+  const int pair = id % pairs_per_seg;
+  const int seg = id / pairs_per_seg;
+  const int seg_end = min((seg + 1) * g.W, g.L);
+  const int a0 = seg * g.W + pair * 2 * run;
+  if (a0 >= seg_end) return;
+  const int na = min(run, seg_end - a0);
+  const int b0 = a0 + na;
+  const int nb = min(run, seg_end - b0);
+  const int total = na + nb;
+  const int diag0 = chunk * kMergeChunk;
+  if (diag0 >= total) return;
+  const int diag1 = min(diag0 + kMergeChunk, total);
+  const int64_t hb = (int64_t)bh * g.L;
+  const uint64_t* A = in + hb + a0;
+  const uint64_t* Bv = in + hb + b0;
+
+  if (threadIdx.x < 2) split[threadIdx.x] = merge_path(A, na, Bv, nb, threadIdx.x == 0 ? diag0 : diag1);
+  __syncthreads();
+  const int as = split[0], ae = split[1];
+  const int bs = diag0 - as, be = diag1 - ae;
+  const int ca = ae - as, cb = be - bs;          // ca + cb == diag1 - diag0
+  for (int i = threadIdx.x; i < ca; i += kSortThreads) buf[i] = A[as + i];
+  for (int i = threadIdx.x; i < cb; i += kSortThreads) buf[ca + i] = Bv[bs + i];
+  __syncthreads();
+
+  const int n = ca + cb;
+  const int d0 = min(threadIdx.x * kMergeItems, n);
+  const int d1 = min(d0 + kMergeItems, n);
+  int ia = merge_path(buf, ca, buf + ca, cb, d0);
+  int ib = d0 - ia;
+  const int64_t obase = hb + a0 + diag0;
+  for (int o = d0; o < d1; ++o) {
+    uint64_t va = ia < ca ? buf[ia] : ~0ull;
+    uint64_t vb = ib < cb ? buf[ca + ib] : ~0ull;
+    uint64_t v;
+    if (va < vb) { v = va; ++ia; } else { v = vb; ++ib; }
+    if (perm_out) perm_out[obase + o] = (int32_t)(uint32_t)v;
+    else out[obase + o] = v;
+  }
+}
+
+__global__ void iota_kernel(int32_t* perm, int L, int64_t total) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) perm[i] = (int32_t)(i % L);
+}
+
+}  // namespace
+
+size_t sort_workspace_bytes(int BH, int L) {
+  return 2 * align_up((size_t)BH * L * sizeof(uint64_t), 256);
+}
+
+basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st) {
+  int64_t total = (int64_t)BH * L;
+  if (total == 0) return BASA_OK;
+  hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, perm, L, total);
+  BASA_HIP_CHECK_LAUNCH("iota_kernel");
+  return BASA_OK;
+}
+
+basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
+                             void* ws, hipStream_t st) {
+  const int BH = x.batch * x.heads, L = x.L;
+  if (BH == 0 || L == 0) return BASA_OK;
+  uint64_t* buf0 = reinterpret_cast<uint64_t*>(ws);
+  uint64_t* buf1 = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(ws) +
+                                               align_up((size_t)BH * L * sizeof(uint64_t), 256));
+  const bool bf16 = x.dtype == BASA_BF16;
+  const int elem = bf16 ? 2 : 4;
+  const int lpr = x.d * elem / 16;
+  const int rows_per_wg = (256 / lpr) * 8;
+  dim3 kgrid(ceil_div(L, rows_per_wg), BH);
+#define BASA_KEYS(BF, D) \
+  hipLaunchKernelGGL((norm_keys_kernel<BF, D>), kgrid, dim3(256), 0, st, x, buf0, keys_out)
+  if (bf16 && x.d == 128) BASA_KEYS(true, 128);
+  else if (bf16 && x.d == 64) BASA_KEYS(true, 64);
+  else if (!bf16 && x.d == 128) BASA_KEYS(false, 128);
+  else BASA_KEYS(false, 64);
+#undef BASA_KEYS
+  BASA_HIP_CHECK_LAUNCH("norm_keys_kernel");
+
+  SegGeom g;
+  g.L = L;
+  g.W = (window > 0 && window < L) ? window : L;
+  g.segs = ceil_div(L, g.W);
+  g.tiles_per_seg = ceil_div(g.W, kTile);
+  const bool single = g.tiles_per_seg == 1;
+  hipLaunchKernelGGL(tile_sort_kernel, dim3(g.segs * g.tiles_per_seg, BH), dim3(kSortThreads), 0, st,
+                     buf0, buf1, single ? perm : nullptr, g);
+  BASA_HIP_CHECK_LAUNCH("tile_sort_kernel");
+  if (single) return BASA_OK;
+
+  uint64_t* src = buf1;
+  uint64_t* dst = buf0;
+  for (int run = kTile; run < g.W; run *= 2) {
+    const bool last = run * 2 >= g.W;
+    const int pairs_per_seg = ceil_div(ceil_div(g.W, run), 2);
+    const int chunks_per_pair = ceil_div(2 * run, kMergeChunk);
+    hipLaunchKernelGGL(merge_pass_kernel, dim3(g.segs * pairs_per_seg * chunks_per_pair, BH),
+                       dim3(kSortThreads), 0, st, src, dst, last ? perm : nullptr, g, run,
+                       chunks_per_pair, pairs_per_seg);
+    BASA_HIP_CHECK_LAUNCH("merge_pass_kernel");
+    uint64_t* t = src; src = dst; dst = t;
+  }
+  return BASA_OK;
+}
+
+}  // namespace basa

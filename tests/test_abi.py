@@ -1,0 +1,109 @@
+"""CPU-only checks of the C-ABI boundary: the built library loads, exports every symbol the
+header declares, and its host-side validation rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import basa_oracle as o
+from paper_2605_19726_amd import binding as bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(bd.lib_path()):
+        from paper_2605_19726_amd import build
+        build.build(verbose=False)
+    return bd.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "basa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(basa_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in basa.h but not exported"
+    assert sorted(bd.EXPORTS) == names
+
+
+def test_version_and_status_strings(lib):
+    assert "gfx950" in bd.basa_version()
+    assert lib.basa_status_string(0) == b"BASA_OK"
+    assert lib.basa_status_string(3) == b"BASA_ERR_WORKSPACE"
+
+
+@pytest.mark.parametrize("n,s", [(16, 0.5), (591, 0.5), (591, 0.75), (1024, 0.9), (1024, 0.0),
+                                 (590, 0.6), (1000, 0.7), (3, 0.99), (512, 0.3), (77, 0.123)])
+def test_kappa_matches_oracle(lib, n, s):
+    assert bd.basa_kappa(n, s) == o.kappa_from_sparsity(n, s)
+
+
+def test_kappa_rejects_bad_input(lib):
+    assert bd.basa_kappa(10, 1.0) == -1
+    assert bd.basa_kappa(10, -0.5) == -1
+    assert bd.basa_kappa(0, 0.5) == -1
+
+
+def fake_tensor(ptr=0x1000, dtype=bd.BF16, batch=1, heads=2, L=256, d=128):
+    return bd.BasaTensor(ptr, dtype, batch, heads, L, d, heads * L * d, L * d, d)
+
+
+def status_of(lib, fn, *args):
+    st = fn(*args)
+    return lib.basa_status_string(st).decode(), lib.basa_last_error().decode()
+
+
+def test_select_argument_validation(lib):
+    q, k = fake_tensor(), fake_tensor()
+    p = bd.params(128, 0.5)
+    V = C.c_void_p
+    dummy = V(0x2000)
+    call = lambda q_, k_, p_, rc=dummy, ws=dummy, wsb=1 << 40: status_of(
+        lib, lib.basa_select, C.byref(q_), C.byref(k_), C.byref(p_), None, rc, dummy, dummy, dummy,
+        None, None, ws, wsb, None)
+    assert call(fake_tensor(ptr=0), k, p)[0] == "BASA_ERR_INVALID_ARG"
+    assert call(fake_tensor(d=96), k, p)[0] == "BASA_ERR_UNSUPPORTED"
+    assert call(fake_tensor(heads=3), k, p)[0] == "BASA_ERR_INVALID_ARG"        # 3 % 2 != 0
+    assert call(q, fake_tensor(dtype=bd.F32), p)[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(100, 0.5))[0] == "BASA_ERR_UNSUPPORTED"
+    assert call(q, k, bd.params(128, 1.0))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, window=100))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, sort=7))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, p, rc=None)[0] == "BASA_ERR_INVALID_ARG"
+    name, why = call(q, k, p, wsb=16)
+    assert name == "BASA_ERR_WORKSPACE" and "need" in why
+    assert call(q, k, p, ws=None)[0] == "BASA_ERR_WORKSPACE"
+    assert call(fake_tensor(ptr=0x1004), k, p)[0] == "BASA_ERR_INVALID_ARG"     # misaligned
+
+
+def test_attention_argument_validation(lib):
+    q, k, v = fake_tensor(), fake_tensor(), fake_tensor()
+    p = bd.params(128)
+    dummy = C.c_void_p(0x2000)
+    call = lambda q_, k_, v_, out=dummy, wsb=16: status_of(
+        lib, lib.basa_sparse_attn, C.byref(q_), C.byref(k_), C.byref(v_), dummy, dummy, 4, None, None,
+        C.byref(p), out, None, dummy, wsb, None)
+    assert call(q, k, fake_tensor(L=128))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, v, out=None)[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, v)[0] == "BASA_ERR_WORKSPACE"
+    st = lib.basa_dense_attn(C.byref(q), C.byref(k), C.byref(v), C.byref(p), dummy, None, dummy, 16, None)
+    assert lib.basa_status_string(st) == b"BASA_ERR_WORKSPACE"
+
+
+def test_workspace_sizes(lib):
+    q, k = fake_tensor(heads=4, L=1000), fake_tensor(heads=2, L=1000)
+    p = bd.params(128, 0.5)
+    sel = lib.basa_select_workspace_size(C.byref(q), C.byref(k), C.byref(p))
+    att = lib.basa_attn_workspace_size(C.byref(q), C.byref(k), C.byref(p))
+    # attention workspace: sorted Q, K and transposed V padded to whole blocks
+    assert att >= (4 + 2 + 2) * 1024 * 128 * 2
+    assert sel >= 2 * 4 * 1000 * 8
+    assert lib.basa_select_workspace_size(C.byref(fake_tensor(d=96)), C.byref(k), C.byref(p)) == 0

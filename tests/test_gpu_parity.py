@@ -1,0 +1,240 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the numpy
+oracle on the same seeded inputs.  Sizes span several tiles and ragged tails; the
+full-size configurations are checked on sampled (head, query block) units."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import basa_oracle as o
+from paper_2605_19726_amd import binding as bd
+from paper_2605_19726_amd import synth
+from parity_util import (check_output, mask_report, np64, oracle_select, unpack_mask)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+C = synth.CONFIGS
+
+# scaled versions of the five workloads: same generators, sizes the oracle finishes in seconds
+SMALL = [
+    C[0],
+    C[1].scaled("lowrank_b64", heads_q=2, heads_kv=2, L=4096 + 64 * 5, salient_frac=0.05),
+    C[4].scaled("lowrank_b128", heads_q=2, heads_kv=2, L=8192 + 128 * 3, salient_frac=0.05),
+    C[2].scaled("multimodal_gqa", heads_q=4, heads_kv=2, L=4096, image_side=32),
+    C[3].scaled("video_ragged", heads_q=2, heads_kv=2, L=5 * 20 * 21, video_thw=(5, 20, 21)),
+    C[0].scaled("tiny_f32_d128_ragged", L=1000, d=128, block=128, heads_q=2, heads_kv=1),
+    C[0].scaled("tiny_bf16_d64", dtype="bf16", L=900),
+]
+
+
+def gen(w):
+    return synth.make_qkv(w, device=DEV)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    bd.load()
+
+
+# ------------------------------------------------------------------ norm sort
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_norm_sort_matches_oracle(w):
+    Q, K, V = gen(w)
+    for x in (Q, K):
+        perm, keys = bd.basa_norm_sort(x, w.block, return_keys=True)
+        torch.cuda.synchronize()
+        for h in range(x.shape[1]):
+            xn = np64(x[0, h])
+            assert np.array_equal(keys[0, h].cpu().numpy(), o.token_sort_keys(xn)), "fp32 sort keys differ"
+            assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), o.norm_sort(xn))
+
+
+def test_norm_sort_windowed_and_ties():
+    w = C[1].scaled("win", heads_q=2, heads_kv=2, L=10000 + 64)
+    Q, _, _ = gen(w)
+    Q[0, 0, 5000:5064] = Q[0, 0, 100:164]            # exact ties across distant positions
+    for window in (0, 64, 1024, 4096, 8192):
+        perm = bd.basa_norm_sort(Q, w.block, window=window)
+        for h in range(2):
+            want = o.norm_sort(np64(Q[0, h]), window)
+            assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), want), f"window={window}"
+
+
+def test_norm_sort_strided_input():
+    # heads interleaved in memory: [1, L, H, d] viewed as [1, H, L, d]
+    w = C[1].scaled("strided", heads_q=3, heads_kv=3, L=5000)
+    Q, _, _ = gen(w)
+    Qs = Q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert not Qs.is_contiguous()
+    perm = bd.basa_norm_sort(Qs, w.block)
+    ref = bd.basa_norm_sort(Q, w.block)
+    assert torch.equal(perm, ref)
+
+
+# ------------------------------------------------------------------ block statistics
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_downsample_matches_oracle(w):
+    Q, K, V = gen(w)
+    for x in (Q, K):
+        perm = bd.basa_norm_sort(x, w.block)
+        for pm in (None, perm):
+            mean, var = bd.basa_downsample(x, w.block, pm)
+            for h in range(x.shape[1]):
+                xn = np64(x[0, h])
+                if pm is not None:
+                    xn = xn[perm[0, h].cpu().numpy()]
+                m_ref, v_ref = o.block_stats(xn, w.block)
+                np.testing.assert_allclose(mean[0, h].cpu().numpy(), m_ref, rtol=1e-5, atol=1e-6)
+                np.testing.assert_allclose(var[0, h].cpu().numpy(), v_ref, rtol=1e-5, atol=1e-6)
+
+
+# ------------------------------------------------------------------ selection
+def _check_selection(w, Q, K, s, beta, sort, window=0):
+    sel = bd.basa_select(Q, K, w.block, s, beta, sort, window, want_scores=True)
+    torch.cuda.synchronize()
+    n_k = sel.n_k
+    gpu_mask = unpack_mask(sel.mask_bits, n_k)
+    total_dc = 0
+    for h in range(Q.shape[1]):
+        ref = oracle_select(Q, K, h, w.block, s, beta, sort, window)
+        hk = h // (Q.shape[1] // K.shape[1])
+        assert sel.kappa == ref["kappa"]
+        assert np.array_equal(sel.perm_q[0, h].cpu().numpy(), ref["perm_q"]), "perm_q"
+        assert np.array_equal(sel.perm_k[0, hk].cpu().numpy(), ref["perm_k"]), "perm_k"
+        sc = sel.scores[0, h].cpu().numpy().astype(np.float64)
+        scale = max(1.0, np.abs(ref["logits"]).max())
+        assert np.abs(sc - ref["logits"]).max() <= 1e-5 * scale, \
+            f"logits off by {np.abs(sc - ref['logits']).max():.3e}"
+        bad, dc = mask_report(gpu_mask[0, h], ref)
+        total_dc += dc - ref["mask"].shape[0]          # every row's threshold block is in the band
+        assert bad == 0, f"{bad} mask mismatches outside the don't-care band (head {h})"
+        assert (sel.row_count[0, h].cpu().numpy() == ref["kappa"]).all()
+        cols = sel.row_cols[0, h].cpu().numpy()
+        assert (np.diff(cols, axis=1) > 0).all(), "columns not ascending"
+        rebuilt = np.zeros_like(gpu_mask[0, h])
+        np.put_along_axis(rebuilt, cols.astype(np.int64), True, axis=1)
+        assert np.array_equal(rebuilt, gpu_mask[0, h]), "bitmap and column list disagree"
+        if np.array_equal(gpu_mask[0, h], ref["mask"]):
+            np.testing.assert_allclose(sel.row_mass[0, h].cpu().numpy(), ref["mass"], rtol=1e-4, atol=1e-6)
+    return total_dc
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_select_matches_oracle(w):
+    Q, K, _ = gen(w)
+    for s in w.sparsities:
+        _check_selection(w, Q, K, s, 1.0, o.SORT_QK)
+
+
+@pytest.mark.parametrize("sort", [o.SORT_NONE, o.SORT_Q, o.SORT_K, o.SORT_QK])
+@pytest.mark.parametrize("beta", [0.0, 1.0, 0.5])
+def test_select_every_sort_mode_and_beta(sort, beta):
+    w = C[0]
+    Q, K, _ = gen(w)
+    _check_selection(w, Q, K, 0.5, beta, sort)
+    w2 = SMALL[1]
+    Q, K, _ = gen(w2)
+    _check_selection(w2, Q, K, 0.75, beta, sort)
+
+
+def test_select_sparsity_extremes_and_window():
+    w = SMALL[2]
+    Q, K, _ = gen(w)
+    for s in (0.0, 0.9, 0.999):
+        _check_selection(w, Q, K, s, 1.0, o.SORT_QK)
+    _check_selection(w, Q, K, 0.5, 1.0, o.SORT_QK, window=2048)
+
+
+def test_select_cross_lengths():
+    w = SMALL[1]
+    Q, K, _ = gen(w)
+    Qs = Q[:, :, :1000].contiguous()
+    _check_selection(w, Qs, K, 0.5, 1.0, o.SORT_QK)
+
+
+# ------------------------------------------------------------------ attention
+def _oracle_attention(Q, K, V, h, sel, block):
+    hk = h // (Q.shape[1] // K.shape[1])
+    return o.sparse_attention(np64(Q[0, h]), np64(K[0, hk]), np64(V[0, hk]), sel["perm_q"],
+                              sel["perm_k"], sel["cols"], block, return_lse=True)
+
+
+def _attn_with_oracle_selection(w, Q, K, V, s, beta=1.0, sort=o.SORT_QK):
+    """GPU attention fed with the ORACLE's permutation and block lists."""
+    H = Q.shape[1]
+    refs = [oracle_select(Q, K, h, w.block, s, beta, sort) for h in range(H)]
+    group = H // K.shape[1]
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a).astype(np.int32)).to(DEV)
+    perm_q = i32(np.stack([r["perm_q"] for r in refs]))[None]
+    perm_k = i32(np.stack([refs[hk * group]["perm_k"] for hk in range(K.shape[1])]))[None]
+    cols = i32(np.stack([r["cols"] for r in refs]))[None]
+    count = torch.full(cols.shape[:3], refs[0]["kappa"], dtype=torch.int32, device=DEV)
+    out, lse = bd.basa_sparse_attn(Q, K, V, count, cols, w.block, perm_q, perm_k, want_lse=True)
+    torch.cuda.synchronize()
+    for h in range(H):
+        O_ref, lse_ref = _oracle_attention(Q, K, V, h, refs[h], w.block)
+        check_output(np64(out[0, h]), O_ref, w.dtype == "bf16", f"{w.name} head {h} s={s}")
+        np.testing.assert_allclose(lse[0, h].cpu().numpy(), lse_ref, rtol=0, atol=2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_sparse_attention_matches_oracle(w):
+    Q, K, V = gen(w)
+    for s in w.sparsities:
+        _attn_with_oracle_selection(w, Q, K, V, s)
+
+
+@pytest.mark.parametrize("sort", [o.SORT_NONE, o.SORT_Q, o.SORT_K, o.SORT_QK])
+def test_sparse_attention_every_sort_mode(sort):
+    for w in (C[0], SMALL[4]):
+        Q, K, V = gen(w)
+        _attn_with_oracle_selection(w, Q, K, V, 0.5, 1.0, sort)
+
+
+@pytest.mark.parametrize("w", [SMALL[0], SMALL[2], SMALL[3], SMALL[4], SMALL[6]], ids=lambda w: w.name)
+def test_zero_sparsity_and_dense_entry_equal_dense_attention(w):
+    Q, K, V = gen(w)
+    sel = bd.basa_select(Q, K, w.block, 0.0)
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+    dense, lse = bd.basa_dense_attn(Q, K, V, w.block, want_lse=True)
+    torch.cuda.synchronize()
+    group = Q.shape[1] // K.shape[1]
+    for h in range(Q.shape[1]):
+        ref, lse_ref = o.dense_attention(np64(Q[0, h]), np64(K[0, h // group]), np64(V[0, h // group]), True)
+        check_output(np64(out[0, h]), ref, w.dtype == "bf16", "s=0")
+        check_output(np64(dense[0, h]), ref, w.dtype == "bf16", "dense entry")
+        np.testing.assert_allclose(lse[0, h].cpu().numpy(), lse_ref, atol=2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+def test_end_to_end_gpu_selection_then_attention():
+    for w in (SMALL[1], SMALL[4]):
+        Q, K, V = gen(w)
+        s = 0.5
+        sel = bd.basa_select(Q, K, w.block, s)
+        out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+        torch.cuda.synchronize()
+        gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
+        for h in range(Q.shape[1]):
+            ref = oracle_select(Q, K, h, w.block, s, 1.0, o.SORT_QK)
+            if not np.array_equal(gpu_mask[0, h], ref["mask"]):
+                assert mask_report(gpu_mask[0, h], ref)[0] == 0
+                continue                          # differs only inside the don't-care band
+            O_ref, _ = _oracle_attention(Q, K, V, h, ref, w.block)
+            check_output(np64(out[0, h]), O_ref, True, f"e2e {w.name} head {h}")
+
+
+def test_cross_attention_lengths():
+    w = SMALL[2]
+    Q, K, V = gen(w)
+    Qs = Q[:, :, :1000].contiguous()              # L_q != L_k, ragged query tail
+    _attn_with_oracle_selection(w, Qs, K, V, 0.5)
+
+
+def test_results_are_deterministic():
+    w = SMALL[2]
+    Q, K, V = gen(w)
+    a = bd.basa_select(Q, K, w.block, 0.5)
+    b = bd.basa_select(Q, K, w.block, 0.5)
+    assert torch.equal(a.mask_bits, b.mask_bits) and torch.equal(a.row_cols, b.row_cols)
+    o1 = bd.basa_sparse_attn(Q, K, V, a.row_count, a.row_cols, w.block, a.perm_q, a.perm_k)
+    o2 = bd.basa_sparse_attn(Q, K, V, a.row_count, a.row_cols, w.block, a.perm_q, a.perm_k)
+    assert torch.equal(o1, o2)
