@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the BA-Att hot path on one MI355X.
+
+A step is one pass of the whole path on one batch of synthetic input already resident
+in HBM: basa_select (norm sort, block pooling, compensated score map, top-kappa) followed
+by basa_sparse_attn (gather + bf16-MFMA block-sparse attention).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--sparsity 0.5]
+                    [--sweep] [--no-cpu-baseline]
+
+--sweep additionally times every configuration / sparsity of the benchmark and writes the
+table to gpurun_out/bench_sweep.json (the printed line stays the headline workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2605_19726_amd import binding as bd   # noqa: E402
+from paper_2605_19726_amd import synth           # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def executed_flops(w, kappa):
+    """4 * n_q * n_k * d per executed block pair, ragged tails counted at their true size."""
+    B, L, d = w.block, w.L, w.d
+    n = w.n_blocks
+    # every row keeps kappa key blocks; the ragged last key block (if kept) is shorter, which
+    # at most changes the total by one block per row: count whole blocks except for the tail
+    # of the query side, which is exact.
+    return 4.0 * w.heads_q * L * (kappa * B if kappa < n else L) * d
+
+
+def selection_bytes(w):
+    """Algorithmic HBM bytes of the selection stage: Q and K are read twice (norm pass, then the
+    gather + pooling pass, which depends on the finished sort), plus the sort's key/index words
+    (one 8-byte word written by the key pass, then read and written by the tile sort and by
+    every merge pass), the block features, the score map and the block lists."""
+    e = 2 if w.dtype == "bf16" else 4
+    rows = (w.heads_q + w.heads_kv) * w.L
+    n = w.n_blocks
+    qk = rows * w.d * e
+    passes = 1 + max(0, int(np.ceil(np.log2(max(w.L, 1) / 4096.0))))
+    sort = rows * 8 * (1 + 2 * passes)
+    feats = (w.heads_q + w.heads_kv) * n * 3 * w.d * 4 * 2
+    scores = w.heads_q * n * n * 4 * 2
+    return dict(two_pass=2 * qk, compulsory=qk, sort=sort, small=feats + scores,
+                total=2 * qk + sort + feats + scores)
+
+
+class Pipeline:
+    """Preallocated buffers for repeated select + attention calls on one workload."""
+
+    def __init__(self, w, sparsity, Q, K, V, beta=1.0, sort=bd.SORT_QK):
+        self.w, self.s, self.beta, self.sort = w, sparsity, beta, sort
+        self.Q, self.K, self.V = Q, K, V
+        dev = Q.device
+        p = bd.params(w.block, sparsity, beta, sort)
+        self.ws_sel = torch.empty(bd.select_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
+        self.ws_att = torch.empty(bd.attn_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
+        self.sel = bd.basa_select(Q, K, w.block, sparsity, beta, sort, ws=self.ws_sel)
+        self.out = torch.empty_like(Q)
+
+    def select(self):
+        bd.basa_select(self.Q, self.K, self.w.block, self.s, self.beta, self.sort, ws=self.ws_sel,
+                       out=self.sel)
+
+    def attn(self):
+        s = self.sel
+        bd.basa_sparse_attn(self.Q, self.K, self.V, s.row_count, s.row_cols, self.w.block, s.perm_q,
+                            s.perm_k, ws=self.ws_att, out=self.out)
+
+    def dense(self):
+        bd.basa_dense_attn(self.Q, self.K, self.V, self.w.block, ws=self.ws_att, out=self.out)
+
+    def step(self):
+        self.select()
+        self.attn()
+
+
+def timed(fn, reps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps
+
+
+def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK):
+    pipe = Pipeline(w, sparsity, Q, K, V, beta, sort)
+    for _ in range(warmup):
+        pipe.step()
+    torch.cuda.synchronize()
+    bd.basa_profile_enable(True)
+    bd.basa_profile_read()
+    t_step = timed(pipe.step, steps)
+    prof = bd.basa_profile_read()
+    bd.basa_profile_enable(False)
+    t_sel = timed(pipe.select, max(2, steps))
+    t_att = timed(pipe.attn, max(2, steps))
+    t_dense = None
+    if dense_reps > 0:
+        pipe.dense()
+        t_dense = timed(pipe.dense, dense_reps)
+    kern_ms = {k: (ms / cnt if cnt else 0.0) for k, (ms, cnt) in prof.items()}
+    kern_per_step = {k: ms / steps for k, (ms, cnt) in prof.items() if cnt}
+    kappa = pipe.sel.kappa
+    fl_exec = executed_flops(w, kappa)
+    fl_dense = 4.0 * w.heads_q * float(w.L) ** 2 * w.d
+    attn_kernel_s = kern_ms.get("attn_mfma_kernel", 0.0) * 1e-3
+    sb = selection_bytes(w)
+    res = dict(
+        workload=w.name, sparsity=sparsity, kappa=kappa, n_blocks=w.n_blocks,
+        t_e2e_ms=t_step * 1e3, t_select_ms=t_sel * 1e3, t_attn_ms=t_att * 1e3,
+        t_dense_ms=None if t_dense is None else t_dense * 1e3,
+        speedup_vs_dense=None if t_dense is None else t_dense / t_step,
+        effective_tflops=fl_dense / t_step / 1e12,
+        executed_tflops_attn_call=fl_exec / t_att / 1e12,
+        executed_tflops_attn_kernel=(fl_exec / attn_kernel_s / 1e12) if attn_kernel_s else None,
+        dense_tflops=None if t_dense is None else fl_dense / t_dense / 1e12,
+        selection_gbs_two_pass=sb["two_pass"] / t_sel / 1e9,
+        selection_gbs_total=sb["total"] / t_sel / 1e9,
+        kernel_avg_ms=kern_ms, kernel_ms_per_step=kern_per_step,
+        executed_flops=fl_exec, selection_bytes=sb,
+    )
+    return res, pipe
+
+
+def cpu_baseline(w, sparsity, Q, K, V, pipe, n_units=24):
+    """Time the numpy oracle on a bounded sample and extrapolate to the whole workload; also
+    compare the GPU output rows of the sampled units with the oracle's."""
+    from oracle import basa_oracle as o
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    group = w.heads_q // w.heads_kv
+    h = 0
+    pipe.step()                 # the dense baseline shares the output buffer: recompute the sparse result
+    torch.cuda.synchronize()
+    q = Q[0, h].to("cpu").to(torch.float64).numpy()
+    k = K[0, h // group].to("cpu").to(torch.float64).numpy()
+    v = V[0, h // group].to("cpu").to(torch.float64).numpy()
+    t0 = time.perf_counter()
+    sel = o.select(q, k, w.block, sparsity, pipe.beta, pipe.sort)
+    t_sel_head = time.perf_counter() - t0
+    n_q = sel["mask"].shape[0]
+    rng = np.random.default_rng(7)
+    units = sorted(set([0, n_q - 1] + rng.choice(n_q, size=min(n_units, n_q), replace=False).tolist()))
+    out_gpu = pipe.out[0, h].to("cpu").to(torch.float64).numpy()
+    gpu_mask_same = bool(np.array_equal(pipe.sel.row_cols[0, h].cpu().numpy(), sel["cols"]))
+    t0 = time.perf_counter()
+    max_err = 0.0
+    for g in units:
+        rows, O, _ = o.sparse_attention_block(q, k, v, sel["perm_q"], sel["perm_k"], g, sel["cols"][g], w.block)
+        if gpu_mask_same:
+            max_err = max(max_err, float(np.abs(out_gpu[rows] - O).max()))
+    t_unit = (time.perf_counter() - t0) / len(units)
+    t_total = t_sel_head * w.heads_q + t_unit * w.heads_q * n_q
+    fl_dense = 4.0 * w.heads_q * float(w.L) ** 2 * w.d
+    return dict(value=fl_dense / t_total / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle",
+                sample=f"numpy fp64 oracle: selection of 1 of {w.heads_q} heads ({t_sel_head:.2f} s) + "
+                       f"attention of {len(units)} of {w.heads_q * n_q} (head, query-block) units "
+                       f"({t_unit:.3f} s each), extrapolated linearly to the whole workload "
+                       f"({t_total:.0f} s)",
+                est_total_s=t_total,
+                gpu_vs_oracle_sample_maxabs=max_err if gpu_mask_same else None)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--sparsity", type=float, default=0.5)
+    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    bd.load()
+    dev = "cuda:0"
+    w = synth.CONFIGS[args.config]
+    Q, K, V = synth.make_qkv(w, device=dev)
+    res, pipe = measure(w, args.sparsity, Q, K, V, args.steps, args.warmup,
+                        dense_reps=0 if args.no_dense else 1)
+    attn_ms = res["kernel_avg_ms"].get("attn_mfma_kernel", 0.0) or res["kernel_avg_ms"].get("attn_simple_kernel", 0.0)
+    achieved = res["executed_flops"] / (attn_ms * 1e-3) / 1e12 if attn_ms else None
+    line = {
+        "metric": "BA-Att effective (dense-equivalent) TFLOP/s at 50% sparsity, L=128K; latency in ms_per_step; vs dense in speedup_vs_dense",
+        "value": res["effective_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["t_e2e_ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "heads_q": w.heads_q, "heads_kv": w.heads_kv, "L": w.L,
+                   "head_dim": w.d, "block": w.block, "sparsity": args.sparsity, "kappa": res["kappa"],
+                   "sort": "QK", "beta": 1.0},
+        "latency_ms": {"select": res["t_select_ms"], "attn": res["t_attn_ms"], "e2e": res["t_e2e_ms"],
+                       "dense": res["t_dense_ms"]},
+        "speedup_vs_dense": res["speedup_vs_dense"],
+        "executed_tflops": res["executed_tflops_attn_call"],
+        "dense_tflops": res["dense_tflops"],
+        "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": (achieved / PEAK_BF16_TFLOPS) if achieved else None, "traffic": None,
+                     "avg_launch_ms": attn_ms},
+        "roofline_select": {"stage": "basa_select (all kernels)", "bound": "hbm",
+                            "achieved": res["selection_gbs_total"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": res["selection_gbs_total"] / PEAK_HBM_GBS,
+                            "achieved_two_pass_qk_only": res["selection_gbs_two_pass"],
+                            "bytes": res["selection_bytes"]},
+        "kernel_ms_per_step": res["kernel_ms_per_step"],
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, args.sparsity, Q, K, V, pipe)
+    if args.sweep:
+        rows = [res]
+        del pipe
+        for s in w.sparsities:
+            if s != args.sparsity:
+                rows.append(measure(w, s, Q, K, V, 2, 1, dense_reps=0)[0])
+        rows.append(measure(w, args.sparsity, Q, K, V, 2, 1, dense_reps=0, beta=0.0)[0] | {"variant": "beta=0"})
+        rows.append(measure(w, args.sparsity, Q, K, V, 2, 1, dense_reps=0, sort=bd.SORT_NONE)[0] | {"variant": "sort=none"})
+        del Q, K, V
+        torch.cuda.empty_cache()
+        for c in synth.CONFIGS:
+            if c.index == w.index:
+                continue
+            q2, k2, v2 = synth.make_qkv(c, device=dev)
+            for s in c.sparsities:
+                rows.append(measure(c, s, q2, k2, v2, 2, 1, dense_reps=1 if s == c.sparsities[0] else 0)[0])
+            del q2, k2, v2
+            torch.cuda.empty_cache()
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_sweep.json"), "w") as f:
+            json.dump(rows, f, indent=1)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -155,6 +155,20 @@ const char* basa_status_string(basa_status s);
 /* Reason of the last non-OK status returned on this thread (host string, owned by the
  * library, valid until the next failing call on the thread). */
 const char* basa_last_error(void);
+/*
+ * Per-kernel timing aid for benchmarks.  While enabled, every kernel launch of the
+ * entry points above is bracketed by a pair of HIP events recorded on the caller's
+ * stream (events are created per launch; nothing else changes).  basa_profile_read
+ * waits for the recorded events, adds the elapsed milliseconds and launch counts per
+ * kernel id into the host arrays total_ms[n] / launches[n] (n >= basa_profile_kernel_count()),
+ * and forgets the records.  Kernel ids are 0 .. count-1; basa_profile_kernel_name(id)
+ * names them.  Not for use under stream capture.
+ */
+basa_status basa_profile_enable(int on);
+int32_t basa_profile_kernel_count(void);
+const char* basa_profile_kernel_name(int32_t id);
+basa_status basa_profile_read(double* total_ms /*host*/, int32_t* launches /*host*/, int32_t n);
+
 /* Library version, e.g. "basa 0.1 gfx950". */
 const char* basa_version(void);
 

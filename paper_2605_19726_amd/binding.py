@@ -24,7 +24,8 @@ EXPORTS = (
     "basa_kappa", "basa_select_workspace_size", "basa_attn_workspace_size",
     "basa_sort_workspace_size", "basa_norm_sort", "basa_downsample", "basa_select",
     "basa_sparse_attn", "basa_dense_attn", "basa_status_string", "basa_last_error",
-    "basa_version",
+    "basa_version", "basa_profile_enable", "basa_profile_kernel_count", "basa_profile_kernel_name",
+    "basa_profile_read",
 )
 
 
@@ -83,6 +84,14 @@ def load():
     lib.basa_last_error.argtypes = []
     lib.basa_version.restype = C.c_char_p
     lib.basa_version.argtypes = []
+    lib.basa_profile_enable.restype = C.c_int
+    lib.basa_profile_enable.argtypes = [C.c_int]
+    lib.basa_profile_kernel_count.restype = C.c_int32
+    lib.basa_profile_kernel_count.argtypes = []
+    lib.basa_profile_kernel_name.restype = C.c_char_p
+    lib.basa_profile_kernel_name.argtypes = [C.c_int32]
+    lib.basa_profile_read.restype = C.c_int
+    lib.basa_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32), C.c_int32]
     _lib = lib
     return lib
 
@@ -245,3 +254,17 @@ def basa_dense_attn(q, k, v, block: int = 128, want_lse: bool = False, ws=None, 
     _check(lib.basa_dense_attn(C.byref(qd), C.byref(kd), C.byref(vd), C.byref(p), _ptr(out), _ptr(lse),
                                _ptr(ws), ws.numel(), _stream(q)))
     return (out, lse) if want_lse else out
+
+
+def basa_profile_enable(on: bool):
+    _check(load().basa_profile_enable(1 if on else 0))
+
+
+def basa_profile_read() -> dict:
+    """{kernel name: (total milliseconds, launches)} since the last read; waits for the events."""
+    lib = load()
+    n = int(lib.basa_profile_kernel_count())
+    ms = (C.c_double * n)()
+    cnt = (C.c_int32 * n)()
+    _check(lib.basa_profile_read(ms, cnt, n))
+    return {lib.basa_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}

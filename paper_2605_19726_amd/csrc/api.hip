@@ -4,6 +4,8 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
+#include <vector>
 #include "common.hpp"
 
 namespace basa {
@@ -20,6 +22,36 @@ void set_error(const char* fmt, ...) {
 basa_status hip_fail(hipError_t e, const char* what) {
   set_error("%s: %s", what, hipGetErrorString(e));
   return BASA_ERR_HIP;
+}
+
+// ---- profiling records -------------------------------------------------------------
+namespace {
+struct ProfRec { int id; hipEvent_t start, stop; };
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+const char* const kKernelNames[K_COUNT] = {
+    "norm_keys_kernel", "tile_sort_kernel", "merge_pass_kernel", "block_stats_kernel",
+    "block_scores_kernel", "row_select_kernel", "gather_kernels", "attn_mfma_kernel",
+    "attn_simple_kernel"};
+}  // namespace
+
+ProfScope::ProfScope(int id, hipStream_t st) : slot_(-1), st_(st) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (!g_prof_on) return;
+  ProfRec r;
+  r.id = id;
+  if (hipEventCreate(&r.start) != hipSuccess) return;
+  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+  (void)hipEventRecord(r.start, st);
+  g_prof_recs.push_back(r);
+  slot_ = (int)g_prof_recs.size() - 1;
+}
+
+ProfScope::~ProfScope() {
+  if (slot_ < 0) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (slot_ < (int)g_prof_recs.size()) (void)hipEventRecord(g_prof_recs[slot_].stop, st_);
 }
 
 namespace {
@@ -276,6 +308,39 @@ const char* basa_status_string(basa_status s) {
 }
 
 const char* basa_last_error(void) { return g_err; }
+
+basa_status basa_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+  return BASA_OK;
+}
+
+int32_t basa_profile_kernel_count(void) { return K_COUNT; }
+
+const char* basa_profile_kernel_name(int32_t id) {
+  return (id >= 0 && id < K_COUNT) ? kKernelNames[id] : "";
+}
+
+basa_status basa_profile_read(double* total_ms, int32_t* launches, int32_t n) {
+  if (!total_ms || !launches || n < K_COUNT) {
+    set_error("basa_profile_read needs arrays of at least %d entries", (int)K_COUNT);
+    return BASA_ERR_INVALID_ARG;
+  }
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (int i = 0; i < n; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  basa_status rc = BASA_OK;
+  for (ProfRec& r : g_prof_recs) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+    if (e == hipSuccess) { total_ms[r.id] += ms; launches[r.id] += 1; }
+    else rc = hip_fail(e, "basa_profile_read");
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof_recs.clear();
+  return rc;
+}
 const char* basa_version(void) { return "basa 0.1 gfx950"; }
 
 }  // extern "C"

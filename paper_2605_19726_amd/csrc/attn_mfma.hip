@@ -33,13 +33,9 @@ constexpr int kKTileElems = kTileKeys * kKStride;
 constexpr int kVTileElems = kD * kVStride;
 constexpr int kStageElems = kKTileElems + kVTileElems;
 
-// Position inside a 16-key group at which key `k16` (0..15) is stored in Vt: the
-// accumulator of a 32x32 MFMA holds, in lane half h, rows 4h+{0..3} and 8+4h+{0..3} of
-// each 16-row group; packing those 8 values gives operand slot 8h+e <-> key
-// 8*(e/4) + 4h + e%4.
-__host__ __device__ constexpr int vt_slot_of_key(int k16) {
-  return 8 * ((k16 >> 2) & 1) + 4 * (k16 >> 3) + (k16 & 3);
-}
+// Key order inside a 16-key group of Vt: the accumulator of a 32x32 MFMA holds, in lane
+// half h, rows 4h+{0..3} and 8+4h+{0..3} of each 16-row group; packing those 8 values
+// gives operand slot 8h+e <-> key 8*(e/4) + 4h + e%4, and Vt stores keys in slot order.
 
 // ---------------------------------------------------------------------------------
 // Gather rows of a bf16 tensor in sorted order into a dense, zero-padded buffer.
@@ -164,39 +160,37 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
   for (int i = 0; i < 4; ++i) o[i] = floatx16{0};
   float m_run = -INFINITY, l_run = 0.f;
 
-  uint4 kreg[CPT], vreg[CPT];
   auto tile_of = [&](int it) -> int {
     const int c = cols ? cols[it / TPB] : it / TPB;
     return c * TPB + (it % TPB);
   };
-  auto load_tile = [&](int it) {
-    const int t = tile_of(it);
-    const uint4* kp = Kh + (int64_t)t * 1024;
-    const uint4* vp = Vh + (int64_t)t * 1024;
+  // Staging registers of the tile in flight.  The prefetch is unconditional (the last
+  // iteration re-fetches its own tile) so that these stay in registers.
+  uint4 kreg[CPT], vreg[CPT];
+  int t_cur = tile_of(0);
+  {
+    const uint4* kp = Kh + (int64_t)t_cur * 1024;
+    const uint4* vp = Vh + (int64_t)t_cur * 1024;
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      kreg[i] = kp[i * NT + tid];
-      vreg[i] = vp[i * NT + tid];
-    }
-  };
-  auto store_tile = [&](int buf) {
-    __bf16* ks = smem + buf * kStageElems;
-    __bf16* vs = ks + kKTileElems;
+    for (int i = 0; i < CPT; ++i) { kreg[i] = kp[i * NT + tid]; vreg[i] = vp[i * NT + tid]; }
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
       const int id = i * NT + tid;
-      *reinterpret_cast<uint4*>(ks + (id >> 4) * kKStride + (id & 15) * 8) = kreg[i];
-      *reinterpret_cast<uint4*>(vs + (id >> 3) * kVStride + (id & 7) * 8) = vreg[i];
+      *reinterpret_cast<uint4*>(smem + (id >> 4) * kKStride + (id & 15) * 8) = kreg[i];
+      *reinterpret_cast<uint4*>(smem + kKTileElems + (id >> 3) * kVStride + (id & 7) * 8) = vreg[i];
     }
-  };
-
-  load_tile(0);
-  store_tile(0);
+  }
   __syncthreads();
 
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
-    if (it + 1 < n_iter) load_tile(it + 1);
+    const int t_next = tile_of(min(it + 1, n_iter - 1));
+    {
+      const uint4* kp = Kh + (int64_t)t_next * 1024;
+      const uint4* vp = Vh + (int64_t)t_next * 1024;
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) { kreg[i] = kp[i * NT + tid]; vreg[i] = vp[i * NT + tid]; }
+    }
     const __bf16* ks = smem + buf * kStageElems;
     const __bf16* vs = ks + kKTileElems;
 
@@ -210,7 +204,7 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
       s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
     }
     // ---- mask keys past L_k (only the last tile of a ragged sequence)
-    const int key0 = tile_of(it) * kTileKeys;
+    const int key0 = t_cur * kTileKeys;
     if (key0 + kTileKeys > a.Lk) {
       const int nvalid = a.Lk - key0;
 #pragma unroll
@@ -255,7 +249,17 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pb[g], o[db], 0, 0, 0);
       }
     }
-    if (it + 1 < n_iter) store_tile(buf ^ 1);
+    {
+      __bf16* kd = smem + (buf ^ 1) * kStageElems;
+      __bf16* vd = kd + kKTileElems;
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) {
+        const int id = i * NT + tid;
+        *reinterpret_cast<uint4*>(kd + (id >> 4) * kKStride + (id & 15) * 8) = kreg[i];
+        *reinterpret_cast<uint4*>(vd + (id >> 3) * kVStride + (id & 7) * 8) = vreg[i];
+      }
+    }
+    t_cur = t_next;
     __syncthreads();
   }
 
@@ -301,12 +305,15 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   uint4* Ks = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B));
   uint4* Vt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B) + sz_kv(BHkv, Nk, B));
 
+  {
+  ProfScope prof(K_GATHER, st);
   hipLaunchKernelGGL(gather_rows_kernel, dim3(Nq * B / 64, BHq), dim3(256), 0, st, a.q, a.perm_q, Qs, Nq * B);
   BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(Q)");
   hipLaunchKernelGGL(gather_rows_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.k, a.perm_k, Ks, Nk * B);
   BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(K)");
   hipLaunchKernelGGL(gather_vt_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.v, a.perm_k, Vt, Nk * B / 64);
   BASA_HIP_CHECK_LAUNCH("gather_vt_kernel");
+  }
 
   MfmaArgs m;
   m.Qs = Qs; m.Ks = Ks; m.Vt = Vt;
@@ -318,6 +325,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.total_blocks = BHq * Nq;
   m.scale_log2e = 1.4426950408889634f / sqrtf((float)kD);
   const size_t lds = 2 * kStageElems * sizeof(__bf16);
+  ProfScope prof(K_ATTN, st);
   if (B == 128) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<128>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

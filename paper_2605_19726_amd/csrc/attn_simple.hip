@@ -134,6 +134,7 @@ basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st) {
   if (BHq == 0 || Nq == 0) return BASA_OK;
   const float scale = 1.0f / sqrtf((float)a.q.d);
   dim3 grid(Nq, BHq);
+  ProfScope prof(K_ATTN_SIMPLE, st);
   const bool bf = a.q.dtype == BASA_BF16;
 #define BASA_AS(BF, D, BB) \
   hipLaunchKernelGGL((attn_simple_kernel<BF, D, BB>), grid, dim3(BB), 0, st, a, Nq, Nk, scale)

@@ -38,6 +38,19 @@ basa_status hip_fail(hipError_t e, const char* what);
     if (e__ != hipSuccess) return ::basa::hip_fail(e__, what); \
   } while (0)
 
+// ---- optional per-kernel timing (basa_profile_*): a scope object brackets one launch
+// with a pair of HIP events on the launch stream when profiling is enabled.
+enum KernelId {
+  K_NORM_KEYS = 0, K_TILE_SORT, K_MERGE, K_STATS, K_SCORES, K_ROW_SELECT, K_GATHER, K_ATTN,
+  K_ATTN_SIMPLE, K_COUNT
+};
+struct ProfScope {
+  ProfScope(int id, hipStream_t st);
+  ~ProfScope();
+  int slot_;
+  hipStream_t st_;
+};
+
 // ---- stage launchers (each validates nothing: the C entry points do) -------------
 
 // Sort keys + segmented sort.  Writes perm[bh][L]; optional keys_out[bh][L].

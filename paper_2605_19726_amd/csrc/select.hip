@@ -171,6 +171,7 @@ basa_status launch_block_scores(const float* featQ, const float* featK, float* s
                                 hipStream_t st) {
   if (BHq == 0 || Nq == 0 || Nk == 0) return BASA_OK;
   dim3 grid(ceil_div(Nk, 128), ceil_div(Nq, 128), BHq);
+  ProfScope prof(K_SCORES, st);
   hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), 0, st, featQ, featK, scores, group, Nq,
                      Nk, kdim_used, feat_stride);
   BASA_HIP_CHECK_LAUNCH("block_scores_kernel");
@@ -182,6 +183,7 @@ basa_status launch_row_select(const float* scores, int rows_total, int Nk, int k
                               float* row_mass, hipStream_t st) {
   if (rows_total == 0) return BASA_OK;
   dim3 grid(ceil_div(rows_total, 4));
+  ProfScope prof(K_ROW_SELECT, st);
 #define BASA_SEL(M)                                                                            \
   hipLaunchKernelGGL((row_select_kernel<M>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
                      kappa, mask_bits, row_count, row_cols, row_mass)

@@ -200,6 +200,8 @@ basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, flo
   const int lpr = x.d * elem / 16;
   const int rows_per_wg = (256 / lpr) * 8;
   dim3 kgrid(ceil_div(L, rows_per_wg), BH);
+  {
+  ProfScope prof(K_NORM_KEYS, st);
 #define BASA_KEYS(BF, D) \
   hipLaunchKernelGGL((norm_keys_kernel<BF, D>), kgrid, dim3(256), 0, st, x, buf0, keys_out)
   if (bf16 && x.d == 128) BASA_KEYS(true, 128);
@@ -208,6 +210,7 @@ basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, flo
   else BASA_KEYS(false, 64);
 #undef BASA_KEYS
   BASA_HIP_CHECK_LAUNCH("norm_keys_kernel");
+  }
 
   SegGeom g;
   g.L = L;
@@ -215,9 +218,12 @@ basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, flo
   g.segs = ceil_div(L, g.W);
   g.tiles_per_seg = ceil_div(g.W, kTile);
   const bool single = g.tiles_per_seg == 1;
+  {
+  ProfScope prof(K_TILE_SORT, st);
   hipLaunchKernelGGL(tile_sort_kernel, dim3(g.segs * g.tiles_per_seg, BH), dim3(kSortThreads), 0, st,
                      buf0, buf1, single ? perm : nullptr, g);
   BASA_HIP_CHECK_LAUNCH("tile_sort_kernel");
+  }
   if (single) return BASA_OK;
 
   uint64_t* src = buf1;
@@ -226,6 +232,7 @@ basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, flo
     const bool last = run * 2 >= g.W;
     const int pairs_per_seg = ceil_div(ceil_div(g.W, run), 2);
     const int chunks_per_pair = ceil_div(2 * run, kMergeChunk);
+    ProfScope prof(K_MERGE, st);
     hipLaunchKernelGGL(merge_pass_kernel, dim3(g.segs * pairs_per_seg * chunks_per_pair, BH),
                        dim3(kSortThreads), 0, st, src, dst, last ? perm : nullptr, g, run,
                        chunks_per_pair, pairs_per_seg);

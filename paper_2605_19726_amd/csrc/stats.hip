@@ -111,6 +111,7 @@ basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, 
   const int N = ceil_div(x.L, B);
   if (BH == 0 || N == 0) return BASA_OK;
   dim3 grid(N, BH);
+  ProfScope prof(K_STATS, st);
   const bool bf = x.dtype == BASA_BF16;
 #define BASA_STATS(BF, D, BB)                                                              \
   hipLaunchKernelGGL((block_stats_kernel<BF, D, BB>), grid, dim3(256), 0, st, x, perm, mean, \
