@@ -1,12 +1,17 @@
 // Block-sparse attention on the bf16 matrix cores of gfx950 (Sec. 2; Eq. 1; Alg. 1
 // step 12), head dimension 128.
 //
-// Layout prepared once per call by the gather kernels below (workspace):
-//   Qs [BHq ][Nq*B][128] bf16   rows of Q in sorted order, zero rows past L_q
-//   Ks [BHkv][Nk*B][128] bf16   rows of K in sorted order, zero rows past L_k
-//   Vt [BHkv][Nk*B/64][128][64] bf16   V in sorted order, transposed per 64-key tile
-//                                      (d major), keys of every 16-group stored in the
-//                                      order the MFMA B/A operand slots consume them.
+// Layout prepared once per call by the gather kernels below (workspace).  K and V are
+// stored as 64-key tiles that are byte-for-byte the LDS image the main kernel wants, so
+// the global -> LDS copy is a linear 16 KB copy done with direct-to-LDS loads:
+//   Qs [BHq ][Nq*B][128] bf16      rows of Q in sorted order, zero rows past L_q
+//   Kt [BHkv][tiles][64 rows][16 chunks of 8 bf16]   rows of K in sorted order; chunk c
+//        of row r sits at chunk position c ^ (r & 15)                (XOR swizzle)
+//   Vt [BHkv][tiles][128 d-rows][8 chunks of 8 keys] V in sorted order, transposed per
+//        tile (d major); the 8 keys of a chunk are in MFMA operand-slot order (below);
+//        chunk c of d-row r sits at chunk position c ^ ((r >> 1) & 7)
+// The swizzles make every ds_read_b128 of 16 consecutive lanes hit 16 distinct 16-byte
+// bank groups.
 //
 // Main kernel: one workgroup per query block, one wave per 32 queries.  Scores are
 // computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K tile rows from
@@ -14,8 +19,13 @@
 // running sum and the rescale factor of the online softmax are per-lane scalars, the
 // row max needs a single exchange between lanes l and l+32, and the exponentiated
 // accumulator registers are, after packing to bf16, already the B operand of the
-// second product O^T = V^T P^T (A = V^T tile rows from LDS).  K/V tiles of 64 keys are
-// double-buffered in LDS: global loads of tile t+1 are in flight while tile t is used.
+// second product O^T = V^T P^T (A = V^T tile rows from LDS).
+// The accumulator of a 32x32 MFMA holds, in lane half h, rows 4h+{0..3} and 8+4h+{0..3}
+// of each 16-row group; packing those 8 values gives operand slot 8h+e <-> key
+// 8*(e/4) + 4h + e%4 of the group, which is the key order inside a Vt chunk pair.
+// The running max is refreshed lazily: the accumulators are rescaled only when some
+// query's tile max exceeds its running max by more than 2^8, so the common iteration
+// touches O only through MFMA.  K/V tiles are double-buffered in LDS.
 #include "common.hpp"
 
 namespace basa {
@@ -23,25 +33,22 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kD = 128;
 constexpr int kTileKeys = 64;
-constexpr int kKStride = 136;   // bf16 elements per K row in LDS (256 B + 16 B pad)
-constexpr int kVStride = 72;    // bf16 elements per V^T row in LDS (128 B + 16 B pad)
-constexpr int kKTileElems = kTileKeys * kKStride;
-constexpr int kVTileElems = kD * kVStride;
-constexpr int kStageElems = kKTileElems + kVTileElems;
-
-// Key order inside a 16-key group of Vt: the accumulator of a 32x32 MFMA holds, in lane
-// half h, rows 4h+{0..3} and 8+4h+{0..3} of each 16-row group; packing those 8 values
-// gives operand slot 8h+e <-> key 8*(e/4) + 4h + e%4, and Vt stores keys in slot order.
+constexpr int kTileBytes = 16384;           // one K tile or one V^T tile
+constexpr int kStageBytes = 2 * kTileBytes; // K tile then V^T tile
+constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
 
 // ---------------------------------------------------------------------------------
-// Gather rows of a bf16 tensor in sorted order into a dense, zero-padded buffer.
+// Gather kernels
 // ---------------------------------------------------------------------------------
+// Rows of a bf16 tensor in sorted order, zero-padded; swizzle = 1 writes K-tile order.
 __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const int32_t* __restrict__ perm,
-                                                          uint4* __restrict__ dst, int rows_padded) {
+                                                          uint4* __restrict__ dst, int rows_padded,
+                                                          int swizzle) {
   const int bh = blockIdx.y;
   const int sub = threadIdx.x & 15, rig = threadIdx.x >> 4;
   const int32_t* pm = perm ? perm + (int64_t)bh * x.L : nullptr;
@@ -59,14 +66,16 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const in
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int pos = blockIdx.x * 64 + it * 16 + rig;
-    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * 16 + sub] = v[it];
+    const int c = swizzle ? (sub ^ (pos & 15)) : sub;
+    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * 16 + c] = v[it];
   }
 }
 
-// V: gather 64 sorted rows, transpose through LDS, write the [128][64] tile.
+// V: gather 64 sorted rows, transpose through LDS, write the swizzled [128][64] tile.
 __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int32_t* __restrict__ perm,
                                                         uint4* __restrict__ dst, int tiles_per_head) {
-  __shared__ __attribute__((aligned(16))) uint16_t rows[kTileKeys][kKStride];
+  constexpr int kRowStride = 136;   // 256 B + 16 B pad
+  __shared__ __attribute__((aligned(16))) uint16_t rows[kTileKeys][kRowStride];
   const int bh = blockIdx.y, tile = blockIdx.x;
   const int sub = threadIdx.x & 15, rig = threadIdx.x >> 4;
   const int32_t* pm = perm ? perm + (int64_t)bh * v.L : nullptr;
@@ -83,7 +92,8 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
     *reinterpret_cast<uint4*>(&rows[kk][sub * 8]) = val;
   }
   __syncthreads();
-  // 1024 output chunks of 8 slots; thread handles chunk (d = id/8, s8 = id%8)
+  // 1024 output chunks of 8 slots; thread handles chunk (d = id/8, s8 = id%8):
+  // 16-key group g16 = s8/2, lane half hh = s8%2, slot e <-> key 16 g16 + 8(e/4) + 4 hh + e%4
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int id = it * 256 + threadIdx.x;
@@ -98,15 +108,15 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
     uint4 o;
     o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
     o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
-    dst[(((int64_t)bh * tiles_per_head + tile) * kD + dd) * 8 + s8] = o;
+    dst[(((int64_t)bh * tiles_per_head + tile) * kD + dd) * 8 + (s8 ^ ((dd >> 1) & 7))] = o;
   }
 }
 
 // ---------------------------------------------------------------------------------
-// Main kernel.
+// Main kernel
 // ---------------------------------------------------------------------------------
 struct MfmaArgs {
-  const uint4* Qs; const uint4* Ks; const uint4* Vt;
+  const uint4* Qs; const char* Kt; const char* Vt;
   const int32_t* row_count; const int32_t* row_cols; int32_t cols_stride;
   const int32_t* perm_q;
   __bf16* out; float* lse;
@@ -114,12 +124,97 @@ struct MfmaArgs {
   float scale_log2e;
 };
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+// Per-wave state of the online softmax and the output accumulator.
+struct WaveState {
+  floatx16 o[4];
+  float m_run, l_run;
+};
+
+// max of three floats; this file is compiled with -fno-honor-nans (scores are finite or
+// -inf), so no NaN canonicalisation is emitted and this becomes one v_max3_f32.
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// One 64-key tile: S^T, softmax, O^T update, reading LDS stage kStage.  kMasked: keys at
+// tile positions >= nvalid do not exist (ragged end of the sequence) and get -inf scores.
+template <int kStage, bool kMasked>
+__device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8], const char* smem,
+                                             const int (&kaddr)[8], const int (&vaddr)[4], float c,
+                                             int nvalid, int h) {
+  const char* ks = smem + kStage * kStageBytes;
+  const char* vs = ks + kTileBytes;
+
+  // ---- S^T = K Q^T : two 32-key row blocks
+  floatx16 s0 = {0}, s1 = {0};
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + kaddr[s]);
+    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + kaddr[s] + 32 * 256);
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
+  }
+  if (kMasked && nvalid < kTileKeys) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kk = 8 * (r >> 2) + 4 * h + (r & 3);
+      if (kk >= nvalid) s0[r] = -INFINITY;
+      if (32 + kk >= nvalid) s1[r] = -INFINITY;
+    }
+  }
+  // ---- online softmax in the log2 domain, lazy running max
+  float mx = max3(s0[0], s1[0], s0[1]);
+#pragma unroll
+  for (int r = 1; r < 15; ++r) mx = max3(mx, s1[r], s0[r + 1]);
+  mx = max3(mx, s1[15], __shfl_xor(max3(mx, s1[15], s1[15]), 32));
+  const float mc = mx * c;
+  if (__builtin_amdgcn_ballot_w64(mc > st.m_run + kLazyTau) != 0) {
+    const float m_new = fmaxf(st.m_run, mc);
+    const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);
+    st.m_run = m_new;
+    st.l_run *= alpha;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[i][r] *= alpha;
+  }
+  const float m_use = st.m_run;
+  bf16x8 pb[4];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    pb[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_use));
+    pb[2 + (r >> 3)][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_use));
+  }
+  // row sum of the bf16-rounded probabilities (the values the second product consumes)
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  float lsum = st.l_run;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 0, 1), ones, lsum, false);
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 2, 3), ones, lsum, false);
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 4, 5), ones, lsum, false);
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 6, 7), ones, lsum, false);
+  }
+  st.l_run = lsum;
+
+  // ---- O^T += V^T P^T
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const bf16x8 vv = *reinterpret_cast<const bf16x8*>(vs + vaddr[g] + db * 32 * 128);
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pb[g], st.o[db], 0, 0, 0);
+    }
+  }
+}
+
 template <int kB>
 __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
-  constexpr int NT = kB * 2;                 // threads
+  constexpr int NW = kB / 32;                // waves
   constexpr int TPB = kB / kTileKeys;        // key tiles per block
-  constexpr int CPT = 1024 / NT;             // 16-byte chunks per thread per tile (K and V each)
-  extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
+  constexpr int LPW = 32 / NW;               // 1 KB direct-to-LDS loads per wave per tile
+  extern __shared__ __attribute__((aligned(16))) char smem[];
 
   // XCD-aware order: consecutive workgroup ids go round-robin over the 8 XCDs; give each
   // XCD a contiguous range of (head, query block) so that its L2 sees one head at a time.
@@ -127,7 +222,8 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
   if ((a.total_blocks & 7) == 0) logical = (blockIdx.x & 7) * (a.total_blocks >> 3) + (blockIdx.x >> 3);
   const int bhq = logical / a.Nq, gq = logical - bhq * a.Nq;
   const int bhk = bhq / a.group;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 31, h = lane >> 5;
 
   const int64_t rowid = (int64_t)bhq * a.Nq + gq;
@@ -139,9 +235,28 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
     const int last_col = cols ? cols[count - 1] : a.Nk - 1;
     if (TPB == 2 && last_col * kB + kTileKeys >= a.Lk) n_iter -= 1;
   }
-  const int tiles_per_head = a.Nk * TPB;
-  const uint4* Kh = a.Ks + (int64_t)bhk * tiles_per_head * 1024;
-  const uint4* Vh = a.Vt + (int64_t)bhk * tiles_per_head * 1024;
+  const int64_t tiles_per_head = (int64_t)a.Nk * TPB;
+  const char* Kh = a.Kt + (int64_t)bhk * tiles_per_head * kTileBytes;
+  const char* Vh = a.Vt + (int64_t)bhk * tiles_per_head * kTileBytes;
+
+  auto tile_of = [&](int it) -> int {
+    const int c = cols ? cols[it / TPB] : it / TPB;
+    return c * TPB + (it % TPB);
+  };
+  // direct-to-LDS copy of tile t into a stage: 32 chunks of 1 KB, chunk j*NW+wave by this wave
+  auto issue_tile = [&](int t, int stage) {
+    const char* kp = Kh + (int64_t)t * kTileBytes + lane * 16;
+    const char* vp = Vh + (int64_t)t * kTileBytes + lane * 16;
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+      const int cb = j * NW + wave;                       // 0..31, wave-uniform
+      const char* src = (cb < 16 ? kp : vp) + (cb & 15) * 1024;
+      char* dst = smem + stage * kStageBytes + cb * 1024;
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+    }
+  };
+
+  issue_tile(tile_of(0), 0);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[8];
@@ -154,117 +269,46 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
       qf[s] = *reinterpret_cast<bf16x8*>(&t);
     }
   }
+  // LDS byte offsets inside a stage.  K: row li (+32 for the second block), chunk 2s+h at
+  // position (2s+h) ^ (li & 15).  V^T: d-row li (+32 db), chunk 2g+h at (2g+h) ^ ((li>>1)&7).
+  int kaddr[8], vaddr[4];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) kaddr[s] = li * 256 + (((2 * s + h) ^ (li & 15)) << 4);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) vaddr[g] = li * 128 + (((2 * g + h) ^ ((li >> 1) & 7)) << 4);
 
-  floatx16 o[4];
+  WaveState st;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o[i] = floatx16{0};
-  float m_run = -INFINITY, l_run = 0.f;
+  for (int i = 0; i < 4; ++i) st.o[i] = floatx16{0};
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+  const float c = a.scale_log2e;
 
-  auto tile_of = [&](int it) -> int {
-    const int c = cols ? cols[it / TPB] : it / TPB;
-    return c * TPB + (it % TPB);
-  };
-  // Staging registers of the tile in flight.  The prefetch is unconditional (the last
-  // iteration re-fetches its own tile) so that these stay in registers.
-  uint4 kreg[CPT], vreg[CPT];
-  int t_cur = tile_of(0);
-  {
-    const uint4* kp = Kh + (int64_t)t_cur * 1024;
-    const uint4* vp = Vh + (int64_t)t_cur * 1024;
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) { kreg[i] = kp[i * NT + tid]; vreg[i] = vp[i * NT + tid]; }
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int id = i * NT + tid;
-      *reinterpret_cast<uint4*>(smem + (id >> 4) * kKStride + (id & 15) * 8) = kreg[i];
-      *reinterpret_cast<uint4*>(smem + kKTileElems + (id >> 3) * kVStride + (id & 7) * 8) = vreg[i];
-    }
-  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  for (int it = 0; it < n_iter; ++it) {
-    const int buf = it & 1;
-    const int t_next = tile_of(min(it + 1, n_iter - 1));
-    {
-      const uint4* kp = Kh + (int64_t)t_next * 1024;
-      const uint4* vp = Vh + (int64_t)t_next * 1024;
-#pragma unroll
-      for (int i = 0; i < CPT; ++i) { kreg[i] = kp[i * NT + tid]; vreg[i] = vp[i * NT + tid]; }
-    }
-    const __bf16* ks = smem + buf * kStageElems;
-    const __bf16* vs = ks + kKTileElems;
-
-    // ---- S^T = K Q^T : two 32-key row blocks
-    floatx16 s0 = {0}, s1 = {0};
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + li * kKStride + 16 * s + 8 * h);
-      const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + (32 + li) * kKStride + 16 * s + 8 * h);
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
-    }
-    // ---- mask keys past L_k (only the last tile of a ragged sequence)
-    const int key0 = t_cur * kTileKeys;
-    if (key0 + kTileKeys > a.Lk) {
-      const int nvalid = a.Lk - key0;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kk = 8 * (r >> 2) + 4 * h + (r & 3);
-        if (kk >= nvalid) s0[r] = -INFINITY;
-        if (32 + kk >= nvalid) s1[r] = -INFINITY;
-      }
-    }
-    // ---- online softmax in the log2 domain
-    float mx = s0[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * a.scale_log2e);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.f;
-    bf16x8 pb[4];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(s0[r], a.scale_log2e, -m_new));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(s1[r], a.scale_log2e, -m_new));
-      psum += p0 + p1;
-      pb[r >> 3][r & 7] = (__bf16)p0;
-      pb[2 + (r >> 3)][r & 7] = (__bf16)p1;
-    }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {         // 16-key group of the tile
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const bf16x8 vv = *reinterpret_cast<const bf16x8*>(vs + (32 * db + li) * kVStride + 16 * g + 8 * h);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pb[g], o[db], 0, 0, 0);
-      }
-    }
-    {
-      __bf16* kd = smem + (buf ^ 1) * kStageElems;
-      __bf16* vd = kd + kKTileElems;
-#pragma unroll
-      for (int i = 0; i < CPT; ++i) {
-        const int id = i * NT + tid;
-        *reinterpret_cast<uint4*>(kd + (id >> 4) * kKStride + (id & 15) * 8) = kreg[i];
-        *reinterpret_cast<uint4*>(vd + (id >> 3) * kVStride + (id & 7) * 8) = vreg[i];
-      }
-    }
-    t_cur = t_next;
+  // All tiles but the last: never ragged.  The last tile is peeled so that the masking code
+  // (and its per-lane constants) stays out of the loop.
+  const int n_main = n_iter - 1;
+  for (int it = 0; it < n_main; it += 2) {
+    issue_tile(tile_of(it + 1), 1);
+    process_tile<0, false>(st, qf, smem, kaddr, vaddr, c, kTileKeys, h);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (it + 1 >= n_main) break;
+    issue_tile(tile_of(it + 2), 0);
+    process_tile<1, false>(st, qf, smem, kaddr, vaddr, c, kTileKeys, h);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  {
+    const int nvalid = a.Lk - tile_of(n_iter - 1) * kTileKeys;
+    if ((n_iter - 1) & 1) process_tile<1, true>(st, qf, smem, kaddr, vaddr, c, nvalid, h);
+    else process_tile<0, true>(st, qf, smem, kaddr, vaddr, c, nvalid, h);
   }
 
   // ---- epilogue: normalise, scatter rows to their original positions
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = st.l_run + __shfl_xor(st.l_run, 32);
   const float inv_l = 1.0f / l_tot;
   const int pos = gq * kB + wave * 32 + li;
   if (pos < a.Lq) {
@@ -276,11 +320,11 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
       for (int r4 = 0; r4 < 4; ++r4) {
         bf16x4 pk;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(o[db][4 * r4 + e] * inv_l);
+        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(st.o[db][4 * r4 + e] * inv_l);
         *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * r4 + 4 * h) = pk;
       }
     if (a.lse && h == 0)
-      a.lse[(int64_t)bhq * a.Lq + orow] = (m_run + __log2f(l_tot)) * 0.6931471805599453f;
+      a.lse[(int64_t)bhq * a.Lq + orow] = (st.m_run + __log2f(l_tot)) * 0.6931471805599453f;
   }
 }
 
@@ -302,21 +346,21 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   if (BHq == 0 || Nq == 0) return BASA_OK;
   char* ws = reinterpret_cast<char*>(a.ws);
   uint4* Qs = reinterpret_cast<uint4*>(ws);
-  uint4* Ks = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B));
+  uint4* Kt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B));
   uint4* Vt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B) + sz_kv(BHkv, Nk, B));
 
   {
-  ProfScope prof(K_GATHER, st);
-  hipLaunchKernelGGL(gather_rows_kernel, dim3(Nq * B / 64, BHq), dim3(256), 0, st, a.q, a.perm_q, Qs, Nq * B);
-  BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(Q)");
-  hipLaunchKernelGGL(gather_rows_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.k, a.perm_k, Ks, Nk * B);
-  BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(K)");
-  hipLaunchKernelGGL(gather_vt_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.v, a.perm_k, Vt, Nk * B / 64);
-  BASA_HIP_CHECK_LAUNCH("gather_vt_kernel");
+    ProfScope prof(K_GATHER, st);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(Nq * B / 64, BHq), dim3(256), 0, st, a.q, a.perm_q, Qs, Nq * B, 0);
+    BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(Q)");
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.k, a.perm_k, Kt, Nk * B, 1);
+    BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(K)");
+    hipLaunchKernelGGL(gather_vt_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.v, a.perm_k, Vt, Nk * B / 64);
+    BASA_HIP_CHECK_LAUNCH("gather_vt_kernel");
   }
 
   MfmaArgs m;
-  m.Qs = Qs; m.Ks = Ks; m.Vt = Vt;
+  m.Qs = Qs; m.Kt = reinterpret_cast<const char*>(Kt); m.Vt = reinterpret_cast<const char*>(Vt);
   m.row_count = a.row_count; m.row_cols = a.row_cols; m.cols_stride = a.cols_stride;
   m.perm_q = a.perm_q;
   m.out = reinterpret_cast<__bf16*>(a.out); m.lse = a.lse;
@@ -324,17 +368,11 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.group = a.q.heads / a.k.heads;
   m.total_blocks = BHq * Nq;
   m.scale_log2e = 1.4426950408889634f / sqrtf((float)kD);
-  const size_t lds = 2 * kStageElems * sizeof(__bf16);
+  const size_t lds = 2 * kStageBytes;
   ProfScope prof(K_ATTN, st);
   if (B == 128) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<128>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((attn_mfma_kernel<128>), dim3(m.total_blocks), dim3(256), lds, st, m);
   } else {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<64>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((attn_mfma_kernel<64>), dim3(m.total_blocks), dim3(128), lds, st, m);
   }
   BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
