@@ -29,7 +29,8 @@ EXTRA = {"attn_mfma.hip": ["-fno-honor-nans"]}
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    dev_flags = os.environ.get("BASA_HIPCC_EXTRA", "").split()     # e.g. -D switches while tuning
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), *dev_flags, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -13,8 +13,13 @@
 // The swizzles make every ds_read_b128 of 16 consecutive lanes hit 16 distinct 16-byte
 // bank groups.
 //
-// Main kernel: one workgroup per query block, one wave per 32 queries.  Scores are
-// computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K tile rows from
+// Main kernel: one workgroup of 8 waves owns 256 consecutive sorted queries, i.e. 2 query
+// blocks of 128 (4 of 64), one wave per 32 queries.  Streaming K/V tiles from L2 into LDS is
+// what bounds this kernel (128 queries per tile would need more L2 bandwidth than the chip
+// has), so the query blocks of a workgroup share every tile: the workgroup walks the UNION
+// of their block lists in ascending order, each tile is fetched once, and only the waves
+// whose query block lists the tile's key block compute on it.  Scores are computed
+// TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K tile rows from
 // LDS, B = Q^T held in registers), so that every lane owns ONE query: the running max,
 // running sum and the rescale factor of the online softmax are per-lane scalars, the
 // row max needs a single exchange between lanes l and l+32, and the exponentiated
@@ -25,7 +30,8 @@
 // 8*(e/4) + 4h + e%4 of the group, which is the key order inside a Vt chunk pair.
 // The running max is refreshed lazily: the accumulators are rescaled only when some
 // query's tile max exceeds its running max by more than 2^8, so the common iteration
-// touches O only through MFMA.  K/V tiles are double-buffered in LDS.
+// touches O only through MFMA.  K/V tiles go through a 4-stage LDS ring (tile t+3 is in
+// flight while tile t is used); one workgroup barrier per tile.
 #include "common.hpp"
 
 namespace basa {
@@ -40,6 +46,12 @@ constexpr int kD = 128;
 constexpr int kTileKeys = 64;
 constexpr int kTileBytes = 16384;           // one K tile or one V^T tile
 constexpr int kStageBytes = 2 * kTileBytes; // K tile then V^T tile
+constexpr int kStages = 4;
+constexpr int kRingBytes = kStages * kStageBytes;
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kQueriesPerWg = kWaves * 32;
+constexpr int kLoadsPerWave = 32 / kWaves;  // 1 KB direct-to-LDS loads per wave per tile
 constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
 
 // ---------------------------------------------------------------------------------
@@ -120,7 +132,7 @@ struct MfmaArgs {
   const int32_t* row_count; const int32_t* row_cols; int32_t cols_stride;
   const int32_t* perm_q;
   __bf16* out; float* lse;
-  int Nq, Nk, Lq, Lk, group, total_blocks;
+  int Nq, Nk, Lq, Lk, group, wgs_per_head, total_wgs;
   float scale_log2e;
 };
 
@@ -137,21 +149,21 @@ struct WaveState {
 // -inf), so no NaN canonicalisation is emitted and this becomes one v_max3_f32.
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-// One 64-key tile: S^T, softmax, O^T update, reading LDS stage kStage.  kMasked: keys at
-// tile positions >= nvalid do not exist (ragged end of the sequence) and get -inf scores.
-template <int kStage, bool kMasked>
-__device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8], const char* smem,
-                                             const int (&kaddr)[8], const int (&vaddr)[4], float c,
-                                             int nvalid, int h) {
-  const char* ks = smem + kStage * kStageBytes;
-  const char* vs = ks + kTileBytes;
+// One 64-key tile: S^T, softmax, O^T update, reading the LDS stage at `stage`.  kMasked:
+// keys at tile positions >= nvalid do not exist (ragged end of the sequence) and get -inf.
+template <bool kMasked>
+__device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8], const char* stage,
+                                             int kaddr0, int vaddr0, float c, int nvalid, int h) {
+  const char* ks = stage;
+  const char* vs = stage + kTileBytes;
 
   // ---- S^T = K Q^T : two 32-key row blocks
   floatx16 s0 = {0}, s1 = {0};
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + kaddr[s]);
-    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + kaddr[s] + 32 * 256);
+    const int ka = kaddr0 ^ (s << 5);     // chunk 2s+h of row li at position (2s+h) ^ (li & 15)
+    const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + ka);
+    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + ka + 32 * 256);
     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
   }
@@ -201,67 +213,115 @@ __device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8
   // ---- O^T += V^T P^T
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
+    const int va = vaddr0 ^ (g << 5);     // chunk 2g+h of d-row li at position (2g+h) ^ ((li>>1)&7)
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      const bf16x8 vv = *reinterpret_cast<const bf16x8*>(vs + vaddr[g] + db * 32 * 128);
+      const bf16x8 vv = *reinterpret_cast<const bf16x8*>(vs + va + db * 32 * 128);
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pb[g], st.o[db], 0, 0, 0);
     }
   }
 }
 
+// Dynamic LDS: [ring: kStages x 32 KB][seq: Nk words][wave_counts: kWaves words].
+// seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
+// this workgroup lists it).  While seq is being built the ring area holds the per-key-block
+// membership flags.
 template <int kB>
-__global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
-  constexpr int NW = kB / 32;                // waves
-  constexpr int TPB = kB / kTileKeys;        // key tiles per block
-  constexpr int LPW = 32 / NW;               // 1 KB direct-to-LDS loads per wave per tile
+__global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
+  constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4
+  constexpr int WPG = kB / 32;               // waves per query block: 4 or 2
+  constexpr int TPB = kB / kTileKeys;        // key tiles per key block: 2 or 1
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  uint32_t* flags = reinterpret_cast<uint32_t*>(smem);
+  uint32_t* seq = reinterpret_cast<uint32_t*>(smem + kRingBytes);
+  uint32_t* wave_counts = seq + a.Nk;
 
   // XCD-aware order: consecutive workgroup ids go round-robin over the 8 XCDs; give each
-  // XCD a contiguous range of (head, query block) so that its L2 sees one head at a time.
+  // XCD a contiguous range of (head, query blocks) so that its L2 sees one head at a time.
   int logical = blockIdx.x;
-  if ((a.total_blocks & 7) == 0) logical = (blockIdx.x & 7) * (a.total_blocks >> 3) + (blockIdx.x >> 3);
-  const int bhq = logical / a.Nq, gq = logical - bhq * a.Nq;
+  if ((a.total_wgs & 7) == 0) logical = (blockIdx.x & 7) * (a.total_wgs >> 3) + (blockIdx.x >> 3);
+  const int bhq = logical / a.wgs_per_head, wg = logical - bhq * a.wgs_per_head;
   const int bhk = bhq / a.group;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 31, h = lane >> 5;
+  const int grp = wave / WPG;                          // query block of this wave inside the wg
+  const int gq = wg * NQB + grp;                       // may be >= Nq in the last workgroup
+  const int nqb = min(NQB, a.Nq - wg * NQB);           // query blocks that exist
 
-  const int64_t rowid = (int64_t)bhq * a.Nq + gq;
-  const int count = a.row_cols ? a.row_count[rowid] : a.Nk;
-  const int32_t* cols = a.row_cols ? a.row_cols + rowid * a.cols_stride : nullptr;
-  int n_iter = count * TPB;
+  // ---- union of the block lists of this workgroup's query blocks ------------------------
+  for (int c = tid; c < a.Nk; c += kThreads) flags[c] = a.row_cols ? 0u : ((1u << nqb) - 1u);
+  __syncthreads();
+  if (a.row_cols) {
+    for (int g = 0; g < nqb; ++g) {
+      const int64_t rowid = (int64_t)bhq * a.Nq + wg * NQB + g;
+      const int cnt = a.row_count[rowid];
+      const int32_t* cl = a.row_cols + rowid * a.cols_stride;
+      for (int i = tid; i < cnt; i += kThreads) atomicOr(&flags[cl[i]], 1u << g);
+    }
+    __syncthreads();
+  }
+  int n_union = 0;
+  for (int base = 0; base < a.Nk; base += kThreads) {
+    const int cidx = base + tid;
+    const uint32_t f = cidx < a.Nk ? flags[cidx] : 0u;
+    const uint64_t bal = __builtin_amdgcn_ballot_w64(f != 0u);
+    if (lane == 0) wave_counts[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const int cw = wave_counts[w];
+      before += (w < wave) ? cw : 0;
+      total += cw;
+    }
+    if (f != 0u) seq[n_union + before + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)cidx | (f << 24);
+    n_union += total;
+    __syncthreads();
+  }
+  // every thread has passed its last read of flags (the ring area) and seq is complete
+
+  int n_tiles = n_union * TPB;
   {
     // a ragged last key block may leave its trailing tile without any valid key
-    const int last_col = cols ? cols[count - 1] : a.Nk - 1;
-    if (TPB == 2 && last_col * kB + kTileKeys >= a.Lk) n_iter -= 1;
+    const int last_col = (int)(seq[n_union - 1] & 0xffffffu);
+    if (TPB == 2 && last_col * kB + kTileKeys >= a.Lk) n_tiles -= 1;
   }
   const int64_t tiles_per_head = (int64_t)a.Nk * TPB;
   const char* Kh = a.Kt + (int64_t)bhk * tiles_per_head * kTileBytes;
   const char* Vh = a.Vt + (int64_t)bhk * tiles_per_head * kTileBytes;
 
-  auto tile_of = [&](int it) -> int {
-    const int c = cols ? cols[it / TPB] : it / TPB;
-    return c * TPB + (it % TPB);
+  // entry of union position i (wave-uniform value in an SGPR)
+  auto entry_of = [&](int t) -> uint32_t {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)seq[t / TPB]);
   };
-  // direct-to-LDS copy of tile t into a stage: 32 chunks of 1 KB, chunk j*NW+wave by this wave
-  auto issue_tile = [&](int t, int stage) {
-    const char* kp = Kh + (int64_t)t * kTileBytes + lane * 16;
-    const char* vp = Vh + (int64_t)t * kTileBytes + lane * 16;
+  // direct-to-LDS copy of tile `tile` into ring stage `stage`: 32 chunks of 1 KB, chunk
+  // j*kWaves+wave by this wave (16 K chunks, then 16 V chunks)
+  auto issue_tile = [&](int tile, int stage) {
+    const char* kp = Kh + (int64_t)tile * kTileBytes;      // wave-uniform bases
+    const char* vp = Vh + (int64_t)tile * kTileBytes;
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-      const int cb = j * NW + wave;                       // 0..31, wave-uniform
-      const char* src = (cb < 16 ? kp : vp) + (cb & 15) * 1024;
+    for (int j = 0; j < kLoadsPerWave; ++j) {
+      const int cb = j * kWaves + wave;                   // 0..31, wave-uniform
+      const char* src = (cb < 16 ? kp : vp) + (cb & 15) * 1024 + (uint32_t)(lane * 16);
       char* dst = smem + stage * kStageBytes + cb * 1024;
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
     }
   };
+  auto tile_of = [&](int t) -> int {
+    const int tt = min(t, n_tiles - 1);
+    return (int)(entry_of(tt) & 0xffffffu) * TPB + (tt % TPB);
+  };
 
+  // prologue: tiles 0..2 into stages 0..2 (past the end: the last tile again, never read)
   issue_tile(tile_of(0), 0);
+  issue_tile(tile_of(1), 1);
+  issue_tile(tile_of(2), 2);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[8];
   {
-    const int64_t qrow = ((int64_t)bhq * a.Nq + gq) * kB + wave * 32 + li;
+    const int64_t qrow = ((int64_t)bhq * a.Nq + min(gq, a.Nq - 1)) * kB + (wave % WPG) * 32 + li;
     const uint4* qp = a.Qs + qrow * 16;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -271,11 +331,9 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
   }
   // LDS byte offsets inside a stage.  K: row li (+32 for the second block), chunk 2s+h at
   // position (2s+h) ^ (li & 15).  V^T: d-row li (+32 db), chunk 2g+h at (2g+h) ^ ((li>>1)&7).
-  int kaddr[8], vaddr[4];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) kaddr[s] = li * 256 + (((2 * s + h) ^ (li & 15)) << 4);
-#pragma unroll
-  for (int g = 0; g < 4; ++g) vaddr[g] = li * 128 + (((2 * g + h) ^ ((li >> 1) & 7)) << 4);
+  // (step s / group g are folded in by xor with s<<5 / g<<5 at the point of use)
+  const int kaddr = li * 256 + ((h ^ (li & 15)) << 4);
+  const int vaddr = li * 128 + ((h ^ ((li >> 1) & 7)) << 4);
 
   WaveState st;
 #pragma unroll
@@ -283,35 +341,44 @@ __global__ __launch_bounds__(kB * 2, 2) void attn_mfma_kernel(MfmaArgs a) {
   st.m_run = -INFINITY;
   st.l_run = 0.f;
   const float c = a.scale_log2e;
-
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  const uint32_t my_bit = 1u << (24 + grp);
 
   // All tiles but the last: never ragged.  The last tile is peeled so that the masking code
-  // (and its per-lane constants) stays out of the loop.
-  const int n_main = n_iter - 1;
-  for (int it = 0; it < n_main; it += 2) {
-    issue_tile(tile_of(it + 1), 1);
-    process_tile<0, false>(st, qf, smem, kaddr, vaddr, c, kTileKeys, h);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // (and its per-lane constants) stays out of the loop.  Loads are issued in tile order, so
+  // "at most 2 tiles of my loads outstanding" means my part of tile t has landed; the barrier
+  // then says everyone's part has, and that everyone is done with tile t-1, whose stage the
+  // next load overwrites.
+  // The union entries needed by the next iteration (which tile to compute, which to fetch) are
+  // read from LDS at the top of an iteration and turned into scalars at its end, so their
+  // latency hides behind the tile's arithmetic.
+  uint32_t e_cur = entry_of(0);
+  for (int t = 0; t < n_tiles - 1; ++t) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLoadsPerWave) : "memory");
     __syncthreads();
-    if (it + 1 >= n_main) break;
-    issue_tile(tile_of(it + 2), 0);
-    process_tile<1, false>(st, qf, smem, kaddr, vaddr, c, kTileKeys, h);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    const int t_fetch = min(t + 3, n_tiles - 1);
+    const uint32_t raw_next = seq[(t + 1) / TPB];
+    const uint32_t raw_fetch = seq[t_fetch / TPB];
+    if (e_cur & my_bit)
+      process_tile<false>(st, qf, smem + (t & (kStages - 1)) * kStageBytes, kaddr, vaddr, c, kTileKeys, h);
+    // stage (t+3)%4 held tile t-1: every wave finished it before the barrier above
+    const int fetch_block = __builtin_amdgcn_readfirstlane((int)raw_fetch) & 0xffffff;
+    issue_tile(fetch_block * TPB + (t_fetch % TPB), (t + 3) & (kStages - 1));
+    e_cur = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_next);
   }
   {
-    const int nvalid = a.Lk - tile_of(n_iter - 1) * kTileKeys;
-    if ((n_iter - 1) & 1) process_tile<1, true>(st, qf, smem, kaddr, vaddr, c, nvalid, h);
-    else process_tile<0, true>(st, qf, smem, kaddr, vaddr, c, nvalid, h);
+    const int t = n_tiles - 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
+    if (e_cur & my_bit)
+      process_tile<true>(st, qf, smem + (t & (kStages - 1)) * kStageBytes, kaddr, vaddr, c, nvalid, h);
   }
 
   // ---- epilogue: normalise, scatter rows to their original positions
   const float l_tot = st.l_run + __shfl_xor(st.l_run, 32);
   const float inv_l = 1.0f / l_tot;
-  const int pos = gq * kB + wave * 32 + li;
-  if (pos < a.Lq) {
+  const int pos = gq * kB + (wave % WPG) * 32 + li;
+  if (gq < a.Nq && pos < a.Lq) {
     const int orow = a.perm_q ? a.perm_q[(int64_t)bhq * a.Lq + pos] : pos;
     __bf16* op = a.out + ((int64_t)bhq * a.Lq + orow) * kD;
 #pragma unroll
@@ -344,6 +411,17 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   const int B = a.B;
   const int Nq = ceil_div(a.q.L, B), Nk = ceil_div(a.k.L, B);
   if (BHq == 0 || Nq == 0) return BASA_OK;
+  const size_t lds = (size_t)kRingBytes + (size_t)Nk * 4 + kWaves * 4;
+  {
+    int dev = 0, max_lds = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute(shared memory per block)");
+    if (lds > (size_t)max_lds) {
+      set_error("attention needs %zu bytes of LDS for %d key blocks, the device offers %d", lds, Nk, max_lds);
+      return BASA_ERR_UNSUPPORTED;
+    }
+  }
   char* ws = reinterpret_cast<char*>(a.ws);
   uint4* Qs = reinterpret_cast<uint4*>(ws);
   uint4* Kt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B));
@@ -366,14 +444,21 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.out = reinterpret_cast<__bf16*>(a.out); m.lse = a.lse;
   m.Nq = Nq; m.Nk = Nk; m.Lq = a.q.L; m.Lk = a.k.L;
   m.group = a.q.heads / a.k.heads;
-  m.total_blocks = BHq * Nq;
+  m.wgs_per_head = ceil_div(Nq * B, kQueriesPerWg);
+  m.total_wgs = BHq * m.wgs_per_head;
   m.scale_log2e = 1.4426950408889634f / sqrtf((float)kD);
-  const size_t lds = 2 * kStageBytes;
   ProfScope prof(K_ATTN, st);
+  hipError_t e;
   if (B == 128) {
-    hipLaunchKernelGGL((attn_mfma_kernel<128>), dim3(m.total_blocks), dim3(256), lds, st, m);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<128>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
+    hipLaunchKernelGGL((attn_mfma_kernel<128>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
   } else {
-    hipLaunchKernelGGL((attn_mfma_kernel<64>), dim3(m.total_blocks), dim3(128), lds, st, m);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<64>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
+    hipLaunchKernelGGL((attn_mfma_kernel<64>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
   }
   BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
   return BASA_OK;
