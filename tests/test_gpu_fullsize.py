@@ -1,0 +1,108 @@
+"""GPU parity at the benchmark's full sizes (configurations 1-4), in the launch configuration
+bench.py times.  Selection (permutations, logits, block mask) is compared with the oracle on
+every head; attention output is compared on sampled (head, query block) units, which the
+oracle computes one by one."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import basa_oracle as o
+from paper_2605_19726_amd import binding as bd
+from paper_2605_19726_amd import synth
+from parity_util import check_output, mask_report, np64, unpack_mask
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+UNITS_PER_CONFIG = 64
+
+
+def _sample_units(w, rng):
+    """(head, query block) units: block 0 and the last (possibly ragged) block of some heads,
+    one unit per KV group, the rest random."""
+    n_q = w.n_blocks
+    group = w.heads_q // w.heads_kv
+    units = {(0, 0), (0, n_q - 1), (w.heads_q - 1, n_q - 1)}
+    for hk in range(w.heads_kv):
+        units.add((hk * group + int(rng.integers(group)), int(rng.integers(n_q))))
+    heads = rng.choice(w.heads_q, size=min(8, w.heads_q), replace=False)
+    while len(units) < UNITS_PER_CONFIG:
+        units.add((int(rng.choice(heads)), int(rng.integers(n_q))))
+    return sorted(units)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_full_size_selection_and_attention(cfg):
+    w = synth.CONFIGS[cfg]
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    group = w.heads_q // w.heads_kv
+    rng = np.random.default_rng(1000 + cfg)
+    units = _sample_units(w, rng)
+    unit_heads = sorted({h for h, _ in units})
+
+    sels = {s: bd.basa_select(Q, K, w.block, s, want_scores=(s == w.sparsities[0])) for s in w.sparsities}
+    outs = {}
+    for s, sel in sels.items():
+        outs[s] = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+    torch.cuda.synchronize()
+    s0 = w.sparsities[0]
+    scores = sels[s0].scores
+    masks = {s: unpack_mask(sel.mask_bits, sel.n_k) for s, sel in sels.items()}
+
+    stats = dict(dontcare=0, max_logit_err=0.0, max_abs=0.0, max_rel=0.0)
+    k_cache = {}
+    for h in range(w.heads_q):
+        hk = h // group
+        q = np64(Q[0, h])
+        if hk not in k_cache:
+            k_cache.clear()
+            k_cache[hk] = np64(K[0, hk])
+        k = k_cache[hk]
+        base = o.select(q, k, w.block, s0)          # permutations, statistics, logits: sparsity-free
+        assert np.array_equal(sels[s0].perm_q[0, h].cpu().numpy(), base["perm_q"]), f"perm_q head {h}"
+        assert np.array_equal(sels[s0].perm_k[0, hk].cpu().numpy(), base["perm_k"]), f"perm_k head {hk}"
+        err = np.abs(scores[0, h].cpu().numpy().astype(np.float64) - base["logits"]).max()
+        scale = max(1.0, np.abs(base["logits"]).max())
+        stats["max_logit_err"] = max(stats["max_logit_err"], err / scale)
+        assert err <= 1e-5 * scale, f"head {h}: logits off by {err:.3e} (scale {scale:.2f})"
+        refs = {}
+        for s in w.sparsities:
+            ref = dict(base)
+            ref["kappa"] = o.kappa_from_sparsity(base["m"].shape[1], s)
+            ref.update(o.select_top_kappa(base["m"], ref["kappa"]))
+            bad, dc = mask_report(masks[s][0, h], ref)
+            stats["dontcare"] += dc - ref["mask"].shape[0]
+            assert bad == 0, f"cfg{cfg} s={s} head {h}: {bad} mask mismatches outside the don't-care band"
+            assert (sels[s].row_count[0, h].cpu().numpy() == ref["kappa"]).all()
+            refs[s] = ref
+        if h in unit_heads:
+            v = np64(V[0, hk])
+            for s in w.sparsities:
+                cols_gpu = sels[s].row_cols[0, h].cpu().numpy().astype(np.int64)
+                out_h = np64(outs[s][0, h])
+                for (hh, g) in units:
+                    if hh != h:
+                        continue
+                    # the attention kernel is checked on the block list it was given (equal to the
+                    # oracle's except inside the don't-care band, which the mask check above covers)
+                    rows, O_ref, _ = o.sparse_attention_block(q, k, v, base["perm_q"], base["perm_k"], g,
+                                                              cols_gpu[g], w.block)
+                    ma, rl = check_output(out_h[rows], O_ref, True, f"cfg{cfg} s={s} unit ({h},{g})")
+                    stats["max_abs"] = max(stats["max_abs"], ma)
+                    stats["max_rel"] = max(stats["max_rel"], rl)
+    print(f"\n[cfg{cfg}] units={len(units)} dontcare_blocks={stats['dontcare']} "
+          f"max_rel_logit_err={stats['max_logit_err']:.2e} out_max_abs={stats['max_abs']:.2e} "
+          f"out_max_relL2={stats['max_rel']:.2e}")
+
+
+def test_full_size_dense_entry_sampled():
+    """Dense baseline at the largest configuration, checked on sampled query blocks of one head."""
+    w = synth.CONFIGS[4]
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    out = bd.basa_dense_attn(Q, K, V, w.block)
+    torch.cuda.synchronize()
+    h = 5
+    q, k, v = np64(Q[0, h]), np64(K[0, h]), np64(V[0, h])
+    for g in (0, 511, w.n_blocks - 1):
+        rows = np.arange(g * w.block, (g + 1) * w.block)
+        ref = o.dense_attention(q[rows], k, v)
+        check_output(np64(out[0, h, rows]), ref, True, f"dense block {g}")
