@@ -30,6 +30,9 @@ from paper_2605_19726_amd import synth           # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# plain-copy calibration (profiles/attn_and_select_cfg4_s50.md); only valid for the workload it names.
+MEASURED_TRAFFIC_BYTES = {("cfg4_dlm_128k", 0.5): 220.6e9}
 
 
 def executed_flops(w, kappa):
@@ -190,6 +193,9 @@ def main():
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain 4 GiB device copies: the known-size kernel against which "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -200,6 +206,14 @@ def main():
         sys.exit(2)
     bd.load()
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.float32, device=dev)      # 4 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
     w = synth.CONFIGS[args.config]
     Q, K, V = synth.make_qkv(w, device=dev)
     res, pipe = measure(w, args.sparsity, Q, K, V, args.steps, args.warmup,
@@ -221,7 +235,8 @@ def main():
         "dense_tflops": res["dense_tflops"],
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": (achieved / PEAK_BF16_TFLOPS) if achieved else None, "traffic": None,
+                     "frac": (achieved / PEAK_BF16_TFLOPS) if achieved else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.sparsity)),
                      "avg_launch_ms": attn_ms},
         "roofline_select": {"stage": "basa_select (all kernels)", "bound": "hbm",
                             "achieved": res["selection_gbs_total"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
