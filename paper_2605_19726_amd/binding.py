@@ -13,7 +13,8 @@ from typing import Optional
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbasa.so")
+# BASA_LIB_PATH overrides the in-tree library (e.g. to try a differently built libbasa.so)
+_LIB_PATH = os.environ.get("BASA_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbasa.so")
 _lib = None
 
 BASA_OK = 0

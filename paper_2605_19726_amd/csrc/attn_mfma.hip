@@ -30,8 +30,8 @@
 // 8*(e/4) + 4h + e%4 of the group, which is the key order inside a Vt chunk pair.
 // The running max is refreshed lazily: the accumulators are rescaled only when some
 // query's tile max exceeds its running max by more than 2^8, so the common iteration
-// touches O only through MFMA.  K/V tiles go through a 4-stage LDS ring (tile t+3 is in
-// flight while tile t is used); one workgroup barrier per tile.
+// touches O only through MFMA.  K/V tiles go through a 4-stage LDS ring used as two slots of
+// two tiles: one pair is computed while the next pair lands; one workgroup barrier per pair.
 #include "common.hpp"
 
 namespace basa {
@@ -316,7 +316,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   // prologue: tiles 0..2 into stages 0..2 (past the end: the last tile again, never read)
   issue_tile(tile_of(0), 0);
   issue_tile(tile_of(1), 1);
-  issue_tile(tile_of(2), 2);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[8];
@@ -348,30 +347,46 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   // "at most 2 tiles of my loads outstanding" means my part of tile t has landed; the barrier
   // then says everyone's part has, and that everyone is done with tile t-1, whose stage the
   // next load overwrites.
-  // The union entries needed by the next iteration (which tile to compute, which to fetch) are
-  // read from LDS at the top of an iteration and turned into scalars at its end, so their
-  // latency hides behind the tile's arithmetic.
-  uint32_t e_cur = entry_of(0);
-  for (int t = 0; t < n_tiles - 1; ++t) {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLoadsPerWave) : "memory");
-    __syncthreads();
-    const int t_fetch = min(t + 3, n_tiles - 1);
-    const uint32_t raw_next = seq[(t + 1) / TPB];
-    const uint32_t raw_fetch = seq[t_fetch / TPB];
-    if (e_cur & my_bit)
-      process_tile<false>(st, qf, smem + (t & (kStages - 1)) * kStageBytes, kaddr, vaddr, c, kTileKeys, h);
-    // stage (t+3)%4 held tile t-1: every wave finished it before the barrier above
-    const int fetch_block = __builtin_amdgcn_readfirstlane((int)raw_fetch) & 0xffffff;
-    issue_tile(fetch_block * TPB + (t_fetch % TPB), (t + 3) & (kStages - 1));
-    e_cur = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_next);
-  }
-  {
-    const int t = n_tiles - 1;
+  // Tiles travel in PAIRS: ring stages {0,1} and {2,3} form two slots of two tiles, and the
+  // workgroup meets at one barrier per pair (half as many barriers, half the skew cost).
+  // Iteration p computes tiles 2p, 2p+1 from slot p%2 while tiles 2p+2, 2p+3 land in the other
+  // slot; their loads are issued right after the barrier, which also says that every wave is
+  // done with that other slot (pair p-1).  The union entries of later tiles are read from LDS
+  // early and turned into scalars late, so their latency hides behind the arithmetic.
+  uint32_t e_a = entry_of(0);
+  uint32_t e_b = entry_of(min(1, n_tiles - 1));
+  int t = 0;
+  for (; t + 2 < n_tiles; t += 2) {          // pairs that do not contain the last tile
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
-    if (e_cur & my_bit)
-      process_tile<true>(st, qf, smem + (t & (kStages - 1)) * kStageBytes, kaddr, vaddr, c, nvalid, h);
+    const int tf0 = min(t + 2, n_tiles - 1), tf1 = min(t + 3, n_tiles - 1);
+    const uint32_t raw_f0 = seq[tf0 / TPB], raw_f1 = seq[tf1 / TPB];
+    const int slot_next = ((t >> 1) + 1) & 1;
+    {
+      const int b0 = __builtin_amdgcn_readfirstlane((int)raw_f0) & 0xffffff;
+      const int b1 = __builtin_amdgcn_readfirstlane((int)raw_f1) & 0xffffff;
+      issue_tile(b0 * TPB + (tf0 % TPB), 2 * slot_next);
+      issue_tile(b1 * TPB + (tf1 % TPB), 2 * slot_next + 1);
+    }
+    const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
+    if (e_a & my_bit) process_tile<false>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
+    if (e_b & my_bit) process_tile<false>(st, qf, slot + kStageBytes, kaddr, vaddr, c, kTileKeys, h);
+    e_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f0);
+    e_b = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f1);
+  }
+  {
+    // the last pair: one or two tiles, the very last one possibly ragged
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
+    if (t + 1 < n_tiles) {
+      if (e_a & my_bit) process_tile<false>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
+      const int nvalid = a.Lk - ((int)(e_b & 0xffffffu) * TPB + ((t + 1) % TPB)) * kTileKeys;
+      if (e_b & my_bit) process_tile<true>(st, qf, slot + kStageBytes, kaddr, vaddr, c, nvalid, h);
+    } else {
+      const int nvalid = a.Lk - ((int)(e_a & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
+      if (e_a & my_bit) process_tile<true>(st, qf, slot, kaddr, vaddr, c, nvalid, h);
+    }
   }
 
   // ---- epilogue: normalise, scatter rows to their original positions
