@@ -146,7 +146,7 @@ SelectWs carve_select(const basa_tensor* q, const basa_tensor* k, const basa_par
   SelectWs w;
   size_t o = 0;
   w.sort_off = o;
-  o += sort_workspace_bytes(BHq > BHk ? BHq : BHk, q->L > k->L ? q->L : k->L);
+  o += sort_workspace_bytes(BHq + BHk, q->L > k->L ? q->L : k->L);   // Q and K may be sorted together
   w.featq_off = o; o += align_up((size_t)BHq * Nq * 3 * q->d * sizeof(float), 256);
   w.featk_off = o; o += align_up((size_t)BHk * Nk * 3 * k->d * sizeof(float), 256);
   w.scores_off = o; o += align_up((size_t)BHq * Nq * Nk * sizeof(float), 256);
@@ -260,15 +260,26 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
 
   const bool sort_q = p->sort == BASA_SORT_Q || p->sort == BASA_SORT_QK;
   const bool sort_k = p->sort == BASA_SORT_K || p->sort == BASA_SORT_QK;
-  if (sort_q) s = launch_norm_sort(qv, p->window, perm_q, nullptr, sort_ws, st);
-  else s = launch_iota_perm(perm_q, BHq, q->L, st);
-  if (s != BASA_OK) return s;
-  if (sort_k) s = launch_norm_sort(kv, p->window, perm_k, nullptr, sort_ws, st);
-  else s = launch_iota_perm(perm_k, BHk, k->L, st);
-  if (s != BASA_OK) return s;
-
-  if ((s = launch_block_stats(qv, sort_q ? perm_q : nullptr, B, nullptr, nullptr, featq, 1, p->beta, st)) != BASA_OK) return s;
-  if ((s = launch_block_stats(kv, sort_k ? perm_k : nullptr, B, nullptr, nullptr, featk, 0, p->beta, st)) != BASA_OK) return s;
+  const bool same_len = q->L == k->L;       // then Q and K share every launch
+  if (sort_q && sort_k && same_len) {
+    s = launch_norm_sort2(qv, kv, p->window, perm_q, perm_k, sort_ws, st);
+    if (s != BASA_OK) return s;
+  } else {
+    if (sort_q) s = launch_norm_sort(qv, p->window, perm_q, nullptr, sort_ws, st);
+    else s = launch_iota_perm(perm_q, BHq, q->L, st);
+    if (s != BASA_OK) return s;
+    if (sort_k) s = launch_norm_sort(kv, p->window, perm_k, nullptr, sort_ws, st);
+    else s = launch_iota_perm(perm_k, BHk, k->L, st);
+    if (s != BASA_OK) return s;
+  }
+  const int32_t* pq = sort_q ? perm_q : nullptr;
+  const int32_t* pk = sort_k ? perm_k : nullptr;
+  if (same_len) {
+    if ((s = launch_select_features(qv, pq, featq, kv, pk, featk, B, p->beta, st)) != BASA_OK) return s;
+  } else {
+    if ((s = launch_block_stats(qv, pq, B, nullptr, nullptr, featq, 1, p->beta, st)) != BASA_OK) return s;
+    if ((s = launch_block_stats(kv, pk, B, nullptr, nullptr, featk, 0, p->beta, st)) != BASA_OK) return s;
+  }
   const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
   if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
   return launch_row_select(sc, BHq * Nq, Nk, kappa, mask_bits, row_count, row_cols, row_mass, st);

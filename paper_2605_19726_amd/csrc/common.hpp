@@ -57,6 +57,9 @@ struct ProfScope {
 size_t sort_workspace_bytes(int BH, int L);
 basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
                              void* ws, hipStream_t st);
+// Two tensors of identical L, d and dtype through the same launches (ws sized for both).
+basa_status launch_norm_sort2(const TensorView& q, const TensorView& k, int window, int32_t* perm_q,
+                              int32_t* perm_k, void* ws, hipStream_t st);
 basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 
 // Block statistics.  Any of the outputs may be null.
@@ -67,6 +70,11 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
                                float* var, float* feat, int feat_is_query, float beta,
                                hipStream_t st);
+
+// Selection features of Q (query side) and K (key side), identical L / d / dtype, in one launch.
+basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, float* feat_q,
+                                   const TensorView& k, const int32_t* perm_k, float* feat_k, int B,
+                                   float beta, hipStream_t st);
 
 // Block logits: scores[BHq][Nq][Nk] = featQ . featK over `kdim` features.
 basa_status launch_block_scores(const float* featQ, const float* featK, float* scores, int BHq,

@@ -27,12 +27,19 @@ __global__ __launch_bounds__(256) void block_scores_kernel(const float* __restri
                                                            const float* __restrict__ featK,
                                                            float* __restrict__ scores, int group,
                                                            int Nq, int Nk, int K, int S) {
-  const int bhq = blockIdx.z;
+  // consecutive workgroup ids go round-robin over the 8 XCDs: hand each XCD a contiguous range
+  // of (head, tile) so that a head's features are pulled into one L2 only
+  const int total = gridDim.x, tiles_x = (Nk + 127) >> 7, tiles_y = (Nq + 127) >> 7;
+  int logical = blockIdx.x;
+  if ((total & 7) == 0) logical = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  const int bhq = logical / (tiles_x * tiles_y);
+  const int rem = logical - bhq * (tiles_x * tiles_y);
+  const int ty = rem / tiles_x, tx = rem - ty * tiles_x;
   const int bhk = bhq / group;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int li = lane & 31, h = lane >> 5;
-  const int row0 = blockIdx.y * 128 + (wave >> 1) * 64;
-  const int col0 = blockIdx.x * 128 + (wave & 1) * 64;
+  const int row0 = ty * 128 + (wave >> 1) * 64;
+  const int col0 = tx * 128 + (wave & 1) * 64;
   if (row0 >= Nq || col0 >= Nk) return;
 
   const int half = K >> 1;
@@ -42,12 +49,15 @@ __global__ __launch_bounds__(256) void block_scores_kernel(const float* __restri
   const float* b1 = featK + ((int64_t)bhk * Nk + min(col0 + 32 + li, Nk - 1)) * S + h * half;
 
   floatx16 c00 = {0}, c01 = {0}, c10 = {0}, c11 = {0};
-#pragma unroll 2
+  // operands of step k+4 are in flight while the 16 MFMAs of step k run
+  float4 va0 = *reinterpret_cast<const float4*>(a0), va1 = *reinterpret_cast<const float4*>(a1);
+  float4 vb0 = *reinterpret_cast<const float4*>(b0), vb1 = *reinterpret_cast<const float4*>(b1);
   for (int k = 0; k < half; k += 4) {
-    const float4 va0 = *reinterpret_cast<const float4*>(a0 + k);
-    const float4 va1 = *reinterpret_cast<const float4*>(a1 + k);
-    const float4 vb0 = *reinterpret_cast<const float4*>(b0 + k);
-    const float4 vb1 = *reinterpret_cast<const float4*>(b1 + k);
+    const int kn = (k + 4 < half) ? k + 4 : k;
+    const float4 na0 = *reinterpret_cast<const float4*>(a0 + kn);
+    const float4 na1 = *reinterpret_cast<const float4*>(a1 + kn);
+    const float4 nb0 = *reinterpret_cast<const float4*>(b0 + kn);
+    const float4 nb1 = *reinterpret_cast<const float4*>(b1 + kn);
     const float xa0[4] = {va0.x, va0.y, va0.z, va0.w};
     const float xa1[4] = {va1.x, va1.y, va1.z, va1.w};
     const float xb0[4] = {vb0.x, vb0.y, vb0.z, vb0.w};
@@ -59,6 +69,7 @@ __global__ __launch_bounds__(256) void block_scores_kernel(const float* __restri
       c10 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb0[e], c10, 0, 0, 0);
       c11 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb1[e], c11, 0, 0, 0);
     }
+    va0 = na0; va1 = na1; vb0 = nb0; vb1 = nb1;
   }
   // accumulator register r of lane (j, h) holds row 8*(r/4) + 4*h + r%4, column j
   float* out = scores + (int64_t)bhq * Nq * Nk;
@@ -170,7 +181,7 @@ basa_status launch_block_scores(const float* featQ, const float* featK, float* s
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
                                 hipStream_t st) {
   if (BHq == 0 || Nq == 0 || Nk == 0) return BASA_OK;
-  dim3 grid(ceil_div(Nk, 128), ceil_div(Nq, 128), BHq);
+  dim3 grid(ceil_div(Nk, 128) * ceil_div(Nq, 128) * BHq);
   ProfScope prof(K_SCORES, st);
   hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), 0, st, featQ, featK, scores, group, Nq,
                      Nk, kdim_used, feat_stride);

@@ -19,16 +19,21 @@ constexpr int kMergeChunk = kSortThreads * kMergeItems;   // 2048 outputs per wo
 // ---------------------------------------------------------------------------------
 // Keys.  A row of d elements is 16-byte chunks spread over LPR adjacent lanes.
 // ---------------------------------------------------------------------------------
+// Up to two tensors of the same L, d and dtype are handled by one launch: rows blockIdx.y <
+// BH0 belong to x0, the rest to x1; packed words and permutations of x1 follow those of x0.
 template <bool kBf16, int kD>
-__global__ __launch_bounds__(256) void norm_keys_kernel(TensorView x, uint64_t* __restrict__ packed,
+__global__ __launch_bounds__(256) void norm_keys_kernel(TensorView x0, TensorView x1, int BH0,
+                                                        uint64_t* __restrict__ packed,
                                                         float* __restrict__ keys_out) {
   constexpr int kElem = kBf16 ? 2 : 4;
   constexpr int LPR = kD * kElem / 16;          // lanes per row: 8, 16 or 32
   constexpr int kRowsPerIter = 256 / LPR;
   constexpr int kIters = 8;
   const int bh = blockIdx.y;
+  const bool second = bh >= BH0;
+  const TensorView& x = second ? x1 : x0;
   const int L = x.L;
-  const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * kElem;
+  const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(second ? bh - BH0 : bh) * kElem;
   const int sub = threadIdx.x % LPR;
   const int rig = threadIdx.x / LPR;
   const int row0 = blockIdx.x * (kRowsPerIter * kIters) + rig;
@@ -69,7 +74,8 @@ struct SegGeom {
 
 __global__ __launch_bounds__(kSortThreads) void tile_sort_kernel(const uint64_t* __restrict__ in,
                                                                  uint64_t* __restrict__ out,
-                                                                 int32_t* __restrict__ perm_out,
+                                                                 int32_t* __restrict__ perm0,
+                                                                 int32_t* __restrict__ perm1, int BH0,
                                                                  SegGeom g) {
   __shared__ uint64_t buf[kTile];
   const int bh = blockIdx.y;
@@ -80,6 +86,7 @@ __global__ __launch_bounds__(kSortThreads) void tile_sort_kernel(const uint64_t*
   if (start >= seg_end) return;
   const int n = min(kTile, seg_end - start);
   const int64_t hb = (int64_t)bh * g.L;
+  int32_t* perm_out = bh < BH0 ? perm0 : (perm1 ? perm1 - (int64_t)BH0 * g.L : nullptr);
 
   for (int i = threadIdx.x; i < kTile; i += kSortThreads)
     buf[i] = (i < n) ? in[hb + start + i] : ~0ull;
@@ -120,7 +127,8 @@ __device__ __forceinline__ int merge_path(const uint64_t* A, int na, const uint6
 
 __global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t* __restrict__ in,
                                                                   uint64_t* __restrict__ out,
-                                                                  int32_t* __restrict__ perm_out,
+                                                                  int32_t* __restrict__ perm0,
+                                                                  int32_t* __restrict__ perm1, int BH0,
                                                                   SegGeom g, int run,
                                                                   int chunks_per_pair, int pairs_per_seg) {
   __shared__ uint64_t buf[kMergeChunk];
@@ -141,6 +149,7 @@ __global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t
   if (diag0 >= total) return;
   const int diag1 = min(diag0 + kMergeChunk, total);
   const int64_t hb = (int64_t)bh * g.L;
+  int32_t* perm_out = bh < BH0 ? perm0 : (perm1 ? perm1 - (int64_t)BH0 * g.L : nullptr);
   const uint64_t* A = in + hb + a0;
   const uint64_t* Bv = in + hb + b0;
 
@@ -188,25 +197,28 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st) {
   return BASA_OK;
 }
 
-basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
-                             void* ws, hipStream_t st) {
-  const int BH = x.batch * x.heads, L = x.L;
+// Sort one tensor (x1 == nullptr) or two tensors of identical L, d and dtype in the same launches.
+static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, int window, int32_t* perm0,
+                                  int32_t* perm1, float* keys_out, void* ws, hipStream_t st) {
+  const int BH0 = x0.batch * x0.heads, BH1 = x1 ? x1->batch * x1->heads : 0, L = x0.L;
+  const int BH = BH0 + BH1;
   if (BH == 0 || L == 0) return BASA_OK;
   uint64_t* buf0 = reinterpret_cast<uint64_t*>(ws);
   uint64_t* buf1 = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(ws) +
                                                align_up((size_t)BH * L * sizeof(uint64_t), 256));
-  const bool bf16 = x.dtype == BASA_BF16;
+  const TensorView& xb = x1 ? *x1 : x0;
+  const bool bf16 = x0.dtype == BASA_BF16;
   const int elem = bf16 ? 2 : 4;
-  const int lpr = x.d * elem / 16;
+  const int lpr = x0.d * elem / 16;
   const int rows_per_wg = (256 / lpr) * 8;
   dim3 kgrid(ceil_div(L, rows_per_wg), BH);
   {
   ProfScope prof(K_NORM_KEYS, st);
 #define BASA_KEYS(BF, D) \
-  hipLaunchKernelGGL((norm_keys_kernel<BF, D>), kgrid, dim3(256), 0, st, x, buf0, keys_out)
-  if (bf16 && x.d == 128) BASA_KEYS(true, 128);
-  else if (bf16 && x.d == 64) BASA_KEYS(true, 64);
-  else if (!bf16 && x.d == 128) BASA_KEYS(false, 128);
+  hipLaunchKernelGGL((norm_keys_kernel<BF, D>), kgrid, dim3(256), 0, st, x0, xb, BH0, buf0, keys_out)
+  if (bf16 && x0.d == 128) BASA_KEYS(true, 128);
+  else if (bf16 && x0.d == 64) BASA_KEYS(true, 64);
+  else if (!bf16 && x0.d == 128) BASA_KEYS(false, 128);
   else BASA_KEYS(false, 64);
 #undef BASA_KEYS
   BASA_HIP_CHECK_LAUNCH("norm_keys_kernel");
@@ -221,7 +233,7 @@ basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, flo
   {
   ProfScope prof(K_TILE_SORT, st);
   hipLaunchKernelGGL(tile_sort_kernel, dim3(g.segs * g.tiles_per_seg, BH), dim3(kSortThreads), 0, st,
-                     buf0, buf1, single ? perm : nullptr, g);
+                     buf0, buf1, single ? perm0 : nullptr, single ? perm1 : nullptr, BH0, g);
   BASA_HIP_CHECK_LAUNCH("tile_sort_kernel");
   }
   if (single) return BASA_OK;
@@ -234,12 +246,22 @@ basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, flo
     const int chunks_per_pair = ceil_div(2 * run, kMergeChunk);
     ProfScope prof(K_MERGE, st);
     hipLaunchKernelGGL(merge_pass_kernel, dim3(g.segs * pairs_per_seg * chunks_per_pair, BH),
-                       dim3(kSortThreads), 0, st, src, dst, last ? perm : nullptr, g, run,
-                       chunks_per_pair, pairs_per_seg);
+                       dim3(kSortThreads), 0, st, src, dst, last ? perm0 : nullptr, last ? perm1 : nullptr,
+                       BH0, g, run, chunks_per_pair, pairs_per_seg);
     BASA_HIP_CHECK_LAUNCH("merge_pass_kernel");
     uint64_t* t = src; src = dst; dst = t;
   }
   return BASA_OK;
+}
+
+basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
+                             void* ws, hipStream_t st) {
+  return norm_sort_impl(x, nullptr, window, perm, nullptr, keys_out, ws, st);
+}
+
+basa_status launch_norm_sort2(const TensorView& q, const TensorView& k, int window, int32_t* perm_q,
+                              int32_t* perm_k, void* ws, hipStream_t st) {
+  return norm_sort_impl(q, &k, window, perm_q, perm_k, nullptr, ws, st);
 }
 
 }  // namespace basa

@@ -11,12 +11,19 @@
 namespace basa {
 namespace {
 
+// One tensor's share of a launch.  Up to two tensors of identical L, d and dtype go through the
+// same launch: rows blockIdx.y < BH0 belong to job 0, the rest to job 1.
+struct StatsJob {
+  TensorView x;
+  const int32_t* perm;
+  float* mean_out;
+  float* var_out;
+  float* feat_out;
+  int feat_is_query;
+};
+
 template <bool kBf16, int kD, int kB>
-__global__ __launch_bounds__(256) void block_stats_kernel(TensorView x, const int32_t* __restrict__ perm,
-                                                          float* __restrict__ mean_out,
-                                                          float* __restrict__ var_out,
-                                                          float* __restrict__ feat_out,
-                                                          int feat_is_query, float beta) {
+__global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob j1, int BH0, float beta) {
   constexpr int kElem = kBf16 ? 2 : 4;
   constexpr int LPR = kD * kElem / 16;       // lanes per row
   constexpr int RPI = 256 / LPR;             // rows per iteration
@@ -26,7 +33,15 @@ __global__ __launch_bounds__(256) void block_stats_kernel(TensorView x, const in
   __shared__ float red[RPI][kD];
   __shared__ float mean_s[kD];
 
-  const int bh = blockIdx.y, g = blockIdx.x;
+  const bool second = (int)blockIdx.y >= BH0;
+  const StatsJob& job = second ? j1 : j0;
+  const TensorView& x = job.x;
+  const int32_t* perm = job.perm;
+  float* mean_out = job.mean_out;
+  float* var_out = job.var_out;
+  float* feat_out = job.feat_out;
+  const int feat_is_query = job.feat_is_query;
+  const int bh = second ? blockIdx.y - BH0 : blockIdx.y, g = blockIdx.x;
   const int L = x.L;
   const int N = (L + kB - 1) / kB;
   const int sub = threadIdx.x % LPR, rig = threadIdx.x / LPR;
@@ -104,18 +119,18 @@ __global__ __launch_bounds__(256) void block_stats_kernel(TensorView x, const in
 
 }  // namespace
 
-basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
-                               float* var, float* feat, int feat_is_query, float beta,
-                               hipStream_t st) {
-  const int BH = x.batch * x.heads;
+static basa_status block_stats_impl(const StatsJob& j0, const StatsJob* j1, int B, float beta, hipStream_t st) {
+  const TensorView& x = j0.x;
+  const int BH0 = x.batch * x.heads;
+  const int BH1 = j1 ? j1->x.batch * j1->x.heads : 0;
   const int N = ceil_div(x.L, B);
-  if (BH == 0 || N == 0) return BASA_OK;
-  dim3 grid(N, BH);
+  if (BH0 + BH1 == 0 || N == 0) return BASA_OK;
+  dim3 grid(N, BH0 + BH1);
   ProfScope prof(K_STATS, st);
   const bool bf = x.dtype == BASA_BF16;
-#define BASA_STATS(BF, D, BB)                                                              \
-  hipLaunchKernelGGL((block_stats_kernel<BF, D, BB>), grid, dim3(256), 0, st, x, perm, mean, \
-                     var, feat, feat_is_query, beta)
+  const StatsJob& jb = j1 ? *j1 : j0;
+#define BASA_STATS(BF, D, BB) \
+  hipLaunchKernelGGL((block_stats_kernel<BF, D, BB>), grid, dim3(256), 0, st, j0, jb, BH0, beta)
   if (bf && x.d == 128 && B == 128) BASA_STATS(true, 128, 128);
   else if (bf && x.d == 128 && B == 64) BASA_STATS(true, 128, 64);
   else if (bf && x.d == 64 && B == 128) BASA_STATS(true, 64, 128);
@@ -127,6 +142,21 @@ basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, 
 #undef BASA_STATS
   BASA_HIP_CHECK_LAUNCH("block_stats_kernel");
   return BASA_OK;
+}
+
+basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
+                               float* var, float* feat, int feat_is_query, float beta,
+                               hipStream_t st) {
+  const StatsJob j{x, perm, mean, var, feat, feat_is_query};
+  return block_stats_impl(j, nullptr, B, beta, st);
+}
+
+basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, float* feat_q,
+                                   const TensorView& k, const int32_t* perm_k, float* feat_k, int B,
+                                   float beta, hipStream_t st) {
+  const StatsJob jq{q, perm_q, nullptr, nullptr, feat_q, 1};
+  const StatsJob jk{k, perm_k, nullptr, nullptr, feat_k, 0};
+  return block_stats_impl(jq, &jk, B, beta, st);
 }
 
 }  // namespace basa
