@@ -101,6 +101,24 @@ def timed(fn, reps):
     return (time.perf_counter() - t0) / reps
 
 
+def attainable_mfma(dev, iters=60000):
+    """The bf16 matrix-core rate a bare loop of independent MFMAs sustains on this chip, with
+    constant and with pseudo-random operand values (TFLOP/s each).  Context for the roofline
+    fraction: the nominal peak is only reached while the operand bits do not toggle."""
+    out = torch.empty(1 << 17, dtype=torch.float32, device=dev)
+    rates = {}
+    for name, rnd in (("constant_operands", False), ("random_operands", True)):
+        bd.basa_calibrate_mfma(rnd, 2000, out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = bd.basa_calibrate_mfma(rnd, iters, out)
+        e1.record()
+        e1.synchronize()
+        rates[name] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return rates
+
+
 def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK):
     pipe = Pipeline(w, sparsity, Q, K, V, beta, sort)
     for _ in range(warmup):
@@ -245,6 +263,10 @@ def main():
                             "bytes": res["selection_bytes"]},
         "kernel_ms_per_step": res["kernel_ms_per_step"],
     }
+    if achieved:
+        rates = attainable_mfma(dev)
+        line["roofline"]["mfma_loop_tflops"] = rates
+        line["roofline"]["frac_of_random_operand_loop"] = achieved / rates["random_operands"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, args.sparsity, Q, K, V, pipe)
     if args.sweep:

@@ -169,6 +169,21 @@ int32_t basa_profile_kernel_count(void);
 const char* basa_profile_kernel_name(int32_t id);
 basa_status basa_profile_read(double* total_ms /*host*/, int32_t* launches /*host*/, int32_t n);
 
+/*
+ * Calibration aid for benchmarks (no part of the method): enqueues a kernel that issues
+ * `iters` x 32 independent bf16 32x32x16 matrix-core instructions per wave on register
+ * operands, 8 waves per compute unit, and nothing else.  random_operands != 0: the operand
+ * fragments hold pseudo-random values and change from one instruction to the next, as they
+ * do in real work; 0: one constant everywhere.  The rate this loop reaches is the rate the
+ * chip sustains for such operands (its power management included).
+ *   out        device, at least 131072 floats (scratch the kernel writes its sums to)
+ *   out_elems  floats `out` holds; too few: BASA_ERR_WORKSPACE
+ *   flops      host, nullable: receives the floating-point operations of the launch
+ * Time it with events on `stream`.
+ */
+basa_status basa_calibrate_mfma(int32_t random_operands, int32_t iters, float* out, size_t out_elems,
+                                double* flops /*host*/, void* stream);
+
 /* Library version, e.g. "basa 0.1 gfx950". */
 const char* basa_version(void);
 

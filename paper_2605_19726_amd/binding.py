@@ -26,7 +26,7 @@ EXPORTS = (
     "basa_sort_workspace_size", "basa_norm_sort", "basa_downsample", "basa_select",
     "basa_sparse_attn", "basa_dense_attn", "basa_status_string", "basa_last_error",
     "basa_version", "basa_profile_enable", "basa_profile_kernel_count", "basa_profile_kernel_name",
-    "basa_profile_read",
+    "basa_profile_read", "basa_calibrate_mfma",
 )
 
 
@@ -93,6 +93,8 @@ def load():
     lib.basa_profile_kernel_name.argtypes = [C.c_int32]
     lib.basa_profile_read.restype = C.c_int
     lib.basa_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32), C.c_int32]
+    lib.basa_calibrate_mfma.restype = C.c_int
+    lib.basa_calibrate_mfma.argtypes = [C.c_int32, C.c_int32, V, C.c_size_t, C.POINTER(C.c_double), V]
     _lib = lib
     return lib
 
@@ -269,3 +271,11 @@ def basa_profile_read() -> dict:
     cnt = (C.c_int32 * n)()
     _check(lib.basa_profile_read(ms, cnt, n))
     return {lib.basa_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+def basa_calibrate_mfma(random_operands: bool, iters: int, out: torch.Tensor) -> float:
+    """Enqueue the matrix-core calibration loop on the current stream; returns its flop count."""
+    flops = C.c_double(0.0)
+    _check(load().basa_calibrate_mfma(1 if random_operands else 0, int(iters), _ptr(out), out.numel(),
+                                      C.byref(flops), _stream(out)))
+    return float(flops.value)

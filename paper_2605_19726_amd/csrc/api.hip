@@ -354,4 +354,19 @@ basa_status basa_profile_read(double* total_ms, int32_t* launches, int32_t n) {
 }
 const char* basa_version(void) { return "basa 0.1 gfx950"; }
 
+basa_status basa_calibrate_mfma(int32_t random_operands, int32_t iters, float* out, size_t out_elems,
+                                double* flops, void* stream) {
+  if (!out || iters < 1 || iters > (1 << 24)) {
+    set_error("basa_calibrate_mfma: out must be a device buffer and 1 <= iters <= 2^24");
+    return BASA_ERR_INVALID_ARG;
+  }
+  if (out_elems < calib_mfma_out_elems()) {
+    set_error("basa_calibrate_mfma: out holds %zu floats, needs %zu", out_elems, calib_mfma_out_elems());
+    return BASA_ERR_WORKSPACE;
+  }
+  if (flops) *flops = calib_mfma_flops(iters);
+  const hipError_t e = launch_calib_mfma(random_operands != 0, iters, out, (hipStream_t)stream);
+  return e == hipSuccess ? BASA_OK : hip_fail(e, "basa_calibrate_mfma");
+}
+
 }  // extern "C"

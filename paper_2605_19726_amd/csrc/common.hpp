@@ -104,6 +104,11 @@ size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B
 basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st);
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st);
 
+// calibration (calib.hip): a loop of independent bf16 MFMAs on register operands
+size_t calib_mfma_out_elems();
+double calib_mfma_flops(int iters);
+hipError_t launch_calib_mfma(bool random_operands, int iters, float* out, hipStream_t stream);
+
 // ---- device helpers ------------------------------------------------------------
 #if defined(__HIPCC__)
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {

@@ -38,29 +38,62 @@ __global__ __launch_bounds__(256) void norm_keys_kernel(TensorView x0, TensorVie
   const int rig = threadIdx.x / LPR;
   const int row0 = blockIdx.x * (kRowsPerIter * kIters) + rig;
 
-  Chunk16<kBf16> c[kIters];
+  uint4 raw[kIters];
 #pragma unroll
   for (int it = 0; it < kIters; ++it) {
     int row = row0 + it * kRowsPerIter;
-    if (row < L) c[it].load(base + (int64_t)row * x.stride_l * kElem, sub);
-    else c[it].zero();
+    raw[it] = make_uint4(0u, 0u, 0u, 0u);
+    if (row < L) raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)row * x.stride_l * kElem)[sub];
+  }
+  // per-lane partial sums of the kIters rows this lane contributes to
+  double acc[kIters];
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    acc[it] = 0.0;
+    const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (kBf16) {
+        // |x| as a double, built from the 15 exponent+mantissa bits of the bf16 (the float to
+        // double conversion instruction is many times slower than these two integer ops): the
+        // high word of the double is bits << 13 plus the exponent rebias (1023-127) << 20, the
+        // low word is zero.  A zero or subnormal bf16 (exponent field 0) comes out as a value
+        // below 2^-126 instead; its square, below 2^-252, is lost against any sum that can
+        // round to a non-zero fp32 key (>= 2^-150), exactly as the true square would be.
+        const double lo = __hiloint2double((int)((__builtin_amdgcn_ubfe(w[i], 0, 15) << 13) + 0x38000000u), 0);
+        const double hi = __hiloint2double((int)((__builtin_amdgcn_ubfe(w[i], 16, 15) << 13) + 0x38000000u), 0);
+        acc[it] = fma(lo, lo, acc[it]);
+        acc[it] = fma(hi, hi, acc[it]);
+      } else {
+        const double v = (double)__uint_as_float(w[i]);
+        acc[it] = fma(v, v, acc[it]);
+      }
+    }
+  }
+  // Reduction over the LPR lanes of a row, all kIters rows at once: in the step with lane
+  // distance 2^b a lane hands the half of its partial sums that its partner keeps to the
+  // partner and halves its own set (8 -> 4 -> 2 -> 1 sums in 7 exchanges instead of 24), so
+  // that after three steps lane `sub` holds one row, iteration 4*bit0 + 2*bit1 + bit2 of sub.
+  static_assert(kIters == 8 && LPR >= 8, "the exchange pattern below is written for 8 rows");
+#pragma unroll
+  for (int b = 0; b < 3; ++b) {
+    const bool upper = (sub >> b) & 1;
+    const int n = kIters >> (b + 1);
+#pragma unroll
+    for (int i = 0; i < n; ++i) {
+      const double give = upper ? acc[i] : acc[i + n];
+      const double keep = upper ? acc[i + n] : acc[i];
+      acc[i] = keep + __shfl_xor(give, 1 << b, LPR);
+    }
   }
 #pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    double acc = 0.0;
-#pragma unroll
-    for (int e = 0; e < Chunk16<kBf16>::kElems; ++e) {
-      double v = (double)c[it].v[e];
-      acc += v * v;
-    }
-#pragma unroll
-    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, LPR);
-    int row = row0 + it * kRowsPerIter;
-    if (sub == 0 && row < L) {
-      float key = (float)acc;
-      packed[(int64_t)bh * L + row] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)row;
-      if (keys_out) keys_out[(int64_t)bh * L + row] = key;
-    }
+  for (int off = 8; off < LPR; off <<= 1) acc[0] += __shfl_xor(acc[0], off, LPR);
+  const int it_mine = 4 * (sub & 1) + (sub & 2) + ((sub >> 2) & 1);
+  const int row = row0 + it_mine * kRowsPerIter;
+  if (sub < 8 && row < L) {
+    const float key = (float)acc[0];
+    packed[(int64_t)bh * L + row] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)row;
+    if (keys_out) keys_out[(int64_t)bh * L + row] = key;
   }
 }
 

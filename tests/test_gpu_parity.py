@@ -59,6 +59,29 @@ def test_norm_sort_windowed_and_ties():
             assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), want), f"window={window}"
 
 
+def test_norm_sort_keys_zeros_subnormals_and_scales():
+    """Sort keys stay bit-identical to the oracle's when rows hold exact zeros, bf16 subnormals,
+    all-zero rows, and values spread over many binades (within what an fp64 sum adds exactly)."""
+    g = torch.Generator().manual_seed(77)
+    L, d = 4096 + 37, 128
+    x = torch.randn(L, d, generator=g)
+    x *= torch.exp2(torch.randint(-12, 13, (L, 1), generator=g).float())      # row scales 2^-12 .. 2^12
+    x *= torch.exp2(torch.randint(-4, 5, (L, d), generator=g).float())        # element scales on top
+    x[torch.rand(L, d, generator=g) < 0.3] = 0.0                               # many exact zeros
+    x[5] = 0.0
+    x[6] = 0.0
+    x[7, 3] = 1e-39                                                            # bf16 subnormal beside normals
+    x[8] = 1e-39                                                               # a row of subnormals only
+    x[9] = 3e-20                                                               # squares far below fp32 range
+    x[10] = 2.0 ** -70
+    x = x.to(torch.bfloat16).reshape(1, 1, L, d).to(DEV)
+    perm, keys = bd.basa_norm_sort(x, 128, return_keys=True)
+    torch.cuda.synchronize()
+    xn = np64(x[0, 0])
+    assert np.array_equal(keys[0, 0].cpu().numpy(), o.token_sort_keys(xn))
+    assert np.array_equal(perm[0, 0].cpu().numpy().astype(np.int64), o.norm_sort(xn))
+
+
 def test_norm_sort_strided_input():
     # heads interleaved in memory: [1, L, H, d] viewed as [1, H, L, d]
     w = C[1].scaled("strided", heads_q=3, heads_kv=3, L=5000)
