@@ -64,7 +64,8 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 
 // Block statistics.  Any of the outputs may be null.
 //   mean/var : [BH][N][d]
-//   feat     : [BH][N][3d] selection features (layout depends on `feat_is_query`):
+//   feat     : [BH][3d/4][N][4] selection features, feature k of block g at [k/4][g][k%4]
+//              (content depends on `feat_is_query`):
 //              query side (Qbar/sqrt(d), beta*VarQ/d, beta*Qbar^2/d),
 //              key side   (Kbar, Kbar^2+VarK, VarK)
 basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,

@@ -4,7 +4,9 @@
 // Scores: with the per-block features written by the pooling kernel the logit l' of a
 // block pair is a dot product, so the N_q x N_k map of a head is a small fp32 GEMM.
 // It runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32); each wave owns a 64x64
-// output tile and streams its 128 feature rows straight from L2 into registers.
+// output tile and streams the features of its 128 blocks straight from L2 into registers
+// (the features are stored four to a group, groups of consecutive blocks adjacent, so that
+// every load of a half-wave is one contiguous 512-byte run).
 //
 // Selection: one wave per row of the map.  The kappa-th largest logit is found by a
 // 32-step bisection on an order-preserving integer image of the floats (ballot +
@@ -42,22 +44,25 @@ __global__ __launch_bounds__(256) void block_scores_kernel(const float* __restri
   const int col0 = tx * 128 + (wave & 1) * 64;
   if (row0 >= Nq || col0 >= Nk) return;
 
+  // features are stored [K/4][N][4]: lane (li, h) reads the 16-byte group of its block, lanes of
+  // a half-wave read consecutive blocks (512 contiguous bytes)
   const int half = K >> 1;
-  const float* a0 = featQ + ((int64_t)bhq * Nq + min(row0 + li, Nq - 1)) * S + h * half;
-  const float* a1 = featQ + ((int64_t)bhq * Nq + min(row0 + 32 + li, Nq - 1)) * S + h * half;
-  const float* b0 = featK + ((int64_t)bhk * Nk + min(col0 + li, Nk - 1)) * S + h * half;
-  const float* b1 = featK + ((int64_t)bhk * Nk + min(col0 + 32 + li, Nk - 1)) * S + h * half;
+  const int64_t gq = (int64_t)Nq * 4, gk = (int64_t)Nk * 4;      // floats per group of 4 features
+  const float* a0 = featQ + (int64_t)bhq * Nq * S + (int64_t)(h * half >> 2) * gq + (int64_t)min(row0 + li, Nq - 1) * 4;
+  const float* a1 = featQ + (int64_t)bhq * Nq * S + (int64_t)(h * half >> 2) * gq + (int64_t)min(row0 + 32 + li, Nq - 1) * 4;
+  const float* b0 = featK + (int64_t)bhk * Nk * S + (int64_t)(h * half >> 2) * gk + (int64_t)min(col0 + li, Nk - 1) * 4;
+  const float* b1 = featK + (int64_t)bhk * Nk * S + (int64_t)(h * half >> 2) * gk + (int64_t)min(col0 + 32 + li, Nk - 1) * 4;
 
   floatx16 c00 = {0}, c01 = {0}, c10 = {0}, c11 = {0};
   // operands of step k+4 are in flight while the 16 MFMAs of step k run
   float4 va0 = *reinterpret_cast<const float4*>(a0), va1 = *reinterpret_cast<const float4*>(a1);
   float4 vb0 = *reinterpret_cast<const float4*>(b0), vb1 = *reinterpret_cast<const float4*>(b1);
   for (int k = 0; k < half; k += 4) {
-    const int kn = (k + 4 < half) ? k + 4 : k;
-    const float4 na0 = *reinterpret_cast<const float4*>(a0 + kn);
-    const float4 na1 = *reinterpret_cast<const float4*>(a1 + kn);
-    const float4 nb0 = *reinterpret_cast<const float4*>(b0 + kn);
-    const float4 nb1 = *reinterpret_cast<const float4*>(b1 + kn);
+    const int kn = ((k + 4 < half) ? k + 4 : k) >> 2;
+    const float4 na0 = *reinterpret_cast<const float4*>(a0 + kn * gq);
+    const float4 na1 = *reinterpret_cast<const float4*>(a1 + kn * gq);
+    const float4 nb0 = *reinterpret_cast<const float4*>(b0 + kn * gk);
+    const float4 nb1 = *reinterpret_cast<const float4*>(b1 + kn * gk);
     const float xa0[4] = {va0.x, va0.y, va0.z, va0.w};
     const float xa1[4] = {va1.x, va1.y, va1.z, va1.w};
     const float xb0[4] = {vb0.x, vb0.y, vb0.z, vb0.w};

@@ -103,15 +103,18 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
     if (mean_out) mean_out[o] = mean_c;
     if (var_out) var_out[o] = var_c;
     if (feat_out) {
-      float* f = feat_out + ((int64_t)bh * N + g) * (3 * kD);
+      // feature k of block g lives at [k / 4][g][k % 4]: the score kernel reads 16-byte groups of
+      // 32 consecutive blocks with one coalesced load
+      float* f = feat_out + (int64_t)bh * N * (3 * kD) + (int64_t)g * 4 + (threadIdx.x & 3);
+      const int64_t c0 = (int64_t)(threadIdx.x >> 2) * N * 4, third = (int64_t)(kD / 4) * N * 4;
       if (feat_is_query) {
-        f[threadIdx.x] = mean_c * (1.0f / sqrtf((float)kD));
-        f[kD + threadIdx.x] = beta * var_c * (1.0f / (float)kD);
-        f[2 * kD + threadIdx.x] = beta * (mean_c * mean_c) * (1.0f / (float)kD);
+        f[c0] = mean_c * (1.0f / sqrtf((float)kD));
+        f[third + c0] = beta * var_c * (1.0f / (float)kD);
+        f[2 * third + c0] = beta * (mean_c * mean_c) * (1.0f / (float)kD);
       } else {
-        f[threadIdx.x] = mean_c;
-        f[kD + threadIdx.x] = mean_c * mean_c + var_c;
-        f[2 * kD + threadIdx.x] = var_c;
+        f[c0] = mean_c;
+        f[third + c0] = mean_c * mean_c + var_c;
+        f[2 * third + c0] = var_c;
       }
     }
   }
