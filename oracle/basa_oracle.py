@@ -171,6 +171,38 @@ def select_top_kappa(m: np.ndarray, kappa: int):
     return dict(mask=mask, cols=cols, mass=mass, theta=theta, next=nxt)
 
 
+def select_top_mass(m: np.ndarray, mass_target: float, min_keep: int = 1, cap: int | None = None):
+    """Cumulative-mass reading of "the mask is built from m under a computational budget"
+    (Sec. 3.1, sentence after Eq. 2): in every row keep the FEWEST key blocks, taken in order
+    of decreasing m' (equal values: lower index first), whose m' sum to at least mass_target;
+    never fewer than min_keep nor more than cap blocks (cap None: no cap).
+
+    Returns dict(mask [N_q, N_k] bool, count [N_q] int64, cols: list of ascending int64 arrays,
+    mass [N_q], cum [N_q, N_k]: cum[r, k-1] = sum of the k largest m' of row r).
+    """
+    n_q, n_k = m.shape
+    cap = n_k if cap is None else min(int(cap), n_k)
+    min_keep = max(1, min(int(min_keep), cap))
+    mask = np.zeros((n_q, n_k), dtype=bool)
+    count = np.zeros(n_q, dtype=np.int64)
+    mass = np.zeros(n_q)
+    cum = np.zeros((n_q, n_k))
+    cols = []
+    for r in range(n_q):
+        order = np.argsort(-m[r], kind="stable")      # descending, ties -> lower index
+        c = np.cumsum(m[r, order])
+        cum[r] = c
+        reached = np.nonzero(c >= mass_target)[0]
+        k = int(reached[0]) + 1 if reached.size else n_k
+        k = max(min_keep, min(k, cap))
+        keep = order[:k]
+        mask[r, keep] = True
+        count[r] = k
+        cols.append(np.sort(keep))
+        mass[r] = c[k - 1]
+    return dict(mask=mask, count=count, cols=cols, mass=mass, cum=cum)
+
+
 # --------------------------------------------------------------------------- #
 # Attention (Eq. 1; Sec. 2 block-sparse attention; Alg. 1 step 12)
 # --------------------------------------------------------------------------- #
@@ -242,10 +274,11 @@ def sparse_attention(Q, K, V, perm_q, perm_k, cols, B: int, return_lse: bool = F
 # The whole operator (Alg. 1)
 # --------------------------------------------------------------------------- #
 def select(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK,
-           window: int = 0):
+           window: int = 0, mass_target: float | None = None, min_keep: int = 1):
     """Alg. 1 steps 1-11 for one head: permutations, block statistics, compensated
     logits, row distribution, top-kappa mask.  Returns a dict with every
-    intermediate."""
+    intermediate.  With mass_target the mask is the cumulative-mass one instead
+    (select_top_mass), capped at the kappa that `sparsity` gives."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     perm_q = norm_sort(Q, window) if sort in (SORT_Q, SORT_QK) else identity_perm(Q.shape[0])
@@ -255,7 +288,10 @@ def select(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK
     logits = block_logits(q_mean, q_var, k_mean, k_var, beta)
     m = row_softmax(logits)
     kappa = kappa_from_sparsity(k_mean.shape[0], sparsity)
-    sel = select_top_kappa(m, kappa)
+    if mass_target is None:
+        sel = select_top_kappa(m, kappa)
+    else:
+        sel = select_top_mass(m, mass_target, min_keep, cap=kappa)
     out = dict(perm_q=perm_q, perm_k=perm_k, q_mean=q_mean, q_var=q_var, k_mean=k_mean,
                k_var=k_var, logits=logits, m=m, kappa=kappa)
     out.update(sel)

@@ -314,6 +314,60 @@ def test_selection_is_nested_in_sparsity():
         prev = mask
 
 
+# ---------------------------------------------------------------- cumulative-mass selection
+def test_top_mass_is_the_smallest_sufficient_subset_bruteforce():
+    """Over ALL subsets of a small row: no smaller subset reaches the target, and no subset of
+    the same size carries more mass."""
+    import itertools
+    m = o.row_softmax(rand(5, 9, 2.0))
+    for p in (0.05, 0.4, 0.7, 0.95, 0.999999):
+        sel = o.select_top_mass(m, p)
+        for r in range(5):
+            k = int(sel["count"][r])
+            best = {size: max(sum(m[r, c] for c in sub) for sub in itertools.combinations(range(9), size))
+                    for size in range(1, 10)}
+            smallest = min(size for size in range(1, 10) if best[size] >= p) if best[9] >= p else 9
+            assert k == smallest
+            assert abs(sel["mass"][r] - best[k]) < 1e-15
+            assert sel["mask"][r].sum() == k and sel["cols"][r].tolist() == np.flatnonzero(sel["mask"][r]).tolist()
+            assert abs(m[r, sel["mask"][r]].sum() - sel["mass"][r]) < 1e-15
+
+
+def test_top_mass_closed_forms_and_limits():
+    n = 16
+    uniform = np.full((1, n), 1.0 / n)
+    for p, want in ((0.01, 1), (0.25, 4), (0.26, 5), (0.5, 8), (1.0, 16)):
+        sel = o.select_top_mass(uniform, p)
+        assert sel["count"][0] == want and sel["cols"][0].tolist() == list(range(want))   # ties: lower index
+    geo = np.array([[0.5, 0.25, 0.125, 0.0625, 0.0625]])
+    assert [int(o.select_top_mass(geo, p)["count"][0]) for p in (0.5, 0.51, 0.75, 0.9, 1.0)] == [1, 2, 2, 4, 5]
+    assert o.select_top_mass(geo[:, ::-1].copy(), 0.75)["cols"][0].tolist() == [3, 4]
+    # floor and ceiling on the count
+    assert o.select_top_mass(geo, 0.1, min_keep=3)["count"][0] == 3
+    assert o.select_top_mass(geo, 0.99, cap=2)["count"][0] == 2
+    assert o.select_top_mass(geo, 0.99, min_keep=4, cap=2)["count"][0] == 2
+    # a target no prefix reaches (rounding): everything is kept
+    assert o.select_top_mass(geo, 1.0 + 1e-9)["count"][0] == 5
+
+
+def test_top_mass_agrees_with_top_kappa_and_is_nested_in_target():
+    Q, K = rand(96, 8), rand(96, 8)
+    prev = None
+    for p in (0.2, 0.5, 0.8, 0.95):
+        sel = o.select(Q, K, 8, 0.0, mass_target=p)
+        m = sel["m"]
+        for r in range(m.shape[0]):
+            k = int(sel["count"][r])
+            top = o.select_top_kappa(m[r:r + 1], k)
+            assert (top["mask"][0] == sel["mask"][r]).all()
+            assert sel["mass"][r] >= p and (k == 1 or sel["mass"][r] - top["theta"][0] < p)
+        if prev is not None:
+            assert (prev | sel["mask"] == sel["mask"]).all()
+        prev = sel["mask"]
+    capped = o.select(Q, K, 8, 0.75, mass_target=0.95)
+    assert capped["count"].max() <= capped["kappa"] == 3
+
+
 # ---------------------------------------------------------------- P8: sparse attention
 def _tiny_case(L=40, d=4, B=8, s=0.5, sort=o.SORT_QK):
     Q, K, V = rand(L, d), rand(L, d), rand(L, d)
