@@ -63,6 +63,13 @@ typedef struct {
   float beta;                /* compensation weight of Eq. 13 (default 1; 0 = plain Eq. 2) */
   double sparsity;           /* s in [0,1): every query block keeps
                                 kappa = max(1, N_k - floor(s*N_k + 1e-9)) key blocks       */
+  double mass_target;        /* 0: keep exactly kappa blocks per row (Alg. 1 step 10).
+                                p in (0,1]: keep, in order of decreasing m', the FEWEST
+                                blocks whose m' sum to at least p ("the mask is built from
+                                m under a computational budget", Sec. 3.1 after Eq. 2, read
+                                as a mass budget), at least min_keep and at most kappa    */
+  int32_t min_keep;          /* floor on the per-row count when mass_target > 0; 0 means 1 */
+  int32_t reserved;          /* 0                                                         */
 } basa_params;
 
 /* Host helper: the per-query-block budget kappa (Alg. 1 input) for n_k key blocks at
@@ -104,11 +111,17 @@ basa_status basa_downsample(const basa_tensor* x, const int32_t* perm, const bas
  * Block selection (Alg. 1 steps 1-11): norm ranking of Q and/or K (p->sort), block
  * statistics, compensated block logits l' = Qbar.Kbar/sqrt(d) + beta*Delta^ with
  * Delta^ of Eq. 14, row softmax m' (Eq. 2) and the kappa largest m' per row (equal
- * values: lower key-block index first).
+ * values: lower key-block index first).  With p->mass_target > 0 the number kept varies by
+ * row: the fewest of the largest m' that sum to at least mass_target, clamped to
+ * [min_keep, kappa]; the sums are formed in fp32, so a row whose cumulative mass comes
+ * within rounding (about 1e-6 relative) of the target may keep one block more or fewer
+ * than exact arithmetic would.
  *   mask_bits  out, nullable, [batch, heads_q, N_q, ceil(N_k/32)] uint32, bit (g_k%32)
  *              of word g_k/32 set iff block pair (g_q, g_k) is kept.
- *   row_count  out [batch, heads_q, N_q] int32: number of kept key blocks (= kappa).
- *   row_cols   out [batch, heads_q, N_q, kappa] int32: kept key blocks, ascending.
+ *   row_count  out [batch, heads_q, N_q] int32: number of kept key blocks (= kappa, or the
+ *              row's own count when mass_target > 0).
+ *   row_cols   out [batch, heads_q, N_q, kappa] int32: kept key blocks, ascending, in the
+ *              first row_count entries of each row (the rest is left untouched).
  *   perm_q     out [batch, heads_q, L_q] int32 (identity when Q is not sorted).
  *   perm_k     out [batch, heads_kv, L_k] int32 (identity when K is not sorted).
  *   row_mass   out, nullable, [batch, heads_q, N_q] float: sum of kept m'.

@@ -38,7 +38,8 @@ class BasaTensor(C.Structure):
 
 class BasaParams(C.Structure):
     _fields_ = [("block", C.c_int32), ("sort", C.c_int32), ("window", C.c_int32),
-                ("beta", C.c_float), ("sparsity", C.c_double)]
+                ("beta", C.c_float), ("sparsity", C.c_double), ("mass_target", C.c_double),
+                ("min_keep", C.c_int32), ("reserved", C.c_int32)]
 
 
 class BasaError(RuntimeError):
@@ -123,8 +124,9 @@ def tensor_desc(x: torch.Tensor) -> BasaTensor:
 
 
 def params(block: int, sparsity: float = 0.0, beta: float = 1.0, sort: int = SORT_QK,
-           window: int = 0) -> BasaParams:
-    return BasaParams(int(block), int(sort), int(window), float(beta), float(sparsity))
+           window: int = 0, mass_target: float = 0.0, min_keep: int = 0) -> BasaParams:
+    return BasaParams(int(block), int(sort), int(window), float(beta), float(sparsity),
+                      float(mass_target), int(min_keep), 0)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -196,10 +198,11 @@ def attn_workspace_size(q, k, p: BasaParams) -> int:
 
 def basa_select(q: torch.Tensor, k: torch.Tensor, block: int, sparsity: float, beta: float = 1.0,
                 sort: int = SORT_QK, window: int = 0, want_mask: bool = True,
-                want_mass: bool = True, want_scores: bool = False, ws=None, out: Selection = None):
+                want_mass: bool = True, want_scores: bool = False, ws=None, out: Selection = None,
+                mass_target: float = 0.0, min_keep: int = 0):
     lib = load()
     qd, kd = tensor_desc(q), tensor_desc(k)
-    p = params(block, sparsity, beta, sort, window)
+    p = params(block, sparsity, beta, sort, window, mass_target, min_keep)
     b, hq, Lq, _ = q.shape
     hk, Lk = k.shape[1], k.shape[2]
     n_q, n_k = n_blocks(Lq, block), n_blocks(Lk, block)

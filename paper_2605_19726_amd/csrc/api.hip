@@ -109,6 +109,12 @@ basa_status check_params(const basa_params* p, bool need_sparsity) {
   if (!(p->beta == p->beta) || std::isinf(p->beta)) {
     set_error("beta must be finite"); return BASA_ERR_INVALID_ARG;
   }
+  if (need_sparsity && !(p->mass_target >= 0.0 && p->mass_target <= 1.0)) {
+    set_error("mass_target %g outside [0, 1]", p->mass_target); return BASA_ERR_INVALID_ARG;
+  }
+  if (need_sparsity && p->min_keep < 0) {
+    set_error("min_keep %d is negative", p->min_keep); return BASA_ERR_INVALID_ARG;
+  }
   return BASA_OK;
 }
 
@@ -282,7 +288,8 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   }
   const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
   if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
-  return launch_row_select(sc, BHq * Nq, Nk, kappa, mask_bits, row_count, row_cols, row_mass, st);
+  return launch_row_select(sc, BHq * Nq, Nk, kappa, (float)p->mass_target, p->min_keep, mask_bits, row_count,
+                           row_cols, row_mass, st);
 }
 
 basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,

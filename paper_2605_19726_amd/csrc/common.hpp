@@ -82,10 +82,12 @@ basa_status launch_block_scores(const float* featQ, const float* featK, float* s
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
                                 hipStream_t st);
 
-// Row softmax mass + top-kappa selection from a score map.
+// Row softmax mass + top-kappa selection from a score map; mass_target > 0 switches to the
+// cumulative-mass count per row (floor min_keep, cap kappa).  row_cols rows are kappa apart.
 basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
-                              uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols,
-                              float* row_mass, hipStream_t st);
+                              float mass_target, int min_keep, uint32_t* mask_bits,
+                              int32_t* row_count, int32_t* row_cols, float* row_mass,
+                              hipStream_t st);
 
 // Attention.
 struct AttnArgs {

@@ -100,9 +100,20 @@ __device__ __forceinline__ uint32_t ordered_bits(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// mass_target == 0: every row keeps `kappa` blocks.  mass_target > 0: a row keeps the fewest of
+// its largest m' that sum to at least mass_target, at least min_keep and at most kappa; the
+// count is found first (a second bisection, on "mass of the logits >= T"), then the same
+// top-count machinery runs with the row's own count.
 template <int MAXI>
 __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ scores,
                                                          int rows_total, int Nk, int kappa,
+                                                         float mass_target, int min_keep,
                                                          uint32_t* __restrict__ mask_bits,
                                                          int32_t* __restrict__ row_count,
                                                          int32_t* __restrict__ row_cols,
@@ -111,44 +122,81 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   const int row = blockIdx.x * 4 + wave;
   if (row >= rows_total) return;
   const float* src = scores + (int64_t)row * Nk;
-  float l[MAXI];
+  float e[MAXI];                        // logits first, then exp(l - max)
   uint32_t u[MAXI];
   float mx = -INFINITY;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
     const int idx = i * 64 + lane;
     if (idx < Nk) {
-      l[i] = src[idx] + 0.0f;          // -0 -> +0 so that equal values have equal images
-      u[i] = ordered_bits(l[i]);
-      mx = fmaxf(mx, l[i]);
+      e[i] = src[idx] + 0.0f;          // -0 -> +0 so that equal values have equal images
+      u[i] = ordered_bits(e[i]);
+      mx = fmaxf(mx, e[i]);
     } else {
-      l[i] = -INFINITY;
+      e[i] = -INFINITY;
       u[i] = 0u;                        // below the image of every float
     }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  float sum_all = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    e[i] = (i * 64 + lane < Nk) ? expf(e[i] - mx) : 0.f;
+    sum_all += e[i];
+  }
+  sum_all = wave_sum(sum_all);
 
-  // T = kappa-th largest image
+  int keep = kappa;
+  if (mass_target > 0.f) {
+    const float need = mass_target * sum_all;
+    // T2 = largest image T such that the logits with image >= T carry at least the target
+    uint32_t T2 = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = T2 | (1u << bit);
+      float sm = 0.f;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) sm += (u[i] >= cand) ? e[i] : 0.f;
+      if (wave_sum(sm) >= need) T2 = cand;
+    }
+    // everything above T2 is needed; of the logits equal to T2, as many as close the gap
+    int n_gt = 0, n_eq = 0;
+    float m_gt = 0.f, e_eq = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      n_gt += __popcll(__ballot(u[i] > T2));
+      n_eq += __popcll(__ballot(u[i] == T2));
+      m_gt += (u[i] > T2) ? e[i] : 0.f;
+      e_eq = fmaxf(e_eq, (u[i] == T2) ? e[i] : 0.f);
+    }
+    m_gt = wave_sum(m_gt);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) e_eq = fmaxf(e_eq, __shfl_xor(e_eq, off));
+    int r = n_eq;
+    if (e_eq > 0.f) r = min(n_eq, max(1, (int)ceilf((need - m_gt) / e_eq)));
+    keep = min(kappa, max(max(1, min_keep), n_gt + r));
+  }
+
+  // T = keep-th largest image
   uint32_t T = 0;
   for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = T | (1u << bit);
     int cnt = 0;
 #pragma unroll
     for (int i = 0; i < MAXI; ++i) cnt += __popcll(__ballot(u[i] >= cand));
-    if (cnt >= kappa) T = cand;
+    if (cnt >= keep) T = cand;
   }
   int n_gt = 0;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) n_gt += __popcll(__ballot(u[i] > T));
-  const int need_eq = kappa - n_gt;      // >= 1 by construction of T
+  const int need_eq = keep - n_gt;       // >= 1 by construction of T
 
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const int words = (Nk + 31) >> 5;
   int32_t* cols = row_cols ? row_cols + (int64_t)row * kappa : nullptr;
   uint32_t* mrow = mask_bits ? mask_bits + (int64_t)row * words : nullptr;
   int emitted = 0, eq_seen = 0;
-  float sum_all = 0.f, sum_sel = 0.f;
+  float sum_sel = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
     if (i * 64 < Nk) {
@@ -157,10 +205,8 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
       const int eq_rank = eq_seen + __popcll(beq & lt_mask);
       const bool sel = (u[i] > T) || (eq && eq_rank < need_eq);
       const uint64_t bsel = __ballot(sel);
-      const float e = (i * 64 + lane < Nk) ? expf(l[i] - mx) : 0.f;
-      sum_all += e;
       if (sel) {
-        sum_sel += e;
+        sum_sel += e[i];
         if (cols) cols[emitted + __popcll(bsel & lt_mask)] = i * 64 + lane;
       }
       if (mrow && lane < 2 && 2 * i + lane < words)
@@ -169,11 +215,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
       eq_seen += __popcll(beq);
     }
   }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    sum_all += __shfl_xor(sum_all, off);
-    sum_sel += __shfl_xor(sum_sel, off);
-  }
+  sum_sel = wave_sum(sum_sel);
   if (lane == 0) {
     if (row_count) row_count[row] = emitted;
     if (row_mass) row_mass[row] = sum_sel / sum_all;
@@ -195,14 +237,15 @@ basa_status launch_block_scores(const float* featQ, const float* featK, float* s
 }
 
 basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
-                              uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols,
-                              float* row_mass, hipStream_t st) {
+                              float mass_target, int min_keep, uint32_t* mask_bits,
+                              int32_t* row_count, int32_t* row_cols, float* row_mass,
+                              hipStream_t st) {
   if (rows_total == 0) return BASA_OK;
   dim3 grid(ceil_div(rows_total, 4));
   ProfScope prof(K_ROW_SELECT, st);
 #define BASA_SEL(M)                                                                            \
   hipLaunchKernelGGL((row_select_kernel<M>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
-                     kappa, mask_bits, row_count, row_cols, row_mass)
+                     kappa, mass_target, min_keep, mask_bits, row_count, row_cols, row_mass)
   if (Nk <= 256) BASA_SEL(4);
   else if (Nk <= 1024) BASA_SEL(16);
   else if (Nk <= 2048) BASA_SEL(32);

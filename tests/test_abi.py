@@ -77,6 +77,9 @@ def test_select_argument_validation(lib):
     assert call(q, k, bd.params(128, 1.0))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, window=100))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, sort=7))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, mass_target=1.5))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, mass_target=-0.1))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, mass_target=0.9, min_keep=-1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, p, rc=None)[0] == "BASA_ERR_INVALID_ARG"
     name, why = call(q, k, p, wsb=16)
     assert name == "BASA_ERR_WORKSPACE" and "need" in why

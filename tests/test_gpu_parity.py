@@ -174,6 +174,68 @@ def test_select_cross_lengths():
     _check_selection(w, Qs, K, 0.5, 1.0, o.SORT_QK)
 
 
+# ------------------------------------------------------------------ cumulative-mass selection
+MASS_BAND = 1e-5     # a row whose cumulative mass comes this close to the target may keep one block more or fewer
+
+
+def _check_mass_selection(w, Q, K, s_cap, p, min_keep):
+    sel = bd.basa_select(Q, K, w.block, s_cap, mass_target=p, min_keep=min_keep)
+    torch.cuda.synchronize()
+    gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
+    lo = max(1, min_keep)
+    n_band = 0
+    for h in range(Q.shape[1]):
+        ref = o.select(np64(Q[0, h]), np64(K[0, h // (Q.shape[1] // K.shape[1])]), w.block, s_cap,
+                       mass_target=p, min_keep=min_keep)
+        cap, cum, m = ref["kappa"], ref["cum"], ref["m"]
+        cnt = sel.row_count[0, h].cpu().numpy()
+        cols = sel.row_cols[0, h].cpu().numpy()
+        assert sel.row_cols.shape[-1] == cap
+        for r in range(m.shape[0]):
+            kg = int(cnt[r])
+            assert min(lo, cap) <= kg <= cap, f"row {r}: count {kg} outside [{lo}, {cap}]"
+            enough = kg == cap or cum[r, kg - 1] >= p - MASS_BAND
+            minimal = kg == min(lo, cap) or cum[r, kg - 2] < p + MASS_BAND
+            assert enough and minimal, f"head {h} row {r}: count {kg}, oracle {int(ref['count'][r])}"
+            n_band += kg != int(ref["count"][r])
+            # the kept set is the row's top-kg set (same tie band as the fixed-budget selection)
+            top = o.select_top_kappa(m[r:r + 1], kg)
+            top["m"] = m[r:r + 1]
+            bad, _ = mask_report(gpu_mask[0, h, r:r + 1], top)
+            assert bad == 0, f"head {h} row {r}: kept set is not the top-{kg} set"
+            assert np.array_equal(np.flatnonzero(gpu_mask[0, h, r]), cols[r, :kg]), "bitmap and list disagree"
+            if np.array_equal(gpu_mask[0, h, r], ref["mask"][r]):
+                assert abs(float(sel.row_mass[0, h, r]) - ref["mass"][r]) <= 1e-4
+    return sel, n_band
+
+
+@pytest.mark.parametrize("w", [SMALL[0], SMALL[1], SMALL[3]], ids=lambda w: w.name)
+def test_mass_selection_matches_oracle(w):
+    Q, K, _ = gen(w)
+    for p, min_keep, s_cap in ((0.5, 0, 0.0), (0.9, 4, 0.0), (0.95, 1, 0.5), (1.0, 0, 0.0), (1e-6, 3, 0.0)):
+        _check_mass_selection(w, Q, K, s_cap, p, min_keep)
+
+
+def test_mass_selection_then_attention_with_ragged_row_counts():
+    """Rows keep different numbers of blocks; the attention kernel walks each row's own count."""
+    w = SMALL[1]
+    Q, K, V = gen(w)
+    sel, _ = _check_mass_selection(w, Q, K, 0.0, 0.8, 2)
+    cnt = sel.row_count.cpu().numpy()
+    assert cnt.min() < cnt.max(), "the target mass should give rows of different lengths on this input"
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+    torch.cuda.synchronize()
+    group = Q.shape[1] // K.shape[1]
+    for h in range(Q.shape[1]):
+        q, k, v = np64(Q[0, h]), np64(K[0, h // group]), np64(V[0, h // group])
+        pq, pk = sel.perm_q[0, h].cpu().numpy().astype(np.int64), sel.perm_k[0, h // group].cpu().numpy().astype(np.int64)
+        cols = sel.row_cols[0, h].cpu().numpy().astype(np.int64)
+        out_h = np64(out[0, h])
+        for g in range(sel.n_q):
+            rows, O_ref, _ = o.sparse_attention_block(q, k, v, pq, pk, g, cols[g, :cnt[0, h, g]], w.block)
+            check_output(out_h[rows], O_ref, w.dtype == "bf16", f"head {h} block {g}")
+
+
 # ------------------------------------------------------------------ attention
 def _oracle_attention(Q, K, V, h, sel, block):
     hk = h // (Q.shape[1] // K.shape[1])
