@@ -343,3 +343,40 @@ def deviation_bound(Q, K, B: int) -> np.ndarray:
     Rq, Mq = block_norm_metrics(Q, B)
     Rk, Mk = block_norm_metrics(K, B)
     return (np.outer(Rq, Mk) + np.outer(Mq, Rk) + np.outer(Rq, Rk)) / math.sqrt(d)
+
+
+def max_logit_deviation(Q, K, B: int) -> np.ndarray:
+    """max over the token pairs (i, j) of a block pair of |l^_ij - l_{g_q,g_k}| with
+    l^_ij = Q_i.K_j / sqrt(d) and l of Eq. 2: the observed deviation that Eq. 8 bounds and
+    Fig. 2 plots against the bound.  Q and K are taken in the order given."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    d = Q.shape[1]
+    q_mean, _ = block_stats(Q, B)
+    k_mean, _ = block_stats(K, B)
+    l_blk = baseline_logits(q_mean, k_mean)
+    l_tok = (Q @ K.T) / math.sqrt(d)
+    n_q, n_k = l_blk.shape
+    dev = np.zeros((n_q, n_k))
+    for gq in range(n_q):
+        for gk in range(n_k):
+            blk = l_tok[gq * B:(gq + 1) * B, gk * B:(gk + 1) * B]
+            dev[gq, gk] = np.abs(blk - l_blk[gq, gk]).max()
+    return dev
+
+
+def pearson_r(x, y) -> float:
+    """Pearson correlation coefficient (the R of Fig. 2)."""
+    x = np.asarray(x, dtype=np.float64).ravel()
+    y = np.asarray(y, dtype=np.float64).ravel()
+    xc, yc = x - x.mean(), y - y.mean()
+    return float((xc * yc).sum() / math.sqrt((xc * xc).sum() * (yc * yc).sum()))
+
+
+def selection_fidelity(m: np.ndarray, mask: np.ndarray, m_hat: np.ndarray):
+    """Per query block: the oracle mass (Eq. 3) that the kept blocks hold, and the l1
+    distance between the block distribution m' and the oracle distribution m_hat
+    (the quantity the deviation analysis of Sec. 3.2 sets out to control)."""
+    recall = np.where(mask, m_hat, 0.0).sum(axis=1)
+    l1 = np.abs(m - m_hat).sum(axis=1)
+    return recall, l1

@@ -459,3 +459,45 @@ def test_tiny_workload_selection_is_not_flat():
     # without sorting, different query blocks keep different key blocks
     sel_ns = o.select(q, k, w.block, 0.5, 1.0, o.SORT_NONE)
     assert len({tuple(r) for r in sel_ns["cols"].tolist()}) > 4
+
+
+# ---------------------------------------------------------------- fidelity diagnostics
+def test_max_logit_deviation_by_loops_and_under_the_bound():
+    Q, K = rand(22, 5), rand(19, 5)            # ragged last blocks on both sides
+    B = 4
+    dev = o.max_logit_deviation(Q, K, B)
+    qm, _ = o.block_stats(Q, B)
+    km, _ = o.block_stats(K, B)
+    for gq in range(dev.shape[0]):
+        for gk in range(dev.shape[1]):
+            lb = float(qm[gq] @ km[gk]) / math.sqrt(5)
+            want = max(abs(float(Q[i] @ K[j]) / math.sqrt(5) - lb)
+                       for i in range(gq * B, min((gq + 1) * B, 22)) for j in range(gk * B, min((gk + 1) * B, 19)))
+            assert abs(dev[gq, gk] - want) < 1e-13
+    assert (dev <= o.deviation_bound(Q, K, B) + 1e-12).all()                      # Eq. 8
+    same = np.repeat(rand(3, 5), 4, axis=0)                                        # homogeneous blocks
+    assert np.abs(o.max_logit_deviation(same, same, 4)).max() < 1e-13
+
+
+def test_pearson_r_closed_forms_and_library():
+    x = rand(50, 1)[:, 0]
+    assert abs(o.pearson_r(x, 2.0 * x + 1.0) - 1.0) < 1e-12
+    assert abs(o.pearson_r(x, -0.5 * x) + 1.0) < 1e-12
+    y = rand(50, 1)[:, 0]
+    assert abs(o.pearson_r(x, y) - np.corrcoef(x, y)[0, 1]) < 1e-12
+    assert abs(o.pearson_r(x, y) - o.pearson_r(y, x)) < 1e-15
+    assert abs(o.pearson_r([0, 0, 1, 1], [0, 1, 0, 1])) < 1e-15
+
+
+def test_selection_fidelity_limits():
+    Q, K = rand(48, 6), rand(48, 6)
+    sel = o.select(Q, K, 8, 0.5, sort=o.SORT_NONE)
+    m_hat = o.oracle_block_mass(Q, K, 8)
+    recall, l1 = o.selection_fidelity(sel["m"], sel["mask"], m_hat)
+    full, _ = o.selection_fidelity(sel["m"], np.ones_like(sel["mask"]), m_hat)
+    np.testing.assert_allclose(full, 1.0, atol=1e-12)                 # keeping everything keeps all mass
+    assert ((recall > 0) & (recall < 1)).all() and ((l1 >= 0) & (l1 <= 2)).all()
+    for r in range(6):
+        assert abs(recall[r] - sum(m_hat[r, c] for c in sel["cols"][r])) < 1e-15
+    _, zero = o.selection_fidelity(m_hat, sel["mask"], m_hat)
+    assert np.abs(zero).max() == 0.0
