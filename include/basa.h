@@ -183,6 +183,58 @@ const char* basa_profile_kernel_name(int32_t id);
 basa_status basa_profile_read(double* total_ms /*host*/, int32_t* launches /*host*/, int32_t n);
 
 /*
+ * ---- Selection-fidelity diagnostics (off the hot path; cost of a dense attention) ----
+ *
+ * Oracle block distribution (Sec. 3.1, Eq. 3): m_hat[g_q, g_k] = mean over the query
+ * tokens of block g_q of the dense attention weight (Eq. 1) that falls on the key tokens
+ * of block g_k, for the ordered sequences Q[perm_q], K[perm_k] (NULL: original order).
+ * bf16 tensors with d = 128 only (BASA_ERR_UNSUPPORTED otherwise).
+ *   base_logits  nullable [batch, heads_q, N_q, N_k] float: block logits l of Eq. 2
+ *                (basa_select's `scores` with beta = 0); needed for max_dev.
+ *   m_hat        out [batch, heads_q, N_q, N_k] float; every row sums to 1.
+ *   max_dev      out, nullable, same shape: max over the token pairs (i, j) of the block pair
+ *                of |Q_i.K_j/sqrt(d) - base_logits[g_q, g_k]|, the observed deviation that
+ *                Sec. 3.2 bounds by U (Eq. 8) and Fig. 2 correlates with it.
+ *   lse          out, nullable, [batch, heads_q, L_q] float, original token order:
+ *                log-sum-exp of every query's scaled logits over all keys.
+ *   ws           workspace of basa_block_mass_workspace_size() bytes.
+ */
+size_t basa_block_mass_workspace_size(const basa_tensor* q, const basa_tensor* k);
+basa_status basa_block_mass(const basa_tensor* q, const basa_tensor* k, const int32_t* perm_q,
+                            const int32_t* perm_k, const basa_params* p, const float* base_logits,
+                            float* m_hat, float* max_dev, float* lse, void* ws, size_t ws_bytes,
+                            void* stream);
+/*
+ * Block-wise norm metrics (Sec. 3.2, Eq. 7) of the ordered sequence x[perm]: per block the
+ * radius R = max_i ||x_i - mean|| and the maximum norm M = max_i ||x_i||.
+ *   radius, max_norm  out [batch, heads, N] float.
+ */
+basa_status basa_block_radius(const basa_tensor* x, const int32_t* perm, const basa_params* p,
+                              float* radius, float* max_norm, void* stream);
+/*
+ * Deviation bound (Eq. 8): bound[bh, g_q, g_k] = (R^Q M^K + M^Q R^K + R^Q R^K) / sqrt(d) from the
+ * outputs of basa_block_radius for Q ([bh_q, n_q]) and K ([bh_kv, n_k]); query head bh reads
+ * KV head bh / (bh_q / bh_kv).   bound: out [bh_q, n_q, n_k] float.
+ */
+basa_status basa_deviation_bound(const float* radius_q, const float* max_norm_q, const float* radius_k,
+                                 const float* max_norm_k, int32_t bh_q, int32_t bh_kv, int32_t n_q,
+                                 int32_t n_k, int32_t d, float* bound, void* stream);
+/*
+ * Per row of the block map (rows = batch * heads_q * N_q, n_k columns): recall = sum of m_hat
+ * over the blocks kept in mask_bits (the dense attention mass the selection retains), and
+ * l1 = || softmax(scores) - m_hat ||_1, the distance the analysis of Sec. 3.2 is about.
+ * All device pointers; recall and l1 are [rows] float, either may be NULL (not both).
+ */
+basa_status basa_selection_fidelity(const float* scores, const uint32_t* mask_bits, const float* m_hat,
+                                    int64_t rows, int32_t n_k, float* recall, float* l1, void* stream);
+/*
+ * The sums a Pearson correlation coefficient (R of Fig. 2) is made of, over n pairs of device
+ * floats: sums[0..5] = n, sum x, sum y, sum x^2, sum y^2, sum xy (device, fp64, overwritten).
+ * Accumulated with fp64 atomics: the last bits depend on the order of arrival.
+ */
+basa_status basa_pearson_sums(const float* x, const float* y, int64_t n, double* sums, void* stream);
+
+/*
  * Calibration aid for benchmarks (no part of the method): enqueues a kernel that issues
  * `iters` x 32 independent bf16 32x32x16 matrix-core instructions per wave on register
  * operands, 8 waves per compute unit, and nothing else.  random_operands != 0: the operand

@@ -26,7 +26,8 @@ EXPORTS = (
     "basa_sort_workspace_size", "basa_norm_sort", "basa_downsample", "basa_select",
     "basa_sparse_attn", "basa_dense_attn", "basa_status_string", "basa_last_error",
     "basa_version", "basa_profile_enable", "basa_profile_kernel_count", "basa_profile_kernel_name",
-    "basa_profile_read", "basa_calibrate_mfma",
+    "basa_profile_read", "basa_calibrate_mfma", "basa_block_mass_workspace_size", "basa_block_mass",
+    "basa_block_radius", "basa_deviation_bound", "basa_selection_fidelity", "basa_pearson_sums",
 )
 
 
@@ -94,6 +95,18 @@ def load():
     lib.basa_profile_kernel_name.argtypes = [C.c_int32]
     lib.basa_profile_read.restype = C.c_int
     lib.basa_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32), C.c_int32]
+    lib.basa_block_mass_workspace_size.restype = C.c_size_t
+    lib.basa_block_mass_workspace_size.argtypes = [T, T]
+    lib.basa_block_mass.restype = C.c_int
+    lib.basa_block_mass.argtypes = [T, T, V, V, P, V, V, V, V, V, C.c_size_t, V]
+    lib.basa_block_radius.restype = C.c_int
+    lib.basa_block_radius.argtypes = [T, V, P, V, V, V]
+    lib.basa_deviation_bound.restype = C.c_int
+    lib.basa_deviation_bound.argtypes = [V, V, V, V, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, V, V]
+    lib.basa_selection_fidelity.restype = C.c_int
+    lib.basa_selection_fidelity.argtypes = [V, V, V, C.c_int64, C.c_int32, V, V, V]
+    lib.basa_pearson_sums.restype = C.c_int
+    lib.basa_pearson_sums.argtypes = [V, V, C.c_int64, V, V]
     lib.basa_calibrate_mfma.restype = C.c_int
     lib.basa_calibrate_mfma.argtypes = [C.c_int32, C.c_int32, V, C.c_size_t, C.POINTER(C.c_double), V]
     _lib = lib
@@ -282,3 +295,59 @@ def basa_calibrate_mfma(random_operands: bool, iters: int, out: torch.Tensor) ->
     _check(load().basa_calibrate_mfma(1 if random_operands else 0, int(iters), _ptr(out), out.numel(),
                                       C.byref(flops), _stream(out)))
     return float(flops.value)
+
+
+# ---------------------------------------------------------------- selection-fidelity diagnostics
+def basa_block_mass(q, k, block: int, perm_q=None, perm_k=None, base_logits=None, want_dev: bool = False,
+                    want_lse: bool = False, ws=None):
+    """m_hat [b, Hq, Nq, Nk] (and max_dev, lse when asked) of the ordered sequences."""
+    lib = load()
+    qd, kd, p = tensor_desc(q), tensor_desc(k), params(block)
+    b, hq, Lq, _ = q.shape
+    n_q, n_k = n_blocks(Lq, block), n_blocks(k.shape[2], block)
+    m_hat = torch.empty((b, hq, n_q, n_k), dtype=torch.float32, device=q.device)
+    dev = torch.empty_like(m_hat) if want_dev else None
+    lse = torch.empty((b, hq, Lq), dtype=torch.float32, device=q.device) if want_lse else None
+    if ws is None:
+        ws = _ws(lib.basa_block_mass_workspace_size(C.byref(qd), C.byref(kd)), q.device)
+    _check(lib.basa_block_mass(C.byref(qd), C.byref(kd), _ptr(perm_q), _ptr(perm_k), C.byref(p),
+                               _ptr(base_logits), _ptr(m_hat), _ptr(dev), _ptr(lse), _ptr(ws), ws.numel(),
+                               _stream(q)))
+    return m_hat, dev, lse
+
+
+def basa_block_radius(x, block: int, perm=None):
+    lib = load()
+    xd, p = tensor_desc(x), params(block)
+    b, h, L, _ = x.shape
+    radius = torch.empty((b, h, n_blocks(L, block)), dtype=torch.float32, device=x.device)
+    max_norm = torch.empty_like(radius)
+    _check(lib.basa_block_radius(C.byref(xd), _ptr(perm), C.byref(p), _ptr(radius), _ptr(max_norm), _stream(x)))
+    return radius, max_norm
+
+
+def basa_deviation_bound(radius_q, max_norm_q, radius_k, max_norm_k, d: int):
+    b, hq, n_q = radius_q.shape
+    hk, n_k = radius_k.shape[1], radius_k.shape[2]
+    bound = torch.empty((b, hq, n_q, n_k), dtype=torch.float32, device=radius_q.device)
+    _check(load().basa_deviation_bound(_ptr(radius_q), _ptr(max_norm_q), _ptr(radius_k), _ptr(max_norm_k),
+                                       b * hq, b * hk, n_q, n_k, int(d), _ptr(bound), _stream(radius_q)))
+    return bound
+
+
+def basa_selection_fidelity(scores, mask_bits, m_hat):
+    """(recall, l1), each [b, Hq, Nq]."""
+    n_k = scores.shape[-1]
+    rows = scores.numel() // n_k
+    recall = torch.empty(scores.shape[:-1], dtype=torch.float32, device=scores.device)
+    l1 = torch.empty_like(recall)
+    _check(load().basa_selection_fidelity(_ptr(scores), _ptr(mask_bits), _ptr(m_hat), rows, n_k, _ptr(recall),
+                                          _ptr(l1), _stream(scores)))
+    return recall, l1
+
+
+def basa_pearson_sums(x, y):
+    """Device tensor of the six fp64 sums (n, sx, sy, sxx, syy, sxy) over two float tensors."""
+    sums = torch.empty(6, dtype=torch.float64, device=x.device)
+    _check(load().basa_pearson_sums(_ptr(x), _ptr(y), x.numel(), _ptr(sums), _stream(x)))
+    return sums

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libbasa.so")
-SOURCES = ["api.hip", "sort.hip", "stats.hip", "select.hip", "attn_simple.hip", "attn_mfma.hip", "calib.hip"]
+SOURCES = ["api.hip", "sort.hip", "stats.hip", "select.hip", "attn_simple.hip", "attn_mfma.hip", "calib.hip", "diag.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

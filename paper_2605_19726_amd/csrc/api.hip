@@ -33,7 +33,7 @@ std::vector<ProfRec> g_prof_recs;
 const char* const kKernelNames[K_COUNT] = {
     "norm_keys_kernel", "tile_sort_kernel", "merge_pass_kernel", "block_stats_kernel",
     "block_scores_kernel", "row_select_kernel", "gather_kernels", "attn_mfma_kernel",
-    "attn_simple_kernel"};
+    "attn_simple_kernel", "block_mass_kernel", "diagnostic_small_kernels"};
 }  // namespace
 
 ProfScope::ProfScope(int id, hipStream_t st) : slot_(-1), st_(st) {
@@ -360,6 +360,74 @@ basa_status basa_profile_read(double* total_ms, int32_t* launches, int32_t n) {
   return rc;
 }
 const char* basa_version(void) { return "basa 0.1 gfx950"; }
+
+size_t basa_block_mass_workspace_size(const basa_tensor* q, const basa_tensor* k) {
+  if (!q || !k) return 0;
+  return block_mass_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L);
+}
+
+basa_status basa_block_mass(const basa_tensor* q, const basa_tensor* k, const int32_t* perm_q,
+                            const int32_t* perm_k, const basa_params* p, const float* base_logits,
+                            float* m_hat, float* max_dev, float* lse, void* ws, size_t ws_bytes,
+                            void* stream) {
+  basa_status s;
+  if ((s = check_qk(q, k)) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  if (q->dtype != BASA_BF16 || q->d != 128) {
+    set_error("basa_block_mass: only bf16 tensors with head dimension 128 are supported");
+    return BASA_ERR_UNSUPPORTED;
+  }
+  if (!m_hat) { set_error("basa_block_mass: m_hat output is required"); return BASA_ERR_INVALID_ARG; }
+  if (max_dev && !base_logits) {
+    set_error("basa_block_mass: max_dev needs base_logits"); return BASA_ERR_INVALID_ARG;
+  }
+  const size_t need = basa_block_mass_workspace_size(q, k);
+  if (!ws || ws_bytes < need) {
+    set_error("block mass workspace too small: need %zu bytes, got %zu", need, ws ? ws_bytes : (size_t)0);
+    return BASA_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(ws) % 256) { set_error("workspace must be 256-byte aligned"); return BASA_ERR_INVALID_ARG; }
+  return launch_block_mass(view_of(*q), view_of(*k), perm_q, perm_k, p->block, base_logits, m_hat, max_dev, lse,
+                           ws, reinterpret_cast<hipStream_t>(stream));
+}
+
+basa_status basa_block_radius(const basa_tensor* x, const int32_t* perm, const basa_params* p, float* radius,
+                              float* max_norm, void* stream) {
+  basa_status s;
+  if ((s = check_tensor(x, "x")) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  if (!radius || !max_norm) { set_error("basa_block_radius: both outputs are required"); return BASA_ERR_INVALID_ARG; }
+  return launch_block_radius(view_of(*x), perm, p->block, radius, max_norm, reinterpret_cast<hipStream_t>(stream));
+}
+
+basa_status basa_deviation_bound(const float* radius_q, const float* max_norm_q, const float* radius_k,
+                                 const float* max_norm_k, int32_t bh_q, int32_t bh_kv, int32_t n_q, int32_t n_k,
+                                 int32_t d, float* bound, void* stream) {
+  if (!radius_q || !max_norm_q || !radius_k || !max_norm_k || !bound) {
+    set_error("basa_deviation_bound: null argument"); return BASA_ERR_INVALID_ARG;
+  }
+  if (bh_q < 0 || bh_kv < 1 || bh_q % bh_kv != 0 || n_q < 0 || n_k < 0 || d < 1 || bh_q > 65535 || n_q > 65535) {
+    set_error("basa_deviation_bound: bad sizes"); return BASA_ERR_INVALID_ARG;
+  }
+  return launch_deviation_bound(radius_q, max_norm_q, radius_k, max_norm_k, bh_q, bh_q / bh_kv, n_q, n_k, d, bound,
+                                reinterpret_cast<hipStream_t>(stream));
+}
+
+basa_status basa_selection_fidelity(const float* scores, const uint32_t* mask_bits, const float* m_hat,
+                                    int64_t rows, int32_t n_k, float* recall, float* l1, void* stream) {
+  if (!scores || !mask_bits || !m_hat || (!recall && !l1)) {
+    set_error("basa_selection_fidelity: null argument"); return BASA_ERR_INVALID_ARG;
+  }
+  if (rows < 0 || rows > (int64_t)1 << 30 || n_k < 1) {
+    set_error("basa_selection_fidelity: bad sizes"); return BASA_ERR_INVALID_ARG;
+  }
+  return launch_fidelity_rows(scores, mask_bits, m_hat, (int)rows, n_k, recall, l1, reinterpret_cast<hipStream_t>(stream));
+}
+
+basa_status basa_pearson_sums(const float* x, const float* y, int64_t n, double* sums, void* stream) {
+  if (!x || !y || !sums || n < 0) { set_error("basa_pearson_sums: null argument or negative n"); return BASA_ERR_INVALID_ARG; }
+  return launch_pearson_sums(x, y, n, sums, reinterpret_cast<hipStream_t>(stream));
+}
 
 basa_status basa_calibrate_mfma(int32_t random_operands, int32_t iters, float* out, size_t out_elems,
                                 double* flops, void* stream) {

@@ -42,7 +42,7 @@ basa_status hip_fail(hipError_t e, const char* what);
 // with a pair of HIP events on the launch stream when profiling is enabled.
 enum KernelId {
   K_NORM_KEYS = 0, K_TILE_SORT, K_MERGE, K_STATS, K_SCORES, K_ROW_SELECT, K_GATHER, K_ATTN,
-  K_ATTN_SIMPLE, K_COUNT
+  K_ATTN_SIMPLE, K_BLOCK_MASS, K_DIAG_SMALL, K_COUNT
 };
 struct ProfScope {
   ProfScope(int id, hipStream_t st);
@@ -106,6 +106,19 @@ struct AttnArgs {
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B);
 basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st);
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st);
+
+// Selection-fidelity diagnostics (diag.hip).  block mass: bf16, d = 128 only.
+size_t block_mass_workspace_bytes(int BHq, int BHkv, int Lq, int Lk);
+basa_status launch_block_mass(const TensorView& q, const TensorView& k, const int32_t* perm_q,
+                              const int32_t* perm_k, int B, const float* base_logits, float* m_hat,
+                              float* max_dev, float* lse, void* ws, hipStream_t st);
+basa_status launch_block_radius(const TensorView& x, const int32_t* perm, int B, float* radius,
+                                float* max_norm, hipStream_t st);
+basa_status launch_deviation_bound(const float* rq, const float* mq, const float* rk, const float* mk,
+                                   int BHq, int group, int Nq, int Nk, int d, float* U, hipStream_t st);
+basa_status launch_fidelity_rows(const float* scores, const uint32_t* mask_bits, const float* m_hat,
+                                 int rows, int Nk, float* recall, float* l1, hipStream_t st);
+basa_status launch_pearson_sums(const float* x, const float* y, int64_t n, double* sums, hipStream_t st);
 
 // calibration (calib.hip): a loop of independent bf16 MFMAs on register operands
 size_t calib_mfma_out_elems();
