@@ -6,7 +6,7 @@ in HBM: basa_select (norm sort, block pooling, compensated score map, top-kappa)
 by basa_sparse_attn (gather + bf16-MFMA block-sparse attention).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--sparsity 0.5]
-                    [--sweep] [--no-cpu-baseline]
+                    [--sweep] [--no-cpu-baseline] [--fidelity]
 
 --sweep additionally times every configuration / sparsity of the benchmark and writes the
 table to gpurun_out/bench_sweep.json (the printed line stays the headline workload).
@@ -65,19 +65,19 @@ def selection_bytes(w):
 class Pipeline:
     """Preallocated buffers for repeated select + attention calls on one workload."""
 
-    def __init__(self, w, sparsity, Q, K, V, beta=1.0, sort=bd.SORT_QK):
-        self.w, self.s, self.beta, self.sort = w, sparsity, beta, sort
+    def __init__(self, w, sparsity, Q, K, V, beta=1.0, sort=bd.SORT_QK, mass_target=0.0):
+        self.w, self.s, self.beta, self.sort, self.mass_target = w, sparsity, beta, sort, mass_target
         self.Q, self.K, self.V = Q, K, V
         dev = Q.device
         p = bd.params(w.block, sparsity, beta, sort)
         self.ws_sel = torch.empty(bd.select_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
         self.ws_att = torch.empty(bd.attn_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
-        self.sel = bd.basa_select(Q, K, w.block, sparsity, beta, sort, ws=self.ws_sel)
+        self.sel = bd.basa_select(Q, K, w.block, sparsity, beta, sort, ws=self.ws_sel, mass_target=mass_target)
         self.out = torch.empty_like(Q)
 
     def select(self):
         bd.basa_select(self.Q, self.K, self.w.block, self.s, self.beta, self.sort, ws=self.ws_sel,
-                       out=self.sel)
+                       out=self.sel, mass_target=self.mass_target)
 
     def attn(self):
         s = self.sel
@@ -119,8 +119,45 @@ def attainable_mfma(dev, iters=60000):
     return rates
 
 
-def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK):
-    pipe = Pipeline(w, sparsity, Q, K, V, beta, sort)
+def fidelity_report(w, Q, K, sparsities):
+    """How much of the dense attention mass the selected blocks hold (recall of the oracle block
+    distribution, Eq. 3), how far m' is from it (l1), and how well the norm bound U (Eq. 8)
+    tracks the observed logit deviation (Pearson R, as in Fig. 2) - for the four combinations
+    of norm sorting and covariance compensation, on this workload's synthetic tensors."""
+    dev = Q.device
+    rows = []
+    for sort, sort_name in ((bd.SORT_NONE, "none"), (bd.SORT_QK, "QK")):
+        base = bd.basa_select(Q, K, w.block, 0.5, beta=0.0, sort=sort, want_scores=True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        m_hat, max_dev, _ = bd.basa_block_mass(Q, K, w.block, base.perm_q, base.perm_k,
+                                               base_logits=base.scores, want_dev=True)
+        e1.record()
+        rq, mq = bd.basa_block_radius(Q, w.block, base.perm_q)
+        rk, mk = bd.basa_block_radius(K, w.block, base.perm_k)
+        U = bd.basa_deviation_bound(rq, mq, rk, mk, w.d)
+        n, sx, sy, sxx, syy, sxy = bd.basa_pearson_sums(U, max_dev).cpu().tolist()
+        pearson = (n * sxy - sx * sy) / max(1e-300, ((n * sxx - sx * sx) * (n * syy - sy * sy)) ** 0.5)
+        mass_ms = e0.elapsed_time(e1)
+        mass_flops = 2 * 2.0 * w.heads_q * w.L * w.L * w.d          # two QK^T passes
+        for beta in (0.0, 1.0):
+            for s in sparsities:
+                sel = base if (beta == 0.0 and s == 0.5) else bd.basa_select(Q, K, w.block, s, beta=beta, sort=sort,
+                                                                             want_scores=True)
+                recall, l1 = bd.basa_selection_fidelity(sel.scores, sel.mask_bits, m_hat)
+                rows.append({"workload": w.name, "sort": sort_name, "beta": beta, "sparsity": s,
+                             "kept_fraction": sel.kappa / sel.n_k, "recall_mean": float(recall.mean()),
+                             "recall_min": float(recall.min()), "l1_mean": float(l1.mean()),
+                             "bound_mean": float(U.mean()), "observed_dev_mean": float(max_dev.mean()),
+                             "pearson_bound_vs_observed": pearson, "block_mass_ms": mass_ms,
+                             "block_mass_tflops": mass_flops / (mass_ms * 1e-3) / 1e12})
+        del m_hat, max_dev, U, base
+        torch.cuda.empty_cache()
+    return rows
+
+
+def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK, mass_target=0.0):
+    pipe = Pipeline(w, sparsity, Q, K, V, beta, sort, mass_target)
     for _ in range(warmup):
         pipe.step()
     torch.cuda.synchronize()
@@ -139,11 +176,16 @@ def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd
     kern_per_step = {k: ms / steps for k, (ms, cnt) in prof.items() if cnt}
     kappa = pipe.sel.kappa
     fl_exec = executed_flops(w, kappa)
+    kept_mean = float(kappa)
+    if mass_target > 0.0:       # rows keep different numbers of blocks: count the executed pairs
+        kept_mean = float(pipe.sel.row_count.double().mean())
+        fl_exec = 4.0 * w.block * float(pipe.sel.row_count.sum()) * min(w.block, w.L) * w.d
     fl_dense = 4.0 * w.heads_q * float(w.L) ** 2 * w.d
     attn_kernel_s = kern_ms.get("attn_mfma_kernel", 0.0) * 1e-3
     sb = selection_bytes(w)
     res = dict(
-        workload=w.name, sparsity=sparsity, kappa=kappa, n_blocks=w.n_blocks,
+        workload=w.name, sparsity=sparsity, kappa=kappa, n_blocks=w.n_blocks, mass_target=mass_target,
+        kept_blocks_per_row_mean=kept_mean,
         t_e2e_ms=t_step * 1e3, t_select_ms=t_sel * 1e3, t_attn_ms=t_att * 1e3,
         t_dense_ms=None if t_dense is None else t_dense * 1e3,
         speedup_vs_dense=None if t_dense is None else t_dense / t_step,
@@ -211,6 +253,10 @@ def main():
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--fidelity", action="store_true",
+                    help="instead of timing the path: selection-fidelity diagnostics (recall of the dense "
+                         "attention mass, l1 distance, bound-vs-deviation correlation) for every bf16 "
+                         "configuration; table written to gpurun_out/fidelity.json")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 4 GiB device copies: the known-size kernel against which "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -231,6 +277,20 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
+    if args.fidelity:
+        table = []
+        for c in synth.CONFIGS:
+            if c.dtype != "bf16" or c.d != 128:
+                continue
+            q2, k2, _ = synth.make_qkv(c, device=dev)
+            table += fidelity_report(c, q2, k2, c.sparsities if 0.5 in c.sparsities else (0.5,) + tuple(c.sparsities))
+            del q2, k2
+            torch.cuda.empty_cache()
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "fidelity.json"), "w") as f:
+            json.dump(table, f, indent=1)
+        print(json.dumps({"fidelity_rows": len(table), "table": table}))
         return
     w = synth.CONFIGS[args.config]
     Q, K, V = synth.make_qkv(w, device=dev)
@@ -277,6 +337,9 @@ def main():
                 rows.append(measure(w, s, Q, K, V, 2, 1, dense_reps=0)[0])
         rows.append(measure(w, args.sparsity, Q, K, V, 2, 1, dense_reps=0, beta=0.0)[0] | {"variant": "beta=0"})
         rows.append(measure(w, args.sparsity, Q, K, V, 2, 1, dense_reps=0, sort=bd.SORT_NONE)[0] | {"variant": "sort=none"})
+        for p_mass in (0.5, 0.9):
+            rows.append(measure(w, 0.0, Q, K, V, 2, 1, dense_reps=0, mass_target=p_mass)[0]
+                        | {"variant": f"cumulative mass {p_mass}"})
         del Q, K, V
         torch.cuda.empty_cache()
         for c in synth.CONFIGS:
