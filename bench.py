@@ -6,7 +6,7 @@ in HBM: basa_select (norm sort, block pooling, compensated score map, top-kappa)
 by basa_sparse_attn (gather + bf16-MFMA block-sparse attention).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--sparsity 0.5]
-                    [--sweep] [--no-cpu-baseline] [--fidelity]
+                    [--sweep] [--no-cpu-baseline] [--fidelity] [--sweep-len]
 
 --sweep additionally times every configuration / sparsity of the benchmark and writes the
 table to gpurun_out/bench_sweep.json (the printed line stays the headline workload).
@@ -253,6 +253,10 @@ def main():
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--sweep-len", action="store_true",
+                    help="instead of the headline line: the sequence-length sweep of the paper's operator "
+                         "benchmark (Sec. 4.3, Fig. 4 axes), L = 16K .. 256K on the 128K workload's generator, "
+                         "sparse vs our dense at several sparsities; table written to gpurun_out/bench_len_sweep.json")
     ap.add_argument("--fidelity", action="store_true",
                     help="instead of timing the path: selection-fidelity diagnostics (recall of the dense "
                          "attention mass, l1 distance, bound-vs-deviation correlation) for every bf16 "
@@ -277,6 +281,28 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
+    if args.sweep_len:
+        table = []
+        for L in (16384, 32768, 65536, 131072, 262144):
+            c = synth.CONFIGS[4].scaled(f"dlm_len_{L // 1024}k", L=L)
+            q2, k2, v2 = synth.make_qkv(c, device=dev)
+            first = True
+            for s_ in (0.5, 0.75, 0.9):
+                r = measure(c, s_, q2, k2, v2, 2, 1, dense_reps=1 if first else 0)[0]
+                if first:
+                    t_dense = r["t_dense_ms"]
+                first = False
+                r["t_dense_ms"], r["speedup_vs_dense"] = t_dense, t_dense / r["t_e2e_ms"]
+                table.append({k: r[k] for k in ("workload", "sparsity", "kappa", "n_blocks", "t_e2e_ms", "t_select_ms",
+                                                "t_attn_ms", "t_dense_ms", "speedup_vs_dense", "effective_tflops",
+                                                "executed_tflops_attn_call", "dense_tflops")})
+            del q2, k2, v2
+            torch.cuda.empty_cache()
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_len_sweep.json"), "w") as f:
+            json.dump(table, f, indent=1)
+        print(json.dumps({"len_sweep_rows": len(table), "table": table}))
         return
     if args.fidelity:
         table = []
