@@ -77,6 +77,8 @@ def test_select_argument_validation(lib):
     assert call(q, k, bd.params(128, 1.0))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, window=100))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, sort=7))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(fake_tensor(L=0), k, p)[0] == "BASA_ERR_INVALID_ARG"            # empty sequence
+    assert call(q, fake_tensor(L=4097 * 128), p)[0] == "BASA_ERR_UNSUPPORTED"   # more than 4096 key blocks
     assert call(q, k, bd.params(128, 0.5, mass_target=1.5))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=-0.1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=0.9, min_keep=-1))[0] == "BASA_ERR_INVALID_ARG"

@@ -1,0 +1,129 @@
+"""GPU parity on the edges of the path: degenerate lengths (a single short block, one token),
+batch > 1 with strided batches, inputs that tie everywhere, and the largest block map the
+library accepts (4096 key blocks per row)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import basa_oracle as o
+from paper_2605_19726_amd import binding as bd
+from paper_2605_19726_amd import synth
+from parity_util import check_output, mask_report, np64, unpack_mask
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+C = synth.CONFIGS
+
+
+def _randn(shape, seed, dtype):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn(shape, generator=g).to(dtype).to(DEV)
+
+
+def _full_check(Q, K, V, block, s, bf16, what):
+    """select + attention of [1, H, L, d] tensors against the oracle, every head, every row."""
+    sel = bd.basa_select(Q, K, block, s, want_scores=True)
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k)
+    torch.cuda.synchronize()
+    gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
+    group = Q.shape[1] // K.shape[1]
+    for h in range(Q.shape[1]):
+        q, k, v = np64(Q[0, h]), np64(K[0, h // group]), np64(V[0, h // group])
+        ref = o.select(q, k, block, s)
+        assert np.array_equal(sel.perm_q[0, h].cpu().numpy(), ref["perm_q"]), what
+        assert np.array_equal(sel.perm_k[0, h // group].cpu().numpy(), ref["perm_k"]), what
+        assert mask_report(gpu_mask[0, h], ref)[0] == 0, what
+        assert (sel.row_count[0, h].cpu().numpy() == ref["kappa"]).all(), what
+        cols = sel.row_cols[0, h].cpu().numpy().astype(np.int64)
+        O_ref = o.sparse_attention(q, k, v, ref["perm_q"], ref["perm_k"], cols, block)
+        check_output(np64(out[0, h]), O_ref, bf16, what)
+
+
+@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 127, 128, 129, 257])
+@pytest.mark.parametrize("block", [64, 128])
+def test_degenerate_lengths_bf16(L, block):
+    Q, K, V = (_randn((1, 2, L, 128), 100 + i + L, torch.bfloat16) for i in range(3))
+    _full_check(Q, K, V, block, 0.5, True, f"bf16 L={L} B={block}")
+
+
+@pytest.mark.parametrize("L", [1, 3, 64, 65, 130])
+def test_degenerate_lengths_f32(L):
+    Q, K, V = (_randn((1, 1, L, 64), 200 + i + L, torch.float32) for i in range(3))
+    _full_check(Q, K, V, 64, 0.5, False, f"f32 L={L}")
+
+
+def test_short_queries_long_keys_and_the_reverse():
+    K, V = _randn((1, 2, 1000, 128), 301, torch.bfloat16), _randn((1, 2, 1000, 128), 302, torch.bfloat16)
+    Q = _randn((1, 2, 5, 128), 303, torch.bfloat16)
+    _full_check(Q, K, V, 128, 0.75, True, "5 queries, 1000 keys")
+    _full_check(K, Q, Q, 128, 0.0, True, "1000 queries, 5 keys")
+
+
+def test_inputs_that_tie_everywhere():
+    """All tokens identical (every norm, every block logit ties), and all-zero queries: the order
+    of equal keys is the original order, equal logits keep the lower block indices, attention
+    over equal scores is the mean of the kept values."""
+    L, block = 1024, 128           # full blocks only: every block mean is exact, so the logits tie bit for bit
+    row = _randn((1, 1, 1, 128), 401, torch.bfloat16)
+    same = row.expand(1, 1, L, 128).contiguous()
+    V = _randn((1, 1, L, 128), 402, torch.bfloat16)
+    _full_check(same, same, V, block, 0.5, True, "identical tokens")
+    sel = bd.basa_select(same, same, block, 0.5)
+    assert torch.equal(sel.perm_q[0, 0].cpu(), torch.arange(L, dtype=torch.int32))
+    assert sel.row_cols[0, 0, 0].cpu().tolist() == list(range(sel.kappa))
+    zeros = torch.zeros_like(same)
+    _full_check(zeros, V, V, block, 0.5, True, "zero queries")
+
+
+def test_batch_two_with_strided_batches():
+    """Two batches living in one buffer with a gap between them: each batch must come out exactly
+    as it does when passed alone, and batch 1 must match the oracle."""
+    w = C[4].scaled("batch2", heads_q=2, heads_kv=2, L=1024 + 128 + 9)
+    parts = [synth.make_qkv(w.scaled(f"b{i}", index=40 + i), device=DEV) for i in range(2)]
+    def pack(i):
+        buf = torch.zeros((2, w.heads_q + 1, w.L, w.d), dtype=parts[0][i].dtype, device=DEV)   # padded head axis
+        buf[0, :w.heads_q], buf[1, :w.heads_q] = parts[0][i][0], parts[1][i][0]
+        return buf[:, :w.heads_q]
+    Q, K, V = pack(0), pack(1), pack(2)
+    assert not Q.is_contiguous()
+    sel = bd.basa_select(Q, K, w.block, 0.5)
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+    for b in range(2):
+        q1, k1, v1 = parts[b]
+        s1 = bd.basa_select(q1, k1, w.block, 0.5)
+        o1 = bd.basa_sparse_attn(q1, k1, v1, s1.row_count, s1.row_cols, w.block, s1.perm_q, s1.perm_k)
+        assert torch.equal(sel.perm_q[b], s1.perm_q[0]) and torch.equal(sel.perm_k[b], s1.perm_k[0])
+        assert torch.equal(sel.mask_bits[b], s1.mask_bits[0]) and torch.equal(sel.row_cols[b], s1.row_cols[0])
+        assert torch.equal(out[b], o1[0])
+    _full_check(Q[1:2], K[1:2], V[1:2], w.block, 0.5, True, "batch 1 of 2")
+
+
+def test_largest_block_map():
+    """4096 key blocks per row (the limit of the row-selection kernel and of the attention
+    kernel's block-list storage in LDS): selection on every row, attention on sampled query blocks."""
+    block, n = 64, 4096
+    L = n * block - 13                         # ragged last block
+    w = C[1].scaled("max_blocks", heads_q=1, heads_kv=1, L=L, salient_frac=0.01)
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    s = 0.9
+    sel = bd.basa_select(Q, K, block, s, want_scores=True)
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k)
+    torch.cuda.synchronize()
+    assert sel.n_k == n
+    q, k, v = np64(Q[0, 0]), np64(K[0, 0]), np64(V[0, 0])
+    ref = o.select(q, k, block, s)
+    assert np.array_equal(sel.perm_q[0, 0].cpu().numpy(), ref["perm_q"])
+    assert np.array_equal(sel.perm_k[0, 0].cpu().numpy(), ref["perm_k"])
+    sc = sel.scores[0, 0].cpu().numpy().astype(np.float64)
+    assert np.abs(sc - ref["logits"]).max() <= 1e-5 * max(1.0, np.abs(ref["logits"]).max())
+    assert mask_report(unpack_mask(sel.mask_bits, n)[0, 0], ref)[0] == 0
+    cols = sel.row_cols[0, 0].cpu().numpy().astype(np.int64)
+    out_h = np64(out[0, 0])
+    rng = np.random.default_rng(5)
+    for g in [0, n - 1] + rng.integers(n, size=6).tolist():
+        rows, O_ref, _ = o.sparse_attention_block(q, k, v, ref["perm_q"], ref["perm_k"], g, cols[g], block)
+        check_output(out_h[rows], O_ref, True, f"query block {g}")
+    with pytest.raises(bd.BasaError) as e:     # one block more is refused, not mishandled
+        Kbig = torch.zeros((1, 1, (n + 1) * block, 128), dtype=torch.bfloat16, device=DEV)
+        bd.basa_select(Q, Kbig, block, s)
+    assert e.value.status_name == "BASA_ERR_UNSUPPORTED"
