@@ -31,7 +31,7 @@ std::mutex g_prof_mu;
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof_recs;
 const char* const kKernelNames[K_COUNT] = {
-    "norm_keys_kernel", "tile_sort_kernel", "merge_pass_kernel", "block_stats_kernel",
+    "norm_tile_sort_kernel", "merge_pass_kernel", "block_stats_kernel",
     "block_scores_kernel", "row_select_kernel", "gather_kernels", "attn_mfma_kernel",
     "attn_simple_kernel", "block_mass_kernel", "diagnostic_small_kernels"};
 }  // namespace

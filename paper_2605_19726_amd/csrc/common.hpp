@@ -41,7 +41,7 @@ basa_status hip_fail(hipError_t e, const char* what);
 // ---- optional per-kernel timing (basa_profile_*): a scope object brackets one launch
 // with a pair of HIP events on the launch stream when profiling is enabled.
 enum KernelId {
-  K_NORM_KEYS = 0, K_TILE_SORT, K_MERGE, K_STATS, K_SCORES, K_ROW_SELECT, K_GATHER, K_ATTN,
+  K_NORM_TILE_SORT = 0, K_MERGE, K_STATS, K_SCORES, K_ROW_SELECT, K_GATHER, K_ATTN,
   K_ATTN_SIMPLE, K_BLOCK_MASS, K_DIAG_SMALL, K_COUNT
 };
 struct ProfScope {

@@ -17,100 +17,35 @@ constexpr int kMergeItems = 8;       // outputs per thread in a merge pass
 constexpr int kMergeChunk = kSortThreads * kMergeItems;   // 2048 outputs per workgroup
 
 // ---------------------------------------------------------------------------------
-// Keys.  A row of d elements is 16-byte chunks spread over LPR adjacent lanes.
-// ---------------------------------------------------------------------------------
+// Keys + tile sort in one kernel.  A workgroup owns one tile of up to kTile consecutive tokens
+// of a segment: it streams their rows (a row of d elements is 16-byte chunks spread over LPR
+// adjacent lanes; two batches of 8 rows per thread in flight), writes the packed (key, index)
+// words into LDS, sorts them there with a bitonic network, and writes the sorted tile (or,
+// when the tile is the whole segment, the permutation itself).  Workgroups of a compute unit
+// are in different phases, so the LDS-bound sort of one hides under the HBM-bound key pass of
+// the others.
+// Segment s of a head covers [s*W, min((s+1)*W, L)); tiles never straddle segments.
 // Up to two tensors of the same L, d and dtype are handled by one launch: rows blockIdx.y <
 // BH0 belong to x0, the rest to x1; packed words and permutations of x1 follow those of x0.
-template <bool kBf16, int kD>
-__global__ __launch_bounds__(256) void norm_keys_kernel(TensorView x0, TensorView x1, int BH0,
-                                                        uint64_t* __restrict__ packed,
-                                                        float* __restrict__ keys_out) {
-  constexpr int kElem = kBf16 ? 2 : 4;
-  constexpr int LPR = kD * kElem / 16;          // lanes per row: 8, 16 or 32
-  constexpr int kRowsPerIter = 256 / LPR;
-  constexpr int kIters = 8;
-  const int bh = blockIdx.y;
-  const bool second = bh >= BH0;
-  const TensorView& x = second ? x1 : x0;
-  const int L = x.L;
-  const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(second ? bh - BH0 : bh) * kElem;
-  const int sub = threadIdx.x % LPR;
-  const int rig = threadIdx.x / LPR;
-  const int row0 = blockIdx.x * (kRowsPerIter * kIters) + rig;
-
-  uint4 raw[kIters];
-#pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    int row = row0 + it * kRowsPerIter;
-    raw[it] = make_uint4(0u, 0u, 0u, 0u);
-    if (row < L) raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)row * x.stride_l * kElem)[sub];
-  }
-  // per-lane partial sums of the kIters rows this lane contributes to
-  double acc[kIters];
-#pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    acc[it] = 0.0;
-    const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if constexpr (kBf16) {
-        // |x| as a double, built from the 15 exponent+mantissa bits of the bf16 (the float to
-        // double conversion instruction is many times slower than these two integer ops): the
-        // high word of the double is bits << 13 plus the exponent rebias (1023-127) << 20, the
-        // low word is zero.  A zero or subnormal bf16 (exponent field 0) comes out as a value
-        // below 2^-126 instead; its square, below 2^-252, is lost against any sum that can
-        // round to a non-zero fp32 key (>= 2^-150), exactly as the true square would be.
-        const double lo = __hiloint2double((int)((__builtin_amdgcn_ubfe(w[i], 0, 15) << 13) + 0x38000000u), 0);
-        const double hi = __hiloint2double((int)((__builtin_amdgcn_ubfe(w[i], 16, 15) << 13) + 0x38000000u), 0);
-        acc[it] = fma(lo, lo, acc[it]);
-        acc[it] = fma(hi, hi, acc[it]);
-      } else {
-        const double v = (double)__uint_as_float(w[i]);
-        acc[it] = fma(v, v, acc[it]);
-      }
-    }
-  }
-  // Reduction over the LPR lanes of a row, all kIters rows at once: in the step with lane
-  // distance 2^b a lane hands the half of its partial sums that its partner keeps to the
-  // partner and halves its own set (8 -> 4 -> 2 -> 1 sums in 7 exchanges instead of 24), so
-  // that after three steps lane `sub` holds one row, iteration 4*bit0 + 2*bit1 + bit2 of sub.
-  static_assert(kIters == 8 && LPR >= 8, "the exchange pattern below is written for 8 rows");
-#pragma unroll
-  for (int b = 0; b < 3; ++b) {
-    const bool upper = (sub >> b) & 1;
-    const int n = kIters >> (b + 1);
-#pragma unroll
-    for (int i = 0; i < n; ++i) {
-      const double give = upper ? acc[i] : acc[i + n];
-      const double keep = upper ? acc[i + n] : acc[i];
-      acc[i] = keep + __shfl_xor(give, 1 << b, LPR);
-    }
-  }
-#pragma unroll
-  for (int off = 8; off < LPR; off <<= 1) acc[0] += __shfl_xor(acc[0], off, LPR);
-  const int it_mine = 4 * (sub & 1) + (sub & 2) + ((sub >> 2) & 1);
-  const int row = row0 + it_mine * kRowsPerIter;
-  if (sub < 8 && row < L) {
-    const float key = (float)acc[0];
-    packed[(int64_t)bh * L + row] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)row;
-    if (keys_out) keys_out[(int64_t)bh * L + row] = key;
-  }
-}
-
-// ---------------------------------------------------------------------------------
-// Tile sort: bitonic network over kTile packed words in LDS.
-// Segment s of a head covers [s*W, min((s+1)*W, L)); tiles never straddle segments.
 // ---------------------------------------------------------------------------------
 struct SegGeom {
   int L, W, segs, tiles_per_seg;
 };
 
-__global__ __launch_bounds__(kSortThreads) void tile_sort_kernel(const uint64_t* __restrict__ in,
-                                                                 uint64_t* __restrict__ out,
-                                                                 int32_t* __restrict__ perm0,
-                                                                 int32_t* __restrict__ perm1, int BH0,
-                                                                 SegGeom g) {
+template <bool kBf16, int kD>
+__global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView x0, TensorView x1, int BH0,
+                                                                      uint64_t* __restrict__ out,
+                                                                      int32_t* __restrict__ perm0,
+                                                                      int32_t* __restrict__ perm1,
+                                                                      float* __restrict__ keys_out, SegGeom g) {
+  constexpr int kElem = kBf16 ? 2 : 4;
+  constexpr int LPR = kD * kElem / 16;          // lanes per row: 8, 16 or 32
+  constexpr int kRowsPerIter = kSortThreads / LPR;
+  constexpr int kIters = 8;
+  constexpr int kRowsPerPass = kRowsPerIter * kIters;
+  static_assert(kTile % kRowsPerPass == 0, "a tile is a whole number of passes");
   __shared__ uint64_t buf[kTile];
+
   const int bh = blockIdx.y;
   const int seg = blockIdx.x / g.tiles_per_seg;
   const int tile = blockIdx.x - seg * g.tiles_per_seg;
@@ -119,12 +54,84 @@ __global__ __launch_bounds__(kSortThreads) void tile_sort_kernel(const uint64_t*
   if (start >= seg_end) return;
   const int n = min(kTile, seg_end - start);
   const int64_t hb = (int64_t)bh * g.L;
-  int32_t* perm_out = bh < BH0 ? perm0 : (perm1 ? perm1 - (int64_t)BH0 * g.L : nullptr);
+  const bool second = bh >= BH0;
+  const TensorView& x = second ? x1 : x0;
+  int32_t* perm_out = second ? (perm1 ? perm1 - (int64_t)BH0 * g.L : nullptr) : perm0;
+  const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(second ? bh - BH0 : bh) * kElem;
+  const int sub = threadIdx.x % LPR;
+  const int rig = threadIdx.x / LPR;
 
-  for (int i = threadIdx.x; i < kTile; i += kSortThreads)
-    buf[i] = (i < n) ? in[hb + start + i] : ~0ull;
+  // ---- phase 1: keys of tokens start .. start+n-1 into buf
+  auto load_pass = [&](int pass, uint4 (&raw)[kIters]) {
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      const int loc = pass * kRowsPerPass + it * kRowsPerIter + rig;
+      raw[it] = make_uint4(0u, 0u, 0u, 0u);
+      if (loc < n) raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)(start + loc) * x.stride_l * kElem)[sub];
+    }
+  };
+  const int passes = (n + kRowsPerPass - 1) / kRowsPerPass;
+  uint4 cur[kIters], nxt[kIters];
+  load_pass(0, cur);
+  for (int pass = 0; pass < passes; ++pass) {
+    if (pass + 1 < passes) load_pass(pass + 1, nxt);
+    // per-lane partial sums of the kIters rows this lane contributes to
+    double acc[kIters];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      acc[it] = 0.0;
+      const uint32_t w[4] = {cur[it].x, cur[it].y, cur[it].z, cur[it].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (kBf16) {
+          // |x| as a double, built from the 15 exponent+mantissa bits of the bf16 (the float to
+          // double conversion instruction is many times slower than these two integer ops): the
+          // high word of the double is bits << 13 plus the exponent rebias (1023-127) << 20, the
+          // low word is zero.  A zero or subnormal bf16 (exponent field 0) comes out as a value
+          // below 2^-126 instead; its square, below 2^-252, is lost against any sum that can
+          // round to a non-zero fp32 key (>= 2^-150), exactly as the true square would be.
+          const double lo = __hiloint2double((int)((__builtin_amdgcn_ubfe(w[i], 0, 15) << 13) + 0x38000000u), 0);
+          const double hi = __hiloint2double((int)((__builtin_amdgcn_ubfe(w[i], 16, 15) << 13) + 0x38000000u), 0);
+          acc[it] = fma(lo, lo, acc[it]);
+          acc[it] = fma(hi, hi, acc[it]);
+        } else {
+          const double v = (double)__uint_as_float(w[i]);
+          acc[it] = fma(v, v, acc[it]);
+        }
+      }
+    }
+    // Reduction over the LPR lanes of a row, all kIters rows at once: in the step with lane
+    // distance 2^b a lane hands the half of its partial sums that its partner keeps to the
+    // partner and halves its own set (8 -> 4 -> 2 -> 1 sums in 7 exchanges instead of 24), so
+    // that after three steps lane `sub` holds one row, iteration 4*bit0 + 2*bit1 + bit2 of sub.
+    static_assert(kIters == 8 && LPR >= 8, "the exchange pattern below is written for 8 rows");
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+      const bool upper = (sub >> b) & 1;
+      const int m = kIters >> (b + 1);
+#pragma unroll
+      for (int i = 0; i < m; ++i) {
+        const double give = upper ? acc[i] : acc[i + m];
+        const double keep = upper ? acc[i + m] : acc[i];
+        acc[i] = keep + __shfl_xor(give, 1 << b, LPR);
+      }
+    }
+#pragma unroll
+    for (int off = 8; off < LPR; off <<= 1) acc[0] += __shfl_xor(acc[0], off, LPR);
+    const int it_mine = 4 * (sub & 1) + (sub & 2) + ((sub >> 2) & 1);
+    const int loc = pass * kRowsPerPass + it_mine * kRowsPerIter + rig;
+    if (sub < 8 && loc < n) {
+      const float key = (float)acc[0];
+      buf[loc] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)(start + loc);
+      if (keys_out) keys_out[hb + start + loc] = key;
+    }
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) cur[it] = nxt[it];
+  }
+  for (int i = n + threadIdx.x; i < kTile; i += kSortThreads) buf[i] = ~0ull;
   __syncthreads();
 
+  // ---- phase 2: bitonic network over the kTile words
   for (int k = 2; k <= kTile; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
       for (int p = threadIdx.x; p < kTile / 2; p += kSortThreads) {
@@ -241,21 +248,7 @@ static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, in
                                                align_up((size_t)BH * L * sizeof(uint64_t), 256));
   const TensorView& xb = x1 ? *x1 : x0;
   const bool bf16 = x0.dtype == BASA_BF16;
-  const int elem = bf16 ? 2 : 4;
-  const int lpr = x0.d * elem / 16;
-  const int rows_per_wg = (256 / lpr) * 8;
-  dim3 kgrid(ceil_div(L, rows_per_wg), BH);
-  {
-  ProfScope prof(K_NORM_KEYS, st);
-#define BASA_KEYS(BF, D) \
-  hipLaunchKernelGGL((norm_keys_kernel<BF, D>), kgrid, dim3(256), 0, st, x0, xb, BH0, buf0, keys_out)
-  if (bf16 && x0.d == 128) BASA_KEYS(true, 128);
-  else if (bf16 && x0.d == 64) BASA_KEYS(true, 64);
-  else if (!bf16 && x0.d == 128) BASA_KEYS(false, 128);
-  else BASA_KEYS(false, 64);
-#undef BASA_KEYS
-  BASA_HIP_CHECK_LAUNCH("norm_keys_kernel");
-  }
+  (void)buf0;
 
   SegGeom g;
   g.L = L;
@@ -264,10 +257,17 @@ static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, in
   g.tiles_per_seg = ceil_div(g.W, kTile);
   const bool single = g.tiles_per_seg == 1;
   {
-  ProfScope prof(K_TILE_SORT, st);
-  hipLaunchKernelGGL(tile_sort_kernel, dim3(g.segs * g.tiles_per_seg, BH), dim3(kSortThreads), 0, st,
-                     buf0, buf1, single ? perm0 : nullptr, single ? perm1 : nullptr, BH0, g);
-  BASA_HIP_CHECK_LAUNCH("tile_sort_kernel");
+  ProfScope prof(K_NORM_TILE_SORT, st);
+  const dim3 grid(g.segs * g.tiles_per_seg, BH);
+#define BASA_KEYS(BF, D)                                                                              \
+  hipLaunchKernelGGL((norm_tile_sort_kernel<BF, D>), grid, dim3(kSortThreads), 0, st, x0, xb, BH0, buf1, \
+                     single ? perm0 : nullptr, single ? perm1 : nullptr, keys_out, g)
+  if (bf16 && x0.d == 128) BASA_KEYS(true, 128);
+  else if (bf16 && x0.d == 64) BASA_KEYS(true, 64);
+  else if (!bf16 && x0.d == 128) BASA_KEYS(false, 128);
+  else BASA_KEYS(false, 64);
+#undef BASA_KEYS
+  BASA_HIP_CHECK_LAUNCH("norm_tile_sort_kernel");
   }
   if (single) return BASA_OK;
 
