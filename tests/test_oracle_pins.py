@@ -501,3 +501,32 @@ def test_selection_fidelity_limits():
         assert abs(recall[r] - sum(m_hat[r, c] for c in sel["cols"][r])) < 1e-15
     _, zero = o.selection_fidelity(m_hat, sel["mask"], m_hat)
     assert np.abs(zero).max() == 0.0
+
+
+# ---------------------------------------------------------------- drift guard (no paper values: see the script's header)
+def test_oracle_reproduces_its_stored_tiny_results():
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_oracle_fixtures", os.path.join(here, "make_oracle_fixtures.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.compute()
+    with open(os.path.join(here, "oracle_tiny.json")) as f:
+        stored = json.load(f)
+
+    def same(a, b, path):
+        if isinstance(a, dict):
+            assert a.keys() == b.keys(), path
+            for k in a:
+                same(a[k], b[k], f"{path}/{k}")
+        elif isinstance(a, list):
+            assert len(a) == len(b), path
+            for i, (x, y) in enumerate(zip(a, b)):
+                same(x, y, f"{path}[{i}]")
+        elif isinstance(a, float):
+            assert abs(a - b) <= 1e-12 * max(1.0, abs(a)), f"{path}: {a} vs {b}"
+        else:
+            assert a == b, f"{path}: {a} vs {b}"
+    same(now, stored, "")
