@@ -106,3 +106,57 @@ def test_full_size_dense_entry_sampled():
         rows = np.arange(g * w.block, (g + 1) * w.block)
         ref = o.dense_attention(q[rows], k, v)
         check_output(np64(out[0, h, rows]), ref, True, f"dense block {g}")
+
+
+def test_full_size_cumulative_mass_selection():
+    """Cumulative-mass selection at the largest configuration: per-row counts on four heads against
+    the oracle (inside the mass band), the kept sets being the rows' top-count sets."""
+    w = synth.CONFIGS[4]
+    Q, K, _ = synth.make_qkv(w, device=DEV)
+    p_mass, band = 0.6, 1e-5
+    sel = bd.basa_select(Q, K, w.block, 0.0, mass_target=p_mass, min_keep=8)
+    torch.cuda.synchronize()
+    mask = unpack_mask(sel.mask_bits, sel.n_k)
+    for h in (0, 7, 19, 31):
+        ref = o.select(np64(Q[0, h]), np64(K[0, h]), w.block, 0.0, mass_target=p_mass, min_keep=8)
+        cnt = sel.row_count[0, h].cpu().numpy()
+        cum, m = ref["cum"], ref["m"]
+        rows = np.arange(m.shape[0])
+        enough = (cnt == ref["kappa"]) | (cum[rows, cnt - 1] >= p_mass - band)
+        minimal = (cnt == 8) | (cum[rows, np.maximum(cnt - 2, 0)] < p_mass + band)
+        assert enough.all() and minimal.all(), f"head {h}: counts outside the band"
+        order = np.argsort(-m, axis=1, kind="stable")
+        for r in range(m.shape[0]):
+            want = np.zeros(m.shape[1], dtype=bool)
+            want[order[r, :cnt[r]]] = True
+            diff = want != mask[0, h, r]
+            if diff.any():
+                theta = m[r, order[r, cnt[r] - 1]]
+                assert (np.abs(m[r, diff] - theta) <= 1e-5 * theta).all(), f"head {h} row {r}"
+        print(f"\n[cfg4 mass {p_mass}] head {h}: kept per row min {cnt.min()} mean {cnt.mean():.1f} max {cnt.max()}, "
+              f"rows off the fp64 count: {(cnt != ref['count']).sum()}")
+
+
+def test_full_size_block_mass_sampled():
+    """Oracle block distribution (Eq. 3) at 128K on the GPU, checked on sampled query blocks of two
+    heads against the oracle's dense attention rows of those queries."""
+    w = synth.CONFIGS[4]
+    Q, K, _ = synth.make_qkv(w, device=DEV)
+    sel = bd.basa_select(Q, K, w.block, 0.5, beta=0.0, want_scores=True)
+    m_hat, dev, _ = bd.basa_block_mass(Q, K, w.block, sel.perm_q, sel.perm_k, base_logits=sel.scores, want_dev=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(m_hat.sum(-1).cpu().numpy(), 1.0, atol=5e-5)
+    B, n = w.block, w.n_blocks
+    for h in (3, 30):
+        q = np64(Q[0, h])[sel.perm_q[0, h].cpu().numpy()]
+        k = np64(K[0, h])[sel.perm_k[0, h].cpu().numpy()]
+        k_mean, _ = o.block_stats(k, B)
+        for g in (0, 500, n - 1):
+            qb = q[g * B:(g + 1) * B]
+            A = o.attention_matrix(qb, k)                               # [128, L]
+            want = A.reshape(B, n, B).sum(axis=(0, 2)) / B
+            np.testing.assert_allclose(m_hat[0, h, g].cpu().numpy(), want, rtol=3e-4, atol=1e-9)
+            l_tok = (qb @ k.T) / np.sqrt(w.d)
+            l_blk = (qb.mean(0) @ k_mean.T) / np.sqrt(w.d)
+            want_dev = np.abs(l_tok.reshape(B, n, B) - l_blk[None, :, None]).max(axis=(0, 2))
+            np.testing.assert_allclose(dev[0, h, g].cpu().numpy(), want_dev, rtol=1e-4, atol=1e-4)
