@@ -207,14 +207,25 @@ __global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t
   const int d1 = min(d0 + kMergeItems, n);
   int ia = merge_path(buf, ca, buf + ca, cb, d0);
   int ib = d0 - ia;
-  const int64_t obase = hb + a0 + diag0;
-  for (int o = d0; o < d1; ++o) {
+  // merge kMergeItems outputs into registers, then hand them back through LDS so that the
+  // global stores of the workgroup are consecutive
+  uint64_t res[kMergeItems];
+#pragma unroll
+  for (int e = 0; e < kMergeItems; ++e) {
     uint64_t va = ia < ca ? buf[ia] : ~0ull;
     uint64_t vb = ib < cb ? buf[ca + ib] : ~0ull;
-    uint64_t v;
-    if (va < vb) { v = va; ++ia; } else { v = vb; ++ib; }
-    if (perm_out) perm_out[obase + o] = (int32_t)(uint32_t)v;
-    else out[obase + o] = v;
+    if (va < vb) { res[e] = va; ++ia; } else { res[e] = vb; ++ib; }
+  }
+  __syncthreads();                       // everyone is done reading the two runs
+#pragma unroll
+  for (int e = 0; e < kMergeItems; ++e)
+    if (d0 + e < d1) buf[d0 + e] = res[e];
+  __syncthreads();
+  const int64_t obase = hb + a0 + diag0;
+  if (perm_out) {
+    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[obase + i] = (int32_t)(uint32_t)buf[i];
+  } else {
+    for (int i = threadIdx.x; i < n; i += kSortThreads) out[obase + i] = buf[i];
   }
 }
 
