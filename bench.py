@@ -9,7 +9,7 @@ by basa_sparse_attn (gather + bf16-MFMA block-sparse attention).  Prints ONE JSO
                     [--sweep] [--no-cpu-baseline] [--fidelity] [--sweep-len]
 
 --sweep additionally times every configuration / sparsity of the benchmark and writes the
-table to gpurun_out/bench_sweep.json (the printed line stays the headline workload).
+table to <out-dir>/bench_sweep.json (the printed line stays the headline workload).
 """
 from __future__ import annotations
 
@@ -253,14 +253,16 @@ def main():
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--out-dir", default=os.path.join(ROOT, "bench_out"),
+                    help="where --sweep, --sweep-len and --fidelity write their tables")
     ap.add_argument("--sweep-len", action="store_true",
                     help="instead of the headline line: the sequence-length sweep of the paper's operator "
                          "benchmark (Sec. 4.3, Fig. 4 axes), L = 16K .. 256K on the 128K workload's generator, "
-                         "sparse vs our dense at several sparsities; table written to gpurun_out/bench_len_sweep.json")
+                         "sparse vs our dense at several sparsities; table written to <out-dir>/bench_len_sweep.json")
     ap.add_argument("--fidelity", action="store_true",
                     help="instead of timing the path: selection-fidelity diagnostics (recall of the dense "
                          "attention mass, l1 distance, bound-vs-deviation correlation) for every bf16 "
-                         "configuration; table written to gpurun_out/fidelity.json")
+                         "configuration; table written to <out-dir>/fidelity.json")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain 4 GiB device copies: the known-size kernel against which "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -299,8 +301,8 @@ def main():
                                                 "executed_tflops_attn_call", "dense_tflops")})
             del q2, k2, v2
             torch.cuda.empty_cache()
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_len_sweep.json"), "w") as f:
+        os.makedirs(args.out_dir, exist_ok=True)
+        with open(os.path.join(args.out_dir, "bench_len_sweep.json"), "w") as f:
             json.dump(table, f, indent=1)
         print(json.dumps({"len_sweep_rows": len(table), "table": table}))
         return
@@ -313,8 +315,8 @@ def main():
             table += fidelity_report(c, q2, k2, c.sparsities if 0.5 in c.sparsities else (0.5,) + tuple(c.sparsities))
             del q2, k2
             torch.cuda.empty_cache()
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "fidelity.json"), "w") as f:
+        os.makedirs(args.out_dir, exist_ok=True)
+        with open(os.path.join(args.out_dir, "fidelity.json"), "w") as f:
             json.dump(table, f, indent=1)
         print(json.dumps({"fidelity_rows": len(table), "table": table}))
         return
@@ -376,8 +378,8 @@ def main():
                 rows.append(measure(c, s, q2, k2, v2, 2, 1, dense_reps=1 if s == c.sparsities[0] else 0)[0])
             del q2, k2, v2
             torch.cuda.empty_cache()
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_sweep.json"), "w") as f:
+        os.makedirs(args.out_dir, exist_ok=True)
+        with open(os.path.join(args.out_dir, "bench_sweep.json"), "w") as f:
             json.dump(rows, f, indent=1)
     print(json.dumps(line))
 
