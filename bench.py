@@ -54,8 +54,8 @@ def selection_bytes(w):
     rows = (w.heads_q + w.heads_kv) * w.L
     n = w.n_blocks
     qk = rows * w.d * e
-    passes = 1 + max(0, int(np.ceil(np.log2(max(w.L, 1) / 4096.0))))
-    sort = rows * 8 * (1 + 2 * passes)
+    merges = max(0, int(np.ceil(np.log2(max(w.L, 1) / 4096.0))))
+    sort = rows * 8 * (1 + 2 * merges)      # the tile sort writes each word once, every merge pass reads and writes it
     feats = (w.heads_q + w.heads_kv) * n * 3 * w.d * 4 * 2
     scores = w.heads_q * n * n * 4 * 2
     return dict(two_pass=2 * qk, compulsory=qk, sort=sort, small=feats + scores,
@@ -117,6 +117,22 @@ def attainable_mfma(dev, iters=60000):
         e1.synchronize()
         rates[name] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
     return rates
+
+
+def attainable_read(dev, gib=2):
+    """GB/s of a read-only 16-byte-per-lane stream over `gib` GiB (the access pattern of the key pass)."""
+    buf = torch.zeros(gib << 28, dtype=torch.int32, device=dev)
+    out = torch.zeros(4, dtype=torch.int32, device=dev)
+    bd.basa_calibrate_read(buf, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    nbytes = 0
+    for _ in range(3):
+        nbytes += bd.basa_calibrate_read(buf, out)
+    e1.record()
+    e1.synchronize()
+    return nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
 def fidelity_report(w, Q, K, sparsities):
@@ -355,6 +371,9 @@ def main():
         rates = attainable_mfma(dev)
         line["roofline"]["mfma_loop_tflops"] = rates
         line["roofline"]["frac_of_random_operand_loop"] = achieved / rates["random_operands"]
+    read_gbs = attainable_read(dev)
+    line["roofline_select"]["read_stream_gbs"] = read_gbs
+    line["roofline_select"]["frac_of_read_stream"] = res["selection_gbs_total"] / read_gbs
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, args.sparsity, Q, K, V, pipe)
     if args.sweep:

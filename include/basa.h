@@ -249,6 +249,14 @@ basa_status basa_pearson_sums(const float* x, const float* y, int64_t n, double*
 basa_status basa_calibrate_mfma(int32_t random_operands, int32_t iters, float* out, size_t out_elems,
                                 double* flops /*host*/, void* stream);
 
+/*
+ * Calibration aid: enqueues one read-only pass over `bytes` bytes of device memory at `buf`
+ * (16-byte aligned, at least 1 MiB; a tail of up to 32 KiB may be left unread), 16-byte loads,
+ * nothing written but possibly the word at `out` (device).  bytes / elapsed time is the
+ * read-only stream rate the memory system sustains.
+ */
+basa_status basa_calibrate_read(const void* buf, size_t bytes, uint32_t* out, void* stream);
+
 /* Library version, e.g. "basa 0.1 gfx950". */
 const char* basa_version(void);
 

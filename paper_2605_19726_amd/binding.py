@@ -26,7 +26,7 @@ EXPORTS = (
     "basa_sort_workspace_size", "basa_norm_sort", "basa_downsample", "basa_select",
     "basa_sparse_attn", "basa_dense_attn", "basa_status_string", "basa_last_error",
     "basa_version", "basa_profile_enable", "basa_profile_kernel_count", "basa_profile_kernel_name",
-    "basa_profile_read", "basa_calibrate_mfma", "basa_block_mass_workspace_size", "basa_block_mass",
+    "basa_profile_read", "basa_calibrate_mfma", "basa_calibrate_read", "basa_block_mass_workspace_size", "basa_block_mass",
     "basa_block_radius", "basa_deviation_bound", "basa_selection_fidelity", "basa_pearson_sums",
 )
 
@@ -107,6 +107,8 @@ def load():
     lib.basa_selection_fidelity.argtypes = [V, V, V, C.c_int64, C.c_int32, V, V, V]
     lib.basa_pearson_sums.restype = C.c_int
     lib.basa_pearson_sums.argtypes = [V, V, C.c_int64, V, V]
+    lib.basa_calibrate_read.restype = C.c_int
+    lib.basa_calibrate_read.argtypes = [V, C.c_size_t, V, V]
     lib.basa_calibrate_mfma.restype = C.c_int
     lib.basa_calibrate_mfma.argtypes = [C.c_int32, C.c_int32, V, C.c_size_t, C.POINTER(C.c_double), V]
     _lib = lib
@@ -351,3 +353,10 @@ def basa_pearson_sums(x, y):
     sums = torch.empty(6, dtype=torch.float64, device=x.device)
     _check(load().basa_pearson_sums(_ptr(x), _ptr(y), x.numel(), _ptr(sums), _stream(x)))
     return sums
+
+
+def basa_calibrate_read(buf: torch.Tensor, out: torch.Tensor) -> int:
+    """Enqueue one read-only pass over `buf` on the current stream; returns the bytes it covers."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(load().basa_calibrate_read(_ptr(buf), nbytes, _ptr(out), _stream(buf)))
+    return nbytes

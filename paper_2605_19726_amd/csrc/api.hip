@@ -429,6 +429,15 @@ basa_status basa_pearson_sums(const float* x, const float* y, int64_t n, double*
   return launch_pearson_sums(x, y, n, sums, reinterpret_cast<hipStream_t>(stream));
 }
 
+basa_status basa_calibrate_read(const void* buf, size_t bytes, uint32_t* out, void* stream) {
+  if (!buf || !out || bytes < (1u << 20) || (reinterpret_cast<uintptr_t>(buf) & 15)) {
+    set_error("basa_calibrate_read: needs a 16-byte aligned device buffer of at least 1 MiB and an output word");
+    return BASA_ERR_INVALID_ARG;
+  }
+  const hipError_t e = launch_calib_read(buf, bytes, out, (hipStream_t)stream);
+  return e == hipSuccess ? BASA_OK : hip_fail(e, "basa_calibrate_read");
+}
+
 basa_status basa_calibrate_mfma(int32_t random_operands, int32_t iters, float* out, size_t out_elems,
                                 double* flops, void* stream) {
   if (!out || iters < 1 || iters > (1 << 24)) {

@@ -1,5 +1,5 @@
-// Calibration kernel: the bf16 matrix-core rate this chip sustains, for putting the roofline
-// fraction of the attention kernel in context.  Not part of the method.
+// Calibration kernels: the bf16 matrix-core rate and the read-only HBM stream rate this chip
+// sustains, for putting the roofline fractions in context.  Not part of the method.
 //
 // A loop of independent v_mfma_f32_32x32x16_bf16 on register operands, 2 workgroups of 4 waves
 // per compute unit.  With `random_operands` the eight A and eight B fragments hold pseudo-random
@@ -59,7 +59,29 @@ __global__ __launch_bounds__(kCalibThreads) void calib_mfma_kernel(float* out, i
   out[blockIdx.x * kCalibThreads + threadIdx.x] = s;
 }
 
+// Read-only stream over a buffer: 256 workgroups per launch wave, 8 x 16 bytes in flight per thread.
+__global__ __launch_bounds__(256) void calib_read_kernel(const uint4* __restrict__ in, size_t n, uint32_t* out) {
+  constexpr int kUnroll = 8;
+  size_t i = ((size_t)blockIdx.x * kUnroll) * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256 * kUnroll;
+  uint32_t acc = 0;
+  for (; i + (kUnroll - 1) * 256 < n; i += stride) {
+    uint4 v[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) v[u] = in[i + u * 256];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (acc == 0x9e3779b9u) out[0] = acc;     // keeps the loads alive; practically never taken
+}
+
 }  // namespace
+
+hipError_t launch_calib_read(const void* buf, size_t bytes, uint32_t* out, hipStream_t stream) {
+  hipLaunchKernelGGL(calib_read_kernel, dim3(4096), dim3(256), 0, stream, reinterpret_cast<const uint4*>(buf),
+                     bytes / 16, out);
+  return hipGetLastError();
+}
 
 size_t calib_mfma_out_elems() { return (size_t)kCalibGrid * kCalibThreads; }
 

@@ -124,6 +124,7 @@ basa_status launch_pearson_sums(const float* x, const float* y, int64_t n, doubl
 size_t calib_mfma_out_elems();
 double calib_mfma_flops(int iters);
 hipError_t launch_calib_mfma(bool random_operands, int iters, float* out, hipStream_t stream);
+hipError_t launch_calib_read(const void* buf, size_t bytes, uint32_t* out, hipStream_t stream);
 
 // ---- device helpers ------------------------------------------------------------
 #if defined(__HIPCC__)
