@@ -48,7 +48,7 @@ def executed_flops(w, kappa):
 def selection_bytes(w):
     """Algorithmic HBM bytes of the selection stage: Q and K are read twice (norm pass, then the
     gather + pooling pass, which depends on the finished sort), plus the sort's key/index words
-    (one 8-byte word written by the key pass, then read and written by the tile sort and by
+    (one 8-byte word per token written by the key + tile-sort pass, then read and written by
     every merge pass), the block features, the score map and the block lists."""
     e = 2 if w.dtype == "bf16" else 4
     rows = (w.heads_q + w.heads_kv) * w.L

@@ -90,9 +90,12 @@ __global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
     __syncthreads();
     float acc_mass = 0.f, acc_dev = 0.f;     // used by threads tid < NQB in pass 1
     for (int t = 0; t < T; ++t) {
-      if (t + 1 < T) {
+      // next tile into registers (past the end: the last tile again, stored but never used;
+      // kept unconditional so that r stays in registers and the loads stay in flight)
+      {
+        const int tn = min(t + 1, T - 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r[i] = Kh[(int64_t)(t + 1) * kTileChunks + i * 256 + tid];
+        for (int i = 0; i < 4; ++i) r[i] = Kh[(int64_t)tn * kTileChunks + i * 256 + tid];
       }
       const char* ks = reinterpret_cast<const char*>(kbuf[t & 1]);
       floatx16 s0 = {0}, s1 = {0};
@@ -144,10 +147,8 @@ __global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
         dev = wave_max(dev);
         if (lane == 0) { part_mass[t & 1][wave] = sum; part_dev[t & 1][wave] = dev; }
       }
-      if (t + 1 < T) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) kbuf[(t + 1) & 1][i * 256 + tid] = r[i];
-      }
+      for (int i = 0; i < 4; ++i) kbuf[(t + 1) & 1][i * 256 + tid] = r[i];
       __syncthreads();
       if (pass == 1 && tid < NQB) {
         // thread b adds up, in a fixed order, the waves of query block b and the tiles of a key block
