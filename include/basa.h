@@ -142,7 +142,10 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
  * f32 tensors: fp32 throughout.
  *   row_count    [batch, heads_q, N_q] int32, each in [1, N_k].
  *   row_cols     [batch, heads_q, N_q, cols_stride] int32, ascending, each in [0, N_k).
- *                NULL means every key block for every row (dense).
+ *                NULL means every key block for every row (dense).  The lists are device
+ *                data the host cannot check: an entry outside [0, N_k) is ignored, a count
+ *                above cols_stride is cut to it, and a query block left without any valid
+ *                key block gets zero output rows (lse -inf).  Entries must not repeat.
  *   perm_q/_k    nullable (NULL = identity).
  *   out          [batch, heads_q, L_q, d] contiguous, dtype of q.
  *   lse          out, nullable, [batch, heads_q, L_q] float: log-sum-exp of the kept

@@ -255,9 +255,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   if (a.row_cols) {
     for (int g = 0; g < nqb; ++g) {
       const int64_t rowid = (int64_t)bhq * a.Nq + wg * NQB + g;
-      const int cnt = a.row_count[rowid];
+      const int cnt = min(a.row_count[rowid], a.cols_stride);
       const int32_t* cl = a.row_cols + rowid * a.cols_stride;
-      for (int i = tid; i < cnt; i += kThreads) atomicOr(&flags[cl[i]], 1u << g);
+      for (int i = tid; i < cnt; i += kThreads) {
+        const int col = cl[i];
+        if ((unsigned)col < (unsigned)a.Nk) atomicOr(&flags[col], 1u << g);     // anything else is ignored
+      }
     }
     __syncthreads();
   }
@@ -281,6 +284,17 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   }
   // every thread has passed its last read of flags (the ring area) and seq is complete
 
+  if (n_union == 0) {
+    // no valid key block in any list of this workgroup (malformed input): its rows become zeros
+    const int pos = gq * kB + (wave % WPG) * 32 + li;
+    if (gq < a.Nq && pos < a.Lq) {
+      const int orow = a.perm_q ? a.perm_q[(int64_t)bhq * a.Lq + pos] : pos;
+      uint4* op = reinterpret_cast<uint4*>(a.out + ((int64_t)bhq * a.Lq + orow) * kD);
+      for (int i = 0; i < 8; ++i) op[8 * h + i] = make_uint4(0u, 0u, 0u, 0u);
+      if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
+    }
+    return;
+  }
   int n_tiles = n_union * TPB;
   {
     // a ragged last key block may leave its trailing tile without any valid key
@@ -391,7 +405,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
 
   // ---- epilogue: normalise, scatter rows to their original positions
   const float l_tot = st.l_run + __shfl_xor(st.l_run, 32);
-  const float inv_l = 1.0f / l_tot;
+  const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;    // a query block without any valid key block: zeros
   const int pos = gq * kB + (wave % WPG) * 32 + li;
   if (gq < a.Nq && pos < a.Lq) {
     const int orow = a.perm_q ? a.perm_q[(int64_t)bhq * a.Lq + pos] : pos;

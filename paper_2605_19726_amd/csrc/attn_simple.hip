@@ -48,11 +48,12 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
   const char* kbase = reinterpret_cast<const char*>(a.k.ptr) + a.k.head_offset(bhk) * kElem;
   const char* vbase = reinterpret_cast<const char*>(a.v.ptr) + a.v.head_offset(bhk) * kElem;
   const int64_t rowid = (int64_t)bhq * Nq + gq;
-  const int count = a.row_cols ? a.row_count[rowid] : Nk;
+  const int count = a.row_cols ? min(a.row_count[rowid], a.cols_stride) : Nk;
   const int32_t* cols = a.row_cols ? a.row_cols + rowid * a.cols_stride : nullptr;
 
   for (int ci = 0; ci < count; ++ci) {
     const int gk = cols ? cols[ci] : ci;
+    if ((unsigned)gk >= (unsigned)Nk) continue;       // not a key block: ignored (uniform over the workgroup)
     const int kstart = gk * kB;
     const int kvalid = min(kB, Lk - kstart);
     for (int t0 = 0; t0 < kvalid; t0 += kTK) {
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
     }
   }
   if (!active) return;
-  const float inv_l = 1.0f / l;
+  const float inv_l = l > 0.f ? 1.0f / l : 0.f;       // a row without any valid key block: zeros
   const int64_t orow = (int64_t)bhq * Lq + qrow;
   if constexpr (kBf16) {
     __bf16* o = reinterpret_cast<__bf16*>(a.out) + orow * kD;

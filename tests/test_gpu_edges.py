@@ -127,3 +127,40 @@ def test_largest_block_map():
         Kbig = torch.zeros((1, 1, (n + 1) * block, 128), dtype=torch.bfloat16, device=DEV)
         bd.basa_select(Q, Kbig, block, s)
     assert e.value.status_name == "BASA_ERR_UNSUPPORTED"
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_malformed_block_lists_are_ignored_not_followed(dtype, d):
+    """Block lists are device data the host cannot validate: entries outside [0, N_k) are skipped,
+    counts above the list stride are cut, and a query block with no valid entry yields zeros."""
+    L, block = 5 * 128 + 40, 128
+    n = (L + block - 1) // block
+    Q, K, V = (_randn((1, 1, L, d), 600 + i, dtype) for i in range(3))
+    stride = 4
+    cols = torch.tensor([[0, 2, 5, 4],            # fine (ragged last block 5 included)
+                         [1, -7, 3, 99999],       # two entries that are no key blocks
+                         [n, -1, 2 ** 30, -2 ** 31],   # nothing valid
+                         [3, 4, 5, 0],            # count says 9, the stride is 4
+                         [2, 0, 0, 0],            # count 1
+                         [5, 1, 0, 0]], dtype=torch.int32, device=DEV).reshape(1, 1, n, stride)
+    count = torch.tensor([4, 4, 4, 9, 1, 2], dtype=torch.int32, device=DEV).reshape(1, 1, n)
+    out, lse = bd.basa_sparse_attn(Q, K, V, count, cols, block, None, None, want_lse=True)
+    torch.cuda.synchronize()
+    valid = [[0, 2, 4, 5], [1, 3], [], [0, 3, 4, 5], [2], [1, 5]]
+    q, k, v = np64(Q[0, 0]), np64(K[0, 0]), np64(V[0, 0])
+    ident = np.arange(L)
+    for g, lst in enumerate(valid):
+        rows = np.arange(g * block, min((g + 1) * block, L))
+        got = np64(out[0, 0, rows])
+        if not lst:
+            assert (got == 0).all() and np.isneginf(lse[0, 0, rows].cpu().numpy()).all()
+            continue
+        _, O_ref, _ = o.sparse_attention_block(q, k, v, ident, ident, g, lst, block)
+        check_output(got, O_ref, dtype == torch.bfloat16, f"query block {g}")
+    # two neighbouring query blocks (one workgroup of the matrix-core kernel) without any valid entry
+    count[0, 0, 3] = 0
+    out = bd.basa_sparse_attn(Q, K, V, count, cols, block, None, None)
+    torch.cuda.synchronize()
+    assert (np64(out[0, 0, 2 * block:4 * block]) == 0).all()
+    _, O_ref, _ = o.sparse_attention_block(q, k, v, ident, ident, 4, [2], block)
+    check_output(np64(out[0, 0, 4 * block:5 * block]), O_ref, dtype == torch.bfloat16, "query block 4")
