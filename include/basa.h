@@ -23,6 +23,10 @@
  *     Query head h reads KV head h / (heads_q / heads_kv).
  *   - Blocks: block g of a sorted sequence holds sorted positions
  *     [g*B, min((g+1)*B, L)); N = ceil(L/B); a ragged last block is allowed.
+ *   - Permutations and block lists passed IN are device data the host cannot check.
+ *     A permutation entry outside [0, L) is replaced by its own position and a list
+ *     entry outside [0, N_k) is skipped: malformed input gives wrong rows, never an
+ *     access outside the caller's tensors.
  */
 #ifndef BASA_H
 #define BASA_H

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const in
     const int pos = blockIdx.x * 64 + it * 16 + rig;
     v[it] = make_uint4(0, 0, 0, 0);
     if (pos < x.L) {
-      const int row = pm ? pm[pos] : pos;
+      const int row = perm_at(pm, 0, pos, x.L);
       v[it] = reinterpret_cast<const uint4*>(base + (int64_t)row * x.stride_l * 2)[sub];
     }
   }
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
     const int pos = tile * kTileKeys + kk;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (pos < v.L) {
-      const int row = pm ? pm[pos] : pos;
+      const int row = perm_at(pm, 0, pos, v.L);
       val = reinterpret_cast<const uint4*>(base + (int64_t)row * v.stride_l * 2)[sub];
     }
     *reinterpret_cast<uint4*>(&rows[kk][sub * 8]) = val;
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
     // no valid key block in any list of this workgroup (malformed input): its rows become zeros
     const int pos = gq * kB + (wave % WPG) * 32 + li;
     if (gq < a.Nq && pos < a.Lq) {
-      const int orow = a.perm_q ? a.perm_q[(int64_t)bhq * a.Lq + pos] : pos;
+      const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
       uint4* op = reinterpret_cast<uint4*>(a.out + ((int64_t)bhq * a.Lq + orow) * kD);
       for (int i = 0; i < 8; ++i) op[8 * h + i] = make_uint4(0u, 0u, 0u, 0u);
       if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;    // a query block without any valid key block: zeros
   const int pos = gq * kB + (wave % WPG) * 32 + li;
   if (gq < a.Nq && pos < a.Lq) {
-    const int orow = a.perm_q ? a.perm_q[(int64_t)bhq * a.Lq + pos] : pos;
+    const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
     __bf16* op = a.out + ((int64_t)bhq * a.Lq + orow) * kD;
 #pragma unroll
     for (int db = 0; db < 4; ++db)

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
   const bool active = pos < Lq;
   const int32_t* pq = a.perm_q ? a.perm_q + (int64_t)bhq * Lq : nullptr;
   const int32_t* pk = a.perm_k ? a.perm_k + (int64_t)bhk * Lk : nullptr;
-  const int qrow = active ? (pq ? pq[pos] : pos) : 0;
+  const int qrow = active ? perm_at(pq, 0, pos, Lq) : 0;
 
   float q[kD], acc[kD];
   {
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
         Chunk16<kBf16> ch;
         if (j < nk) {
           const int kp = kstart + t0 + j;
-          const int krow = pk ? pk[kp] : kp;
+          const int krow = perm_at(pk, 0, kp, Lk);
           const char* src = which ? vbase + (int64_t)krow * a.v.stride_l * kElem
                                   : kbase + (int64_t)krow * a.k.stride_l * kElem;
           ch.load(src, c);

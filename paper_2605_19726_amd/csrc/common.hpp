@@ -128,6 +128,14 @@ hipError_t launch_calib_read(const void* buf, size_t bytes, uint32_t* out, hipSt
 
 // ---- device helpers ------------------------------------------------------------
 #if defined(__HIPCC__)
+// Entry `pos` of a permutation of 0..L-1 (null = identity).  Permutations are device data the
+// host cannot check: a value that is no index falls back to `pos`, so that a malformed
+// permutation gives wrong rows, never an access outside the tensor.
+__device__ __forceinline__ int perm_at(const int32_t* __restrict__ pm, int64_t offset, int pos, int L) {
+  if (!pm) return pos;
+  const int r = pm[offset + pos];
+  return (unsigned)r < (unsigned)L ? r : pos;
+}
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);
 }

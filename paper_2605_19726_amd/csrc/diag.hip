@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
       const float l_tot = l_run + __shfl_xor(l_run, 32);
       lse2 = m_run + __log2f(l_tot);
       if (a.lse && q_valid && h == 0) {
-        const int orow = a.perm_q ? a.perm_q[(int64_t)bhq * a.Lq + qpos] : qpos;
+        const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq);
         a.lse[(int64_t)bhq * a.Lq + orow] = lse2 * 0.6931471805599453f;
       }
     }
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) void diag_gather_rows_kernel(TensorView x, con
     const int pos = blockIdx.x * 64 + it * 16 + rig;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (pos < x.L) {
-      const int row = pm ? pm[pos] : pos;
+      const int row = perm_at(pm, 0, pos, x.L);
       v = reinterpret_cast<const uint4*>(base + (int64_t)row * x.stride_l * 2)[sub];
     }
     const int cpos = swizzle ? (sub ^ (pos & 15)) : sub;
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void block_radius_kernel(TensorView x, const i
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int pos = g * kB + it * RPI + rig;
-    if (pos < L) c[it].load(base + (int64_t)(pm ? pm[pos] : pos) * x.stride_l * kElem, sub);
+    if (pos < L) c[it].load(base + (int64_t)perm_at(pm, 0, pos, L) * x.stride_l * kElem, sub);
     else c[it].zero();
   }
 #pragma unroll

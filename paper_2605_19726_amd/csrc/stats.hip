@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
   for (int it = 0; it < ITERS; ++it) {
     int pos = g * kB + it * RPI + rig;
     if (pos < L) {
-      int row = pm ? pm[pos] : pos;
+      const int row = perm_at(pm, 0, pos, L);
       c[it].load(base + (int64_t)row * x.stride_l * kElem, sub);
     } else {
       c[it].zero();

@@ -164,3 +164,29 @@ def test_malformed_block_lists_are_ignored_not_followed(dtype, d):
     assert (np64(out[0, 0, 2 * block:4 * block]) == 0).all()
     _, O_ref, _ = o.sparse_attention_block(q, k, v, ident, ident, 4, [2], block)
     check_output(np64(out[0, 0, 4 * block:5 * block]), O_ref, dtype == torch.bfloat16, "query block 4")
+
+
+def test_malformed_key_permutation_stays_inside_the_tensor():
+    """A permutation entry that is no index falls back to its own position: wrong rows for the
+    caller, but never an access outside K or V.  Checked against the oracle fed with the same
+    (sanitised) index array, through pooling and through both attention kernels."""
+    L, block = 3 * 128 + 17, 128
+    rng = np.random.default_rng(9)
+    for dtype, d in ((torch.bfloat16, 128), (torch.float32, 64)):
+        Q, K, V = (_randn((1, 1, L, d), 700 + i, dtype) for i in range(3))
+        perm = rng.permutation(L).astype(np.int32)
+        bad = perm.copy()
+        bad[[3, 100, 250, L - 1]] = [L, -1, 2 ** 31 - 1, -2 ** 31]
+        clean = np.where((bad >= 0) & (bad < L), bad, np.arange(L)).astype(np.int64)
+        pk = torch.from_numpy(bad).to(DEV).reshape(1, 1, L)
+        mean, var = bd.basa_downsample(K, block, pk)
+        m_ref, v_ref = o.block_stats(np64(K[0, 0])[clean], block)
+        np.testing.assert_allclose(mean[0, 0].cpu().numpy(), m_ref, rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(var[0, 0].cpu().numpy(), v_ref, rtol=1e-5, atol=1e-6)
+        n = (L + block - 1) // block
+        cols = torch.arange(n, dtype=torch.int32, device=DEV).repeat(n, 1).reshape(1, 1, n, n)
+        count = torch.full((1, 1, n), n, dtype=torch.int32, device=DEV)
+        out = bd.basa_sparse_attn(Q, K, V, count, cols, block, None, pk)
+        torch.cuda.synchronize()
+        ref = o.dense_attention(np64(Q[0, 0]), np64(K[0, 0])[clean], np64(V[0, 0])[clean])
+        check_output(np64(out[0, 0]), ref, dtype == torch.bfloat16, f"{dtype}")
