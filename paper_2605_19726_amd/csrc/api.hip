@@ -160,7 +160,7 @@ SelectWs carve_select(const basa_tensor* q, const basa_tensor* k, const basa_par
   return w;
 }
 
-bool use_mfma(const basa_tensor* q) { return q->dtype == BASA_BF16 && q->d == 128; }
+bool use_mfma(const basa_tensor* q) { return q->dtype == BASA_BF16; }   // d is 64 or 128 (check_tensor)
 
 basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                         const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,

@@ -1,5 +1,6 @@
 // Block-sparse attention on the bf16 matrix cores of gfx950 (Sec. 2; Eq. 1; Alg. 1
-// step 12), head dimension 128.
+// step 12), head dimension D = 128 (the shapes below) or 64 (rows, tiles and accumulators
+// half as large: 8 chunks per row, K swizzle by row & 7, 8 KB tiles).
 //
 // Layout prepared once per call by the gather kernels below (workspace).  K and V are
 // stored as 64-key tiles that are byte-for-byte the LDS image the main kernel wants, so
@@ -42,33 +43,44 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kD = 128;
 constexpr int kTileKeys = 64;
-constexpr int kTileBytes = 16384;           // one K tile or one V^T tile
-constexpr int kStageBytes = 2 * kTileBytes; // K tile then V^T tile
 constexpr int kStages = 4;
-constexpr int kRingBytes = kStages * kStageBytes;
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kQueriesPerWg = kWaves * 32;
-constexpr int kLoadsPerWave = 32 / kWaves;  // 1 KB direct-to-LDS loads per wave per tile
 constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
+
+// Sizes that follow from the head dimension D.
+template <int D>
+struct Geo {
+  static constexpr int kRowBytes = D * 2;                    // one row of Q or K
+  static constexpr int kChunksPerRow = kRowBytes / 16;       // 16-byte chunks per row: 16 or 8
+  static constexpr int kTileBytes = kTileKeys * kRowBytes;   // one K tile; a V^T tile (D rows of 128 B) is as large
+  static constexpr int kStageBytes = 2 * kTileBytes;         // K tile then V^T tile
+  static constexpr int kRingBytes = kStages * kStageBytes;
+  static constexpr int kKSteps = D / 16;                     // MFMA k-steps of S^T = K Q^T
+  static constexpr int kDBlocks = D / 32;                    // 32-row blocks of O^T
+  static constexpr int kChunksPerTile = kTileBytes / 1024;   // 1 KB direct-to-LDS loads per K (or V^T) tile
+  static constexpr int kLoadsPerWave = 2 * kChunksPerTile / kWaves;
+};
 
 // ---------------------------------------------------------------------------------
 // Gather kernels
 // ---------------------------------------------------------------------------------
 // Rows of a bf16 tensor in sorted order, zero-padded; swizzle = 1 writes K-tile order.
+template <int D>
 __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const int32_t* __restrict__ perm,
                                                           uint4* __restrict__ dst, int rows_padded,
                                                           int swizzle) {
+  constexpr int CPR = Geo<D>::kChunksPerRow, RPI = 256 / CPR, ITERS = 64 / RPI;
   const int bh = blockIdx.y;
-  const int sub = threadIdx.x & 15, rig = threadIdx.x >> 4;
+  const int sub = threadIdx.x % CPR, rig = threadIdx.x / CPR;
   const int32_t* pm = perm ? perm + (int64_t)bh * x.L : nullptr;
   const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * 2;
-  uint4 v[4];
+  uint4 v[ITERS];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int pos = blockIdx.x * 64 + it * 16 + rig;
+  for (int it = 0; it < ITERS; ++it) {
+    const int pos = blockIdx.x * 64 + it * RPI + rig;
     v[it] = make_uint4(0, 0, 0, 0);
     if (pos < x.L) {
       const int row = perm_at(pm, 0, pos, x.L);
@@ -76,25 +88,27 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const in
     }
   }
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int pos = blockIdx.x * 64 + it * 16 + rig;
-    const int c = swizzle ? (sub ^ (pos & 15)) : sub;
-    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * 16 + c] = v[it];
+  for (int it = 0; it < ITERS; ++it) {
+    const int pos = blockIdx.x * 64 + it * RPI + rig;
+    const int c = swizzle ? (sub ^ (pos & (CPR - 1))) : sub;
+    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * CPR + c] = v[it];
   }
 }
 
-// V: gather 64 sorted rows, transpose through LDS, write the swizzled [128][64] tile.
+// V: gather 64 sorted rows, transpose through LDS, write the swizzled [D][64] tile.
+template <int D>
 __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int32_t* __restrict__ perm,
                                                         uint4* __restrict__ dst, int tiles_per_head) {
-  constexpr int kRowStride = 136;   // 256 B + 16 B pad
+  constexpr int CPR = Geo<D>::kChunksPerRow, RPI = 256 / CPR, ITERS = 64 / RPI;
+  constexpr int kRowStride = D + 8;   // one row + 16 B pad
   __shared__ __attribute__((aligned(16))) uint16_t rows[kTileKeys][kRowStride];
   const int bh = blockIdx.y, tile = blockIdx.x;
-  const int sub = threadIdx.x & 15, rig = threadIdx.x >> 4;
+  const int sub = threadIdx.x % CPR, rig = threadIdx.x / CPR;
   const int32_t* pm = perm ? perm + (int64_t)bh * v.L : nullptr;
   const char* base = reinterpret_cast<const char*>(v.ptr) + v.head_offset(bh) * 2;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int kk = it * 16 + rig;
+  for (int it = 0; it < ITERS; ++it) {
+    const int kk = it * RPI + rig;
     const int pos = tile * kTileKeys + kk;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (pos < v.L) {
@@ -104,10 +118,10 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
     *reinterpret_cast<uint4*>(&rows[kk][sub * 8]) = val;
   }
   __syncthreads();
-  // 1024 output chunks of 8 slots; thread handles chunk (d = id/8, s8 = id%8):
+  // 8 D output chunks of 8 slots; thread handles chunk (d = id/8, s8 = id%8):
   // 16-key group g16 = s8/2, lane half hh = s8%2, slot e <-> key 16 g16 + 8(e/4) + 4 hh + e%4
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  for (int it = 0; it < D * 8 / 256; ++it) {
     const int id = it * 256 + threadIdx.x;
     const int dd = id >> 3, s8 = id & 7;
     const int g16 = s8 >> 1, hh = s8 & 1;
@@ -120,7 +134,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
     uint4 o;
     o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
     o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
-    dst[(((int64_t)bh * tiles_per_head + tile) * kD + dd) * 8 + (s8 ^ ((dd >> 1) & 7))] = o;
+    dst[(((int64_t)bh * tiles_per_head + tile) * D + dd) * 8 + (s8 ^ ((dd >> 1) & 7))] = o;
   }
 }
 
@@ -140,8 +154,9 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
 // Per-wave state of the online softmax and the output accumulator.
+template <int D>
 struct WaveState {
-  floatx16 o[4];
+  floatx16 o[Geo<D>::kDBlocks];
   float m_run, l_run;
 };
 
@@ -151,19 +166,19 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 
 // One 64-key tile: S^T, softmax, O^T update, reading the LDS stage at `stage`.  kMasked:
 // keys at tile positions >= nvalid do not exist (ragged end of the sequence) and get -inf.
-template <bool kMasked>
-__device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8], const char* stage,
+template <bool kMasked, int D>
+__device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf)[Geo<D>::kKSteps], const char* stage,
                                              int kaddr0, int vaddr0, float c, int nvalid, int h) {
   const char* ks = stage;
-  const char* vs = stage + kTileBytes;
+  const char* vs = stage + Geo<D>::kTileBytes;
 
   // ---- S^T = K Q^T : two 32-key row blocks
   floatx16 s0 = {0}, s1 = {0};
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const int ka = kaddr0 ^ (s << 5);     // chunk 2s+h of row li at position (2s+h) ^ (li & 15)
+  for (int s = 0; s < Geo<D>::kKSteps; ++s) {
+    const int ka = kaddr0 ^ (s << 5);     // chunk 2s+h of row li at position (2s+h) ^ (li & (chunks per row - 1))
     const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + ka);
-    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + ka + 32 * 256);
+    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + ka + 32 * Geo<D>::kRowBytes);
     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
   }
@@ -187,7 +202,7 @@ __device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8
     st.m_run = m_new;
     st.l_run *= alpha;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < Geo<D>::kDBlocks; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[i][r] *= alpha;
   }
@@ -215,7 +230,7 @@ __device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8
   for (int g = 0; g < 4; ++g) {
     const int va = vaddr0 ^ (g << 5);     // chunk 2g+h of d-row li at position (2g+h) ^ ((li>>1)&7)
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
+    for (int db = 0; db < Geo<D>::kDBlocks; ++db) {
       const bf16x8 vv = *reinterpret_cast<const bf16x8*>(vs + va + db * 32 * 128);
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pb[g], st.o[db], 0, 0, 0);
     }
@@ -226,8 +241,10 @@ __device__ __forceinline__ void process_tile(WaveState& st, const bf16x8 (&qf)[8
 // seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
 // this workgroup lists it).  While seq is being built the ring area holds the per-key-block
 // membership flags.
-template <int kB>
+template <int kB, int D>
 __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
+  using G = Geo<D>;
+  constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = G::kRingBytes;
   constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4
   constexpr int WPG = kB / 32;               // waves per query block: 4 or 2
   constexpr int TPB = kB / kTileKeys;        // key tiles per key block: 2 or 1
@@ -289,8 +306,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
     const int pos = gq * kB + (wave % WPG) * 32 + li;
     if (gq < a.Nq && pos < a.Lq) {
       const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-      uint4* op = reinterpret_cast<uint4*>(a.out + ((int64_t)bhq * a.Lq + orow) * kD);
-      for (int i = 0; i < 8; ++i) op[8 * h + i] = make_uint4(0u, 0u, 0u, 0u);
+      uint4* op = reinterpret_cast<uint4*>(a.out + ((int64_t)bhq * a.Lq + orow) * D);
+      for (int i = 0; i < G::kChunksPerRow / 2; ++i) op[(G::kChunksPerRow / 2) * h + i] = make_uint4(0u, 0u, 0u, 0u);
       if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
     }
     return;
@@ -315,9 +332,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
     const char* kp = Kh + (int64_t)tile * kTileBytes;      // wave-uniform bases
     const char* vp = Vh + (int64_t)tile * kTileBytes;
 #pragma unroll
-    for (int j = 0; j < kLoadsPerWave; ++j) {
-      const int cb = j * kWaves + wave;                   // 0..31, wave-uniform
-      const char* src = (cb < 16 ? kp : vp) + (cb & 15) * 1024 + (uint32_t)(lane * 16);
+    for (int j = 0; j < G::kLoadsPerWave; ++j) {
+      const int cb = j * kWaves + wave;                   // wave-uniform: K chunks first, then V^T chunks
+      const char* src = (cb < G::kChunksPerTile ? kp : vp) + (cb % G::kChunksPerTile) * 1024 + (uint32_t)(lane * 16);
       char* dst = smem + stage * kStageBytes + cb * 1024;
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
     }
@@ -332,12 +349,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   issue_tile(tile_of(1), 1);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
-  bf16x8 qf[8];
+  bf16x8 qf[G::kKSteps];
   {
     const int64_t qrow = ((int64_t)bhq * a.Nq + min(gq, a.Nq - 1)) * kB + (wave % WPG) * 32 + li;
-    const uint4* qp = a.Qs + qrow * 16;
+    const uint4* qp = a.Qs + qrow * G::kChunksPerRow;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < G::kKSteps; ++s) {
       uint4 t = qp[2 * s + h];
       qf[s] = *reinterpret_cast<bf16x8*>(&t);
     }
@@ -345,12 +362,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   // LDS byte offsets inside a stage.  K: row li (+32 for the second block), chunk 2s+h at
   // position (2s+h) ^ (li & 15).  V^T: d-row li (+32 db), chunk 2g+h at (2g+h) ^ ((li>>1)&7).
   // (step s / group g are folded in by xor with s<<5 / g<<5 at the point of use)
-  const int kaddr = li * 256 + ((h ^ (li & 15)) << 4);
+  const int kaddr = li * G::kRowBytes + ((h ^ (li & (G::kChunksPerRow - 1))) << 4);
   const int vaddr = li * 128 + ((h ^ ((li >> 1) & 7)) << 4);
 
-  WaveState st;
+  WaveState<D> st;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) st.o[i] = floatx16{0};
+  for (int i = 0; i < G::kDBlocks; ++i) st.o[i] = floatx16{0};
   st.m_run = -INFINITY;
   st.l_run = 0.f;
   const float c = a.scale_log2e;
@@ -383,8 +400,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
       issue_tile(b1 * TPB + (tf1 % TPB), 2 * slot_next + 1);
     }
     const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
-    if (e_a & my_bit) process_tile<false>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
-    if (e_b & my_bit) process_tile<false>(st, qf, slot + kStageBytes, kaddr, vaddr, c, kTileKeys, h);
+    if (e_a & my_bit) process_tile<false, D>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
+    if (e_b & my_bit) process_tile<false, D>(st, qf, slot + kStageBytes, kaddr, vaddr, c, kTileKeys, h);
     e_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f0);
     e_b = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f1);
   }
@@ -394,12 +411,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
     __syncthreads();
     const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
     if (t + 1 < n_tiles) {
-      if (e_a & my_bit) process_tile<false>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
+      if (e_a & my_bit) process_tile<false, D>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
       const int nvalid = a.Lk - ((int)(e_b & 0xffffffu) * TPB + ((t + 1) % TPB)) * kTileKeys;
-      if (e_b & my_bit) process_tile<true>(st, qf, slot + kStageBytes, kaddr, vaddr, c, nvalid, h);
+      if (e_b & my_bit) process_tile<true, D>(st, qf, slot + kStageBytes, kaddr, vaddr, c, nvalid, h);
     } else {
       const int nvalid = a.Lk - ((int)(e_a & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
-      if (e_a & my_bit) process_tile<true>(st, qf, slot, kaddr, vaddr, c, nvalid, h);
+      if (e_a & my_bit) process_tile<true, D>(st, qf, slot, kaddr, vaddr, c, nvalid, h);
     }
   }
 
@@ -409,9 +426,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   const int pos = gq * kB + (wave % WPG) * 32 + li;
   if (gq < a.Nq && pos < a.Lq) {
     const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-    __bf16* op = a.out + ((int64_t)bhq * a.Lq + orow) * kD;
+    __bf16* op = a.out + ((int64_t)bhq * a.Lq + orow) * D;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         bf16x4 pk;
@@ -424,15 +441,37 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   }
 }
 
-size_t off_k(int BHq, int Nq, int B) { return align_up((size_t)BHq * Nq * B * kD * 2, 256); }
-size_t sz_kv(int BHkv, int Nk, int B) { return align_up((size_t)BHkv * Nk * B * kD * 2, 256); }
+size_t off_k(int BHq, int Nq, int B, int d) { return align_up((size_t)BHq * Nq * B * d * 2, 256); }
+size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk * B * d * 2, 256); }
+
+template <int kB, int D>
+basa_status launch_main(const MfmaArgs& m, size_t lds, hipStream_t st) {
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
+  hipLaunchKernelGGL((attn_mfma_kernel<kB, D>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
+  BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
+  return BASA_OK;
+}
+
+template <int D>
+basa_status launch_gathers(const AttnArgs& a, uint4* Qs, uint4* Kt, uint4* Vt, int BHq, int BHkv, int Nq, int Nk,
+                           hipStream_t st) {
+  const int B = a.B;
+  hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(Nq * B / 64, BHq), dim3(256), 0, st, a.q, a.perm_q, Qs, Nq * B, 0);
+  BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(Q)");
+  hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.k, a.perm_k, Kt, Nk * B, 1);
+  BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(K)");
+  hipLaunchKernelGGL(gather_vt_kernel<D>, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.v, a.perm_k, Vt, Nk * B / 64);
+  BASA_HIP_CHECK_LAUNCH("gather_vt_kernel");
+  return BASA_OK;
+}
 
 }  // namespace
 
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B) {
-  (void)d;
   const int Nq = ceil_div(Lq, B), Nk = ceil_div(Lk, B);
-  return off_k(BHq, Nq, B) + 2 * sz_kv(BHkv, Nk, B);
+  return off_k(BHq, Nq, B, d) + 2 * sz_kv(BHkv, Nk, B, d);
 }
 
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
@@ -440,7 +479,8 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   const int B = a.B;
   const int Nq = ceil_div(a.q.L, B), Nk = ceil_div(a.k.L, B);
   if (BHq == 0 || Nq == 0) return BASA_OK;
-  const size_t lds = (size_t)kRingBytes + (size_t)Nk * 4 + kWaves * 4;
+  const int d = a.q.d;
+  const size_t lds = (size_t)(d == 128 ? Geo<128>::kRingBytes : Geo<64>::kRingBytes) + (size_t)Nk * 4 + kWaves * 4;
   {
     int dev = 0, max_lds = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -453,17 +493,14 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   }
   char* ws = reinterpret_cast<char*>(a.ws);
   uint4* Qs = reinterpret_cast<uint4*>(ws);
-  uint4* Kt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B));
-  uint4* Vt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B) + sz_kv(BHkv, Nk, B));
+  uint4* Kt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B, d));
+  uint4* Vt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B, d) + sz_kv(BHkv, Nk, B, d));
 
   {
     ProfScope prof(K_GATHER, st);
-    hipLaunchKernelGGL(gather_rows_kernel, dim3(Nq * B / 64, BHq), dim3(256), 0, st, a.q, a.perm_q, Qs, Nq * B, 0);
-    BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(Q)");
-    hipLaunchKernelGGL(gather_rows_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.k, a.perm_k, Kt, Nk * B, 1);
-    BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(K)");
-    hipLaunchKernelGGL(gather_vt_kernel, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.v, a.perm_k, Vt, Nk * B / 64);
-    BASA_HIP_CHECK_LAUNCH("gather_vt_kernel");
+    const basa_status s = d == 128 ? launch_gathers<128>(a, Qs, Kt, Vt, BHq, BHkv, Nq, Nk, st)
+                                   : launch_gathers<64>(a, Qs, Kt, Vt, BHq, BHkv, Nq, Nk, st);
+    if (s != BASA_OK) return s;
   }
 
   MfmaArgs m;
@@ -475,22 +512,10 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.group = a.q.heads / a.k.heads;
   m.wgs_per_head = ceil_div(Nq * B, kQueriesPerWg);
   m.total_wgs = BHq * m.wgs_per_head;
-  m.scale_log2e = 1.4426950408889634f / sqrtf((float)kD);
+  m.scale_log2e = 1.4426950408889634f / sqrtf((float)d);
   ProfScope prof(K_ATTN, st);
-  hipError_t e;
-  if (B == 128) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
-    hipLaunchKernelGGL((attn_mfma_kernel<128>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
-  } else {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<64>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
-    hipLaunchKernelGGL((attn_mfma_kernel<64>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
-  }
-  BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
-  return BASA_OK;
+  if (d == 128) return B == 128 ? launch_main<128, 128>(m, lds, st) : launch_main<64, 128>(m, lds, st);
+  return B == 128 ? launch_main<128, 64>(m, lds, st) : launch_main<64, 64>(m, lds, st);
 }
 
 }  // namespace basa

@@ -190,3 +190,20 @@ def test_malformed_key_permutation_stays_inside_the_tensor():
         torch.cuda.synchronize()
         ref = o.dense_attention(np64(Q[0, 0]), np64(K[0, 0])[clean], np64(V[0, 0])[clean])
         check_output(np64(out[0, 0]), ref, dtype == torch.bfloat16, f"{dtype}")
+
+
+@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("L", [1, 64, 130, 1000, 2048 + 77])
+def test_bf16_head_dim_64(L, block):
+    """bf16 with head dimension 64 runs on the matrix-core kernel too (half-size rows and tiles)."""
+    Hq, Hk = 4, 2
+    Q = _randn((1, Hq, L, 64), 800 + L, torch.bfloat16)
+    K, V = _randn((1, Hk, L, 64), 801 + L, torch.bfloat16), _randn((1, Hk, L, 64), 802 + L, torch.bfloat16)
+    _full_check(Q, K, V, block, 0.5, True, f"d=64 L={L} B={block}")
+    if L >= 1000:
+        dense, lse = bd.basa_dense_attn(Q, K, V, block, want_lse=True)
+        torch.cuda.synchronize()
+        for h in range(Hq):
+            ref, lse_ref = o.dense_attention(np64(Q[0, h]), np64(K[0, h // 2]), np64(V[0, h // 2]), True)
+            check_output(np64(dense[0, h]), ref, True, "dense d=64")
+            np.testing.assert_allclose(lse[0, h].cpu().numpy(), lse_ref, atol=2e-2)
