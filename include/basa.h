@@ -142,7 +142,7 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
  * ordered queries Q' = Q[perm_q], softmax attention (Eq. 1) restricted to the tokens
  * of the listed key blocks of K' = K[perm_k], V' = V[perm_k], normalised over those
  * tokens; the row of sorted position i is written to out row perm_q[i].
- * bf16 tensors: bf16 MFMA with fp32 accumulation and fp32 softmax state (d = 128);
+ * bf16 tensors: bf16 MFMA with fp32 accumulation and fp32 softmax state (d = 64 or 128);
  * f32 tensors: fp32 throughout.
  *   row_count    [batch, heads_q, N_q] int32, each in [1, N_k].
  *   row_cols     [batch, heads_q, N_q, cols_stride] int32, ascending, each in [0, N_k).
