@@ -172,6 +172,21 @@ def fidelity_report(w, Q, K, sparsities):
     return rows
 
 
+def graph_step_ms(pipe, reps=20):
+    """Milliseconds per step when the whole step (about 14 launches) is replayed from a HIP graph:
+    what a caller sees who captures the path once, as serving loops on short sequences do."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipe.step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pipe.step()
+    graph.replay()
+    return timed(graph.replay, reps) * 1e3
+
+
 def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK, mass_target=0.0):
     pipe = Pipeline(w, sparsity, Q, K, V, beta, sort, mass_target)
     for _ in range(warmup):
@@ -307,13 +322,15 @@ def main():
             q2, k2, v2 = synth.make_qkv(c, device=dev)
             first = True
             for s_ in (0.5, 0.75, 0.9):
-                r = measure(c, s_, q2, k2, v2, 2, 1, dense_reps=1 if first else 0)[0]
+                r, pipe_ = measure(c, s_, q2, k2, v2, 2, 1, dense_reps=1 if first else 0)
+                r["t_e2e_graph_ms"] = graph_step_ms(pipe_)
+                del pipe_
                 if first:
                     t_dense = r["t_dense_ms"]
                 first = False
                 r["t_dense_ms"], r["speedup_vs_dense"] = t_dense, t_dense / r["t_e2e_ms"]
                 table.append({k: r[k] for k in ("workload", "sparsity", "kappa", "n_blocks", "t_e2e_ms", "t_select_ms",
-                                                "t_attn_ms", "t_dense_ms", "speedup_vs_dense", "effective_tflops",
+                                                "t_attn_ms", "t_dense_ms", "t_e2e_graph_ms", "speedup_vs_dense", "effective_tflops",
                                                 "executed_tflops_attn_call", "dense_tflops")})
             del q2, k2, v2
             torch.cuda.empty_cache()

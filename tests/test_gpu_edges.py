@@ -207,3 +207,40 @@ def test_bf16_head_dim_64(L, block):
             ref, lse_ref = o.dense_attention(np64(Q[0, h]), np64(K[0, h // 2]), np64(V[0, h // 2]), True)
             check_output(np64(dense[0, h]), ref, True, "dense d=64")
             np.testing.assert_allclose(lse[0, h].cpu().numpy(), lse_ref, atol=2e-2)
+
+
+def test_hip_graph_capture_and_replay():
+    """With caller-owned buffers the library allocates nothing and never synchronises, so a
+    select + attention pass can be captured into a HIP graph; every replay, with eager work
+    and synchronisation in between, must reproduce the eager result bit for bit."""
+    w = C[4].scaled("graph", heads_q=4, heads_kv=4, L=4096 + 128 + 31)
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    p = bd.params(w.block, 0.5)
+    ws_sel = torch.empty(bd.select_workspace_size(Q, K, p), dtype=torch.uint8, device=DEV)
+    ws_att = torch.empty(bd.attn_workspace_size(Q, K, p), dtype=torch.uint8, device=DEV)
+    sel = bd.basa_select(Q, K, w.block, 0.5, ws=ws_sel)
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k, ws=ws_att)
+    torch.cuda.synchronize()
+    want_out, want_cols, want_perm = out.clone(), sel.row_cols.clone(), sel.perm_k.clone()
+
+    def step():
+        bd.basa_select(Q, K, w.block, 0.5, ws=ws_sel, out=sel)
+        bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k, ws=ws_att, out=out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(4):
+        out.zero_(); sel.row_cols.zero_(); sel.perm_k.zero_()      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want_out), f"replay {rep}: output differs"
+        assert torch.equal(sel.row_cols, want_cols) and torch.equal(sel.perm_k, want_perm), f"replay {rep}"
+        # a different eager call in between must not disturb the next replay
+        bd.basa_select(Q, K, w.block, 0.75)
