@@ -52,7 +52,7 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-template <int kB>
+template <int kB, bool kDev>      // kDev: also the observed logit deviation (needs base_logits)
 __global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
   constexpr int NQB = kQueriesPerWg / kB;   // query blocks per workgroup: 1 or 2
   constexpr int WPG = kB / 32;              // waves per query block: 4 or 2
@@ -128,23 +128,23 @@ __global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
         m_run = m_new;
       } else {
         float lblk = 0.f;
-        if (a.base_logits && gq < a.Nq) lblk = a.base_logits[((int64_t)bhq * a.Nq + gq) * a.Nk + t / TPB];
+        if (kDev && gq < a.Nq) lblk = a.base_logits[((int64_t)bhq * a.Nq + gq) * a.Nk + t / TPB];
         float sum = 0.f, dev = 0.f;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
           const int kk = 8 * (q >> 2) + 4 * h + (q & 3);
           if (kk < nvalid) {
             sum += __builtin_amdgcn_exp2f(fmaf(s0[q], c, -lse2));
-            dev = fmaxf(dev, fabsf(s0[q] * a.inv_sqrt_d - lblk));
+            if (kDev) dev = fmaxf(dev, fabsf(s0[q] * a.inv_sqrt_d - lblk));
           }
           if (32 + kk < nvalid) {
             sum += __builtin_amdgcn_exp2f(fmaf(s1[q], c, -lse2));
-            dev = fmaxf(dev, fabsf(s1[q] * a.inv_sqrt_d - lblk));
+            if (kDev) dev = fmaxf(dev, fabsf(s1[q] * a.inv_sqrt_d - lblk));
           }
         }
         if (!q_valid) { sum = 0.f; dev = 0.f; }
         sum = wave_sum(sum);
-        dev = wave_max(dev);
+        if (kDev) dev = wave_max(dev);
         if (lane == 0) { part_mass[t & 1][wave] = sum; part_dev[t & 1][wave] = dev; }
       }
 #pragma unroll
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
             const int n_q = min(kB, a.Lq - gqb * kB);
             const int64_t o = ((int64_t)bhq * a.Nq + gqb) * a.Nk + t / TPB;
             a.m_hat[o] = acc_mass / (float)n_q;
-            if (a.max_dev) a.max_dev[o] = acc_dev;
+            if (kDev) a.max_dev[o] = acc_dev;
             acc_mass = 0.f;
             acc_dev = 0.f;
           }
@@ -385,8 +385,11 @@ basa_status launch_block_mass(const TensorView& q, const TensorView& k, const in
   a.inv_sqrt_d = 1.0f / sqrtf((float)kD);
   ProfScope prof(K_BLOCK_MASS, st);
   const dim3 grid(rows_q / kQueriesPerWg, BHq);
-  if (B == 128) hipLaunchKernelGGL((block_mass_kernel<128>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((block_mass_kernel<64>), grid, dim3(256), 0, st, a);
+  const bool want_dev = max_dev != nullptr && base_logits != nullptr;
+  if (B == 128 && want_dev) hipLaunchKernelGGL((block_mass_kernel<128, true>), grid, dim3(256), 0, st, a);
+  else if (B == 128) hipLaunchKernelGGL((block_mass_kernel<128, false>), grid, dim3(256), 0, st, a);
+  else if (want_dev) hipLaunchKernelGGL((block_mass_kernel<64, true>), grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((block_mass_kernel<64, false>), grid, dim3(256), 0, st, a);
   BASA_HIP_CHECK_LAUNCH("block_mass_kernel");
   return BASA_OK;
 }
