@@ -5,7 +5,7 @@
 // Layout prepared once per call by the gather kernels below (workspace).  K and V are
 // stored as 64-key tiles that are byte-for-byte the LDS image the main kernel wants, so
 // the global -> LDS copy is a linear 16 KB copy done with direct-to-LDS loads:
-//   Qs [BHq ][Nq*B][128] bf16      rows of Q in sorted order, zero rows past L_q
+//   (Q needs no copy: every wave reads the rows of its 32 queries once, through perm_q)
 //   Kt [BHkv][tiles][64 rows][16 chunks of 8 bf16]   rows of K in sorted order; chunk c
 //        of row r sits at chunk position c ^ (r & 15)                (XOR swizzle)
 //   Vt [BHkv][tiles][128 d-rows][8 chunks of 8 keys] V in sorted order, transposed per
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
 // Main kernel
 // ---------------------------------------------------------------------------------
 struct MfmaArgs {
-  const uint4* Qs; const char* Kt; const char* Vt;
+  TensorView q; const char* Kt; const char* Vt;
   const int32_t* row_count; const int32_t* row_cols; int32_t cols_stride;
   const int32_t* perm_q;
   __bf16* out; float* lse;
@@ -351,8 +351,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[G::kKSteps];
   {
-    const int64_t qrow = ((int64_t)bhq * a.Nq + min(gq, a.Nq - 1)) * kB + (wave % WPG) * 32 + li;
-    const uint4* qp = a.Qs + qrow * G::kChunksPerRow;
+    // the query of sorted position qpos, read from the caller's tensor; positions past L_q
+    // (padding of the last block, or a query block that does not exist) read row 0 and are never stored
+    const int qpos = min(gq, a.Nq - 1) * kB + (wave % WPG) * 32 + li;
+    const int qrow = qpos < a.Lq ? perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq) : 0;
+    const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q.ptr) +
+                                                     (a.q.head_offset(bhq) + (int64_t)qrow * a.q.stride_l) * 2);
 #pragma unroll
     for (int s = 0; s < G::kKSteps; ++s) {
       uint4 t = qp[2 * s + h];
@@ -441,7 +445,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   }
 }
 
-size_t off_k(int BHq, int Nq, int B, int d) { return align_up((size_t)BHq * Nq * B * d * 2, 256); }
 size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk * B * d * 2, 256); }
 
 template <int kB, int D>
@@ -455,11 +458,8 @@ basa_status launch_main(const MfmaArgs& m, size_t lds, hipStream_t st) {
 }
 
 template <int D>
-basa_status launch_gathers(const AttnArgs& a, uint4* Qs, uint4* Kt, uint4* Vt, int BHq, int BHkv, int Nq, int Nk,
-                           hipStream_t st) {
+basa_status launch_gathers(const AttnArgs& a, uint4* Kt, uint4* Vt, int BHkv, int Nk, hipStream_t st) {
   const int B = a.B;
-  hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(Nq * B / 64, BHq), dim3(256), 0, st, a.q, a.perm_q, Qs, Nq * B, 0);
-  BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(Q)");
   hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.k, a.perm_k, Kt, Nk * B, 1);
   BASA_HIP_CHECK_LAUNCH("gather_rows_kernel(K)");
   hipLaunchKernelGGL(gather_vt_kernel<D>, dim3(Nk * B / 64, BHkv), dim3(256), 0, st, a.v, a.perm_k, Vt, Nk * B / 64);
@@ -471,7 +471,8 @@ basa_status launch_gathers(const AttnArgs& a, uint4* Qs, uint4* Kt, uint4* Vt, i
 
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B) {
   const int Nq = ceil_div(Lq, B), Nk = ceil_div(Lk, B);
-  return off_k(BHq, Nq, B, d) + 2 * sz_kv(BHkv, Nk, B, d);
+  (void)BHq; (void)Nq;
+  return 2 * sz_kv(BHkv, Nk, B, d);
 }
 
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
@@ -492,19 +493,18 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
     }
   }
   char* ws = reinterpret_cast<char*>(a.ws);
-  uint4* Qs = reinterpret_cast<uint4*>(ws);
-  uint4* Kt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B, d));
-  uint4* Vt = reinterpret_cast<uint4*>(ws + off_k(BHq, Nq, B, d) + sz_kv(BHkv, Nk, B, d));
+  uint4* Kt = reinterpret_cast<uint4*>(ws);
+  uint4* Vt = reinterpret_cast<uint4*>(ws + sz_kv(BHkv, Nk, B, d));
 
   {
     ProfScope prof(K_GATHER, st);
-    const basa_status s = d == 128 ? launch_gathers<128>(a, Qs, Kt, Vt, BHq, BHkv, Nq, Nk, st)
-                                   : launch_gathers<64>(a, Qs, Kt, Vt, BHq, BHkv, Nq, Nk, st);
+    const basa_status s = d == 128 ? launch_gathers<128>(a, Kt, Vt, BHkv, Nk, st)
+                                   : launch_gathers<64>(a, Kt, Vt, BHkv, Nk, st);
     if (s != BASA_OK) return s;
   }
 
   MfmaArgs m;
-  m.Qs = Qs; m.Kt = reinterpret_cast<const char*>(Kt); m.Vt = reinterpret_cast<const char*>(Vt);
+  m.q = a.q; m.Kt = reinterpret_cast<const char*>(Kt); m.Vt = reinterpret_cast<const char*>(Vt);
   m.row_count = a.row_count; m.row_cols = a.row_cols; m.cols_stride = a.cols_stride;
   m.perm_q = a.perm_q;
   m.out = reinterpret_cast<__bf16*>(a.out); m.lse = a.lse;
