@@ -16,8 +16,10 @@
 //
 // Main kernel: one workgroup of 8 waves owns 256 consecutive sorted queries, i.e. 2 query
 // blocks of 128 (4 of 64), one wave per 32 queries.  Streaming K/V tiles from L2 into LDS is
-// what bounds this kernel (128 queries per tile would need more L2 bandwidth than the chip
-// has), so the query blocks of a workgroup share every tile: the workgroup walks the UNION
+// the costly part beside the MFMAs themselves (with 128 queries per tile fetch the kernel was
+// 12 % slower: 8 TB/s of L2 -> LDS traffic), so the query blocks of a workgroup share every tile,
+// and 256 queries are what the register file holds (64 accumulator registers per 32 queries,
+// two waves per SIMD): the workgroup walks the UNION
 // of their block lists in ascending order, each tile is fetched once, and only the waves
 // whose query block lists the tile's key block compute on it.  Scores are computed
 // TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K tile rows from
