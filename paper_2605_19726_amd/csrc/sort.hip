@@ -32,6 +32,92 @@ struct SegGeom {
   int L, W, segs, tiles_per_seg;
 };
 
+// ---- the tile's bitonic network, 16 words per thread in registers ------------------------
+// Word i of the tile lives at LDS slot i + i/16 (one pad word per 16: a thread's 16 consecutive
+// words, and the other two ownership patterns below, then hit distinct banks).
+constexpr int kTileSlots = kTile + kTile / 16;
+__device__ __forceinline__ int tile_slot(int i) { return i + (i >> 4); }
+
+// Three ways of dealing the 4096 = 2^12 words to 256 threads x 16 registers; in layout G the
+// register number is index bits 4G+3 .. 4G, so the compare-exchange stages whose distance 2^b
+// has b in that range work on registers only.
+template <int G>
+__device__ __forceinline__ int word_of(int t, int r) {
+  if (G == 0) return (t << 4) | r;
+  if (G == 1) return ((t >> 4) << 8) | (r << 4) | (t & 15);
+  return (r << 8) | t;
+}
+template <int G>
+__device__ __forceinline__ void regs_from_lds(uint64_t (&v)[16], const uint64_t* buf, int t) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = buf[tile_slot(word_of<G>(t, r))];
+}
+template <int G>
+__device__ __forceinline__ void regs_to_lds(const uint64_t (&v)[16], uint64_t* buf, int t) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) buf[tile_slot(word_of<G>(t, r))] = v[r];
+}
+// Stages of the merge step with block size k whose compare distance 2^b has b_lo <= b <= b_hi,
+// all inside layout G's register bits.  A pair is ordered ascending where index bit log2(k) is 0.
+template <int G>
+__device__ __forceinline__ void stages_in_regs(uint64_t (&v)[16], int t, int k, int b_hi, int b_lo) {
+  asm volatile("" : "+v"(t));      // as in relayout(): recompute the word indices here
+#pragma unroll
+  for (int lb = 3; lb >= 0; --lb) {
+    const int b = 4 * G + lb;
+    if (b <= b_hi && b >= b_lo) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (r & (1 << lb)) continue;
+        const int r2 = r | (1 << lb);
+        const bool up = (word_of<G>(t, r) & k) == 0;
+        const uint64_t a = v[r], c = v[r2];
+        const bool swap = (a > c) == up;
+        v[r] = swap ? c : a;
+        v[r2] = swap ? a : c;
+      }
+    }
+  }
+}
+// Moves the tile from layout A (registers) to layout B (registers) through LDS.
+template <int A, int B>
+__device__ __forceinline__ void relayout(uint64_t (&v)[16], uint64_t* buf, int t) {
+  // the slot addresses are recomputed at every use (two integer ops each): left to itself the
+  // compiler keeps all 48 of them in registers across the whole network and halves the occupancy
+  asm volatile("" : "+v"(t));
+  regs_to_lds<A>(v, buf, t);
+  __syncthreads();
+  regs_from_lds<B>(v, buf, t);
+  __syncthreads();                 // everyone has read before anyone writes the next layout
+}
+// Sorts the kTile words in buf (slots tile_slot(i)) ascending; ends with the words back in buf.
+__device__ __forceinline__ void sort_tile_in_lds(uint64_t* buf, int t) {
+  static_assert(kTile == 4096 && kSortThreads == 256, "16 words per thread, 12 index bits in three groups of 4");
+  uint64_t v[16];
+  regs_from_lds<0>(v, buf, t);
+  __syncthreads();
+  for (int m = 1; m <= 12; ++m) {
+    const int k = 1 << m;          // k = 4096: bit 12 of an index is always 0, everything ascending
+    if (m > 8) {
+      relayout<0, 2>(v, buf, t);
+      stages_in_regs<2>(v, t, k, m - 1, 8);
+      relayout<2, 1>(v, buf, t);
+      stages_in_regs<1>(v, t, k, 7, 4);
+      relayout<1, 0>(v, buf, t);
+      stages_in_regs<0>(v, t, k, 3, 0);
+    } else if (m > 4) {
+      relayout<0, 1>(v, buf, t);
+      stages_in_regs<1>(v, t, k, m - 1, 4);
+      relayout<1, 0>(v, buf, t);
+      stages_in_regs<0>(v, t, k, 3, 0);
+    } else {
+      stages_in_regs<0>(v, t, k, m - 1, 0);
+    }
+  }
+  regs_to_lds<0>(v, buf, t);
+  __syncthreads();
+}
+
 template <bool kBf16, int kD>
 __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView x0, TensorView x1, int BH0,
                                                                       uint64_t* __restrict__ out,
@@ -44,7 +130,7 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
   constexpr int kIters = 8;
   constexpr int kRowsPerPass = kRowsPerIter * kIters;
   static_assert(kTile % kRowsPerPass == 0, "a tile is a whole number of passes");
-  __shared__ uint64_t buf[kTile];
+  __shared__ uint64_t buf[kTileSlots];
 
   const int bh = blockIdx.y;
   const int seg = blockIdx.x / g.tiles_per_seg;
@@ -122,32 +208,21 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
     const int loc = pass * kRowsPerPass + it_mine * kRowsPerIter + rig;
     if (sub < 8 && loc < n) {
       const float key = (float)acc[0];
-      buf[loc] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)(start + loc);
+      buf[tile_slot(loc)] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)(start + loc);
       if (keys_out) keys_out[hb + start + loc] = key;
     }
 #pragma unroll
     for (int it = 0; it < kIters; ++it) cur[it] = nxt[it];
   }
-  for (int i = n + threadIdx.x; i < kTile; i += kSortThreads) buf[i] = ~0ull;
+  for (int i = n + threadIdx.x; i < kTile; i += kSortThreads) buf[tile_slot(i)] = ~0ull;
   __syncthreads();
 
   // ---- phase 2: bitonic network over the kTile words
-  for (int k = 2; k <= kTile; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int p = threadIdx.x; p < kTile / 2; p += kSortThreads) {
-        int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));
-        int l = i | j;
-        uint64_t a = buf[i], b = buf[l];
-        bool up = (i & k) == 0;
-        if ((a > b) == up) { buf[i] = b; buf[l] = a; }
-      }
-      __syncthreads();
-    }
-  }
+  sort_tile_in_lds(buf, threadIdx.x);
   if (perm_out) {
-    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[hb + start + i] = (int32_t)(uint32_t)buf[i];
+    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[hb + start + i] = (int32_t)(uint32_t)buf[tile_slot(i)];
   } else {
-    for (int i = threadIdx.x; i < n; i += kSortThreads) out[hb + start + i] = buf[i];
+    for (int i = threadIdx.x; i < n; i += kSortThreads) out[hb + start + i] = buf[tile_slot(i)];
   }
 }
 
