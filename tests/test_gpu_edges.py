@@ -244,3 +244,25 @@ def test_hip_graph_capture_and_replay():
         assert torch.equal(sel.row_cols, want_cols) and torch.equal(sel.perm_k, want_perm), f"replay {rep}"
         # a different eager call in between must not disturb the next replay
         bd.basa_select(Q, K, w.block, 0.75)
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64)])
+def test_packed_qkv_views(dtype, d):
+    """Q, K and V as strided views of one packed [1, L, 3, H, d] buffer (token-major, heads
+    interleaved): every kernel follows the strides; results equal those on contiguous copies."""
+    H, L, block = 3, 777, 128
+    packed = _randn((1, L, 3, H, d), 900 + d, dtype)
+    Q, K, V = (packed[:, :, i].permute(0, 2, 1, 3) for i in range(3))          # [1, H, L, d] views
+    assert not Q.is_contiguous() and Q.stride(2) == 3 * H * d
+    Qc, Kc, Vc = Q.contiguous(), K.contiguous(), V.contiguous()
+    sel = bd.basa_select(Q, K, block, 0.5)
+    ref = bd.basa_select(Qc, Kc, block, 0.5)
+    for name in ("perm_q", "perm_k", "mask_bits", "row_cols", "row_count", "row_mass"):
+        assert torch.equal(getattr(sel, name), getattr(ref, name)), name
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k)
+    want = bd.basa_sparse_attn(Qc, Kc, Vc, ref.row_count, ref.row_cols, block, ref.perm_q, ref.perm_k)
+    assert out.is_contiguous() and torch.equal(out, want)
+    mean, var = bd.basa_downsample(K, block, sel.perm_k)
+    mean_c, var_c = bd.basa_downsample(Kc, block, ref.perm_k)
+    assert torch.equal(mean, mean_c) and torch.equal(var, var_c)
+    _full_check(Q, K, V, block, 0.5, dtype == torch.bfloat16, f"packed qkv {dtype} d={d}")
