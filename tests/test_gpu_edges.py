@@ -266,3 +266,44 @@ def test_packed_qkv_views(dtype, d):
     mean_c, var_c = bd.basa_downsample(Kc, block, ref.perm_k)
     assert torch.equal(mean, mean_c) and torch.equal(var, var_c)
     _full_check(Q, K, V, block, 0.5, dtype == torch.bfloat16, f"packed qkv {dtype} d={d}")
+
+
+def test_optional_outputs_may_be_null():
+    w = C[4].scaled("nulls", heads_q=2, heads_kv=2, L=1500)
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    full = bd.basa_select(Q, K, w.block, 0.5)
+    lean = bd.basa_select(Q, K, w.block, 0.5, want_mask=False, want_mass=False)
+    assert lean.mask_bits is None and lean.row_mass is None
+    assert torch.equal(lean.row_cols, full.row_cols) and torch.equal(lean.perm_k, full.perm_k)
+    mean, var = bd.basa_downsample(K, w.block, full.perm_k, want_var=False)
+    assert var is None
+    mean2, _ = bd.basa_downsample(K, w.block, full.perm_k)
+    assert torch.equal(mean, mean2)
+
+
+def test_two_streams_with_their_own_buffers_do_not_interfere():
+    """The library keeps no device-side state of its own: calls on two streams, each with its own
+    workspaces and outputs, may overlap and give what they give when run alone."""
+    wa = C[4].scaled("sa", heads_q=4, heads_kv=4, L=8192 + 50)
+    wb = C[1].scaled("sb", heads_q=4, heads_kv=4, L=6000)
+    A = synth.make_qkv(wa, device=DEV)
+    Bt = synth.make_qkv(wb, device=DEV)
+
+    def run(w, qkv):
+        Q, K, V = qkv
+        sel = bd.basa_select(Q, K, w.block, 0.5)
+        return bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+
+    alone_a, alone_b = run(wa, A), run(wb, Bt)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(3):
+        with torch.cuda.stream(s1):
+            oa = run(wa, A)
+        with torch.cuda.stream(s2):
+            ob = run(wb, Bt)
+        outs.append((oa, ob))
+    torch.cuda.synchronize()
+    for oa, ob in outs:
+        assert torch.equal(oa, alone_a) and torch.equal(ob, alone_b)
