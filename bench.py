@@ -197,6 +197,14 @@ def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd
     t_step = timed(pipe.step, steps)
     prof = bd.basa_profile_read()
     bd.basa_profile_enable(False)
+    # the same step again, one pair of events per step on the stream the library launches on
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in evs:
+        e0.record()
+        pipe.step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     t_sel = timed(pipe.select, max(2, steps))
     t_att = timed(pipe.attn, max(2, steps))
     t_dense = None
@@ -216,6 +224,7 @@ def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd
     sb = selection_bytes(w)
     res = dict(
         workload=w.name, sparsity=sparsity, kappa=kappa, n_blocks=w.n_blocks, mass_target=mass_target,
+        step_ms_median=per_step[len(per_step) // 2], step_ms_min=per_step[0],
         kept_blocks_per_row_mean=kept_mean,
         t_e2e_ms=t_step * 1e3, t_select_ms=t_sel * 1e3, t_attn_ms=t_att * 1e3,
         t_dense_ms=None if t_dense is None else t_dense * 1e3,
@@ -369,6 +378,7 @@ def main():
                    "sort": "QK", "beta": 1.0},
         "latency_ms": {"select": res["t_select_ms"], "attn": res["t_attn_ms"], "e2e": res["t_e2e_ms"],
                        "dense": res["t_dense_ms"]},
+        "step_ms_median": res["step_ms_median"], "step_ms_min": res["step_ms_min"],
         "speedup_vs_dense": res["speedup_vs_dense"],
         "executed_tflops": res["executed_tflops_attn_call"],
         "dense_tflops": res["dense_tflops"],
