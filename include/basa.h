@@ -73,7 +73,11 @@ typedef struct {
                                 m under a computational budget", Sec. 3.1 after Eq. 2, read
                                 as a mass budget), at least min_keep and at most kappa    */
   int32_t min_keep;          /* floor on the per-row count when mass_target > 0; 0 means 1 */
-  int32_t reserved;          /* 0                                                         */
+  int32_t attn_shape;        /* basa_sparse_attn, bf16 only: shape of the attention workgroup.
+                              * 0 = chosen by the library (on the device, from how much the
+                              * lists of neighbouring query blocks overlap), 1 = 256 queries
+                              * sharing every K/V tile, 2 = 128 queries.  Same results up to
+                              * fp32 summation order; other entry points ignore it.         */
 } basa_params;
 
 /* Host helper: the per-query-block budget kappa (Alg. 1 input) for n_k key blocks at
@@ -155,6 +159,7 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
  *   lse          out, nullable, [batch, heads_q, L_q] float: log-sum-exp of the kept
  *                logits of every query (original order).
  *   ws           workspace of basa_attn_workspace_size() bytes.
+ *   p            block and attn_shape are read.
  */
 basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                              const int32_t* row_count, const int32_t* row_cols,

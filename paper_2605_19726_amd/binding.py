@@ -40,7 +40,7 @@ class BasaTensor(C.Structure):
 class BasaParams(C.Structure):
     _fields_ = [("block", C.c_int32), ("sort", C.c_int32), ("window", C.c_int32),
                 ("beta", C.c_float), ("sparsity", C.c_double), ("mass_target", C.c_double),
-                ("min_keep", C.c_int32), ("reserved", C.c_int32)]
+                ("min_keep", C.c_int32), ("attn_shape", C.c_int32)]
 
 
 class BasaError(RuntimeError):
@@ -139,9 +139,9 @@ def tensor_desc(x: torch.Tensor) -> BasaTensor:
 
 
 def params(block: int, sparsity: float = 0.0, beta: float = 1.0, sort: int = SORT_QK,
-           window: int = 0, mass_target: float = 0.0, min_keep: int = 0) -> BasaParams:
+           window: int = 0, mass_target: float = 0.0, min_keep: int = 0, attn_shape: int = 0) -> BasaParams:
     return BasaParams(int(block), int(sort), int(window), float(beta), float(sparsity),
-                      float(mass_target), int(min_keep), 0)
+                      float(mass_target), int(min_keep), int(attn_shape))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -245,10 +245,10 @@ def basa_select(q: torch.Tensor, k: torch.Tensor, block: int, sparsity: float, b
 
 
 def basa_sparse_attn(q, k, v, row_count, row_cols, block: int, perm_q=None, perm_k=None,
-                     want_lse: bool = False, ws=None, out=None):
+                     want_lse: bool = False, ws=None, out=None, attn_shape: int = 0):
     lib = load()
     qd, kd, vd = tensor_desc(q), tensor_desc(k), tensor_desc(v)
-    p = params(block)
+    p = params(block, attn_shape=attn_shape)
     b, hq, Lq, d = q.shape
     if out is None:
         out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)

@@ -164,7 +164,7 @@ bool use_mfma(const basa_tensor* q) { return q->dtype == BASA_BF16; }   // d is 
 
 basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                         const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,
-                        const int32_t* perm_q, const int32_t* perm_k, int B, void* out, float* lse,
+                        const int32_t* perm_q, const int32_t* perm_k, int B, int variant, void* out, float* lse,
                         void* ws, size_t ws_bytes, void* stream) {
   if (!out) { set_error("null output pointer"); return BASA_ERR_INVALID_ARG; }
   if (reinterpret_cast<uintptr_t>(out) % 16) { set_error("out must be 16-byte aligned"); return BASA_ERR_INVALID_ARG; }
@@ -172,6 +172,7 @@ basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_t
   a.q = view_of(*q); a.k = view_of(*k); a.v = view_of(*v);
   a.row_count = row_count; a.row_cols = row_cols; a.cols_stride = cols_stride;
   a.perm_q = perm_q; a.perm_k = perm_k; a.B = B; a.out = out; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes;
+  a.variant = variant;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (use_mfma(q)) {
     const size_t need = attn_mfma_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L, q->d, B);
@@ -301,8 +302,9 @@ basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const b
   if ((s = check_params(p, false)) != BASA_OK) return s;
   if (row_cols && !row_count) { set_error("row_cols given without row_count"); return BASA_ERR_INVALID_ARG; }
   if (row_cols && cols_stride < 1) { set_error("cols_stride must be >= 1"); return BASA_ERR_INVALID_ARG; }
-  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, out, lse, ws,
-                     ws_bytes, stream);
+  if (p->attn_shape < 0 || p->attn_shape > 2) { set_error("attn_shape must be 0, 1 or 2"); return BASA_ERR_INVALID_ARG; }
+  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, out, lse,
+                     ws, ws_bytes, stream);
 }
 
 basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
@@ -311,7 +313,7 @@ basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const ba
   basa_status s;
   if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
-  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, out, lse, ws, ws_bytes, stream);
+  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 1, out, lse, ws, ws_bytes, stream);
 }
 
 const char* basa_status_string(basa_status s) {

@@ -46,11 +46,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTileKeys = 64;
-constexpr int kStages = 4;
-constexpr int kThreads = 512;
-constexpr int kWaves = kThreads / 64;
-constexpr int kQueriesPerWg = kWaves * 32;
 constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
+// Two shapes of workgroup.  SHARED: 8 waves own 256 queries = two (four) neighbouring query blocks
+// that share every K/V tile; best when their lists overlap, which they do for the full method.
+// SOLO: 4 waves own 128 queries = one query block of 128 (two of 64), two workgroups per compute
+// unit; every tile is fetched per 128 queries, but no wave ever waits for a tile that only its
+// neighbour lists - best when neighbouring lists have little in common.
+constexpr int kSharedQueries = 256, kSoloQueries = 128;
 
 // Sizes that follow from the head dimension D.
 template <int D>
@@ -59,12 +61,12 @@ struct Geo {
   static constexpr int kChunksPerRow = kRowBytes / 16;       // 16-byte chunks per row: 16 or 8
   static constexpr int kTileBytes = kTileKeys * kRowBytes;   // one K tile; a V^T tile (D rows of 128 B) is as large
   static constexpr int kStageBytes = 2 * kTileBytes;         // K tile then V^T tile
-  static constexpr int kRingBytes = kStages * kStageBytes;
   static constexpr int kKSteps = D / 16;                     // MFMA k-steps of S^T = K Q^T
   static constexpr int kDBlocks = D / 32;                    // 32-row blocks of O^T
   static constexpr int kChunksPerTile = kTileBytes / 1024;   // 1 KB direct-to-LDS loads per K (or V^T) tile
-  static constexpr int kLoadsPerWave = 2 * kChunksPerTile / kWaves;
 };
+// Ring stages of a workgroup shape: SHARED walks tiles in pairs (two slots of two), SOLO one by one.
+constexpr int stages_of(int wg_queries) { return wg_queries == kSharedQueries ? 4 : 2; }
 
 // ---------------------------------------------------------------------------------
 // Gather kernels
@@ -150,6 +152,8 @@ struct MfmaArgs {
   __bf16* out; float* lse;
   int Nq, Nk, Lq, Lk, group, wgs_per_head, total_wgs;
   float scale_log2e;
+  const int32_t* probe;      // nullable: {blocks in both lists, blocks in the lists} over sampled pairs
+  int run_if_solo;           // with probe: this launch runs iff (lists overlap little) == run_if_solo
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -243,11 +247,22 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
 // seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
 // this workgroup lists it).  While seq is being built the ring area holds the per-key-block
 // membership flags.
-template <int kB, int D>
-__global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
+template <int kB, int D, int kWgQueries>
+__global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 2) void attn_mfma_kernel(MfmaArgs a) {
   using G = Geo<D>;
-  constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = G::kRingBytes;
-  constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4
+  constexpr int kWaves = kWgQueries / 32, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
+  constexpr int kStages = stages_of(kWgQueries);
+  constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = kStages * kStageBytes;
+  constexpr int kLoadsPerWave = 2 * G::kChunksPerTile / kWaves;
+  constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4 (SOLO: 1 or 2)
+  if (a.probe) {
+    // the other shape of workgroup is launched too; exactly one of the two does the work.  Union of
+    // a pair of lists = both lists - common blocks; SOLO pays about 1.17x per tile, so it wins
+    // when the union exceeds 1.2 lists.
+    const int common = a.probe[0], listed = a.probe[1];
+    const bool little_overlap = 20 * (int64_t)(listed - common) > 12 * (int64_t)listed;
+    if ((int)little_overlap != a.run_if_solo) return;
+  }
   constexpr int WPG = kB / 32;               // waves per query block: 4 or 2
   constexpr int TPB = kB / kTileKeys;        // key tiles per key block: 2 or 1
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -334,7 +349,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
     const char* kp = Kh + (int64_t)tile * kTileBytes;      // wave-uniform bases
     const char* vp = Vh + (int64_t)tile * kTileBytes;
 #pragma unroll
-    for (int j = 0; j < G::kLoadsPerWave; ++j) {
+    for (int j = 0; j < kLoadsPerWave; ++j) {
       const int cb = j * kWaves + wave;                   // wave-uniform: K chunks first, then V^T chunks
       const char* src = (cb < G::kChunksPerTile ? kp : vp) + (cb % G::kChunksPerTile) * 1024 + (uint32_t)(lane * 16);
       char* dst = smem + stage * kStageBytes + cb * 1024;
@@ -346,9 +361,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
     return (int)(entry_of(tt) & 0xffffffu) * TPB + (tt % TPB);
   };
 
-  // prologue: tiles 0..2 into stages 0..2 (past the end: the last tile again, never read)
+  // prologue: the first tile (SHARED: the first pair; past the end: the last tile again, never read)
   issue_tile(tile_of(0), 0);
-  issue_tile(tile_of(1), 1);
+  if (kStages == 4) issue_tile(tile_of(1), 1);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[G::kKSteps];
@@ -390,6 +405,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
   // slot; their loads are issued right after the barrier, which also says that every wave is
   // done with that other slot (pair p-1).  The union entries of later tiles are read from LDS
   // early and turned into scalars late, so their latency hides behind the arithmetic.
+  if constexpr (kStages == 4) {
   uint32_t e_a = entry_of(0);
   uint32_t e_b = entry_of(min(1, n_tiles - 1));
   int t = 0;
@@ -425,6 +441,24 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
       if (e_a & my_bit) process_tile<true, D>(st, qf, slot, kaddr, vaddr, c, nvalid, h);
     }
   }
+  } else {
+    // SOLO: two stages, one tile per barrier; tile t+1 lands while tile t is computed
+    uint32_t e_cur = entry_of(0);
+    int t = 0;
+    for (; t + 1 < n_tiles; ++t) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      const uint32_t raw_n = seq[(t + 1) / TPB];
+      const uint32_t e_nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_n);
+      issue_tile((int)(e_nxt & 0xffffffu) * TPB + ((t + 1) % TPB), (t + 1) & 1);
+      if (e_cur & my_bit) process_tile<false, D>(st, qf, smem + (t & 1) * kStageBytes, kaddr, vaddr, c, kTileKeys, h);
+      e_cur = e_nxt;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
+    if (e_cur & my_bit) process_tile<true, D>(st, qf, smem + (t & 1) * kStageBytes, kaddr, vaddr, c, nvalid, h);
+  }
 
   // ---- epilogue: normalise, scatter rows to their original positions
   const float l_tot = st.l_run + __shfl_xor(st.l_run, 32);
@@ -449,14 +483,57 @@ __global__ __launch_bounds__(kThreads, 1) void attn_mfma_kernel(MfmaArgs a) {
 
 size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk * B * d * 2, 256); }
 
-template <int kB, int D>
-basa_status launch_main(const MfmaArgs& m, size_t lds, hipStream_t st) {
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D>),
+template <int D>
+size_t lds_bytes(int wg_queries, int Nk) {
+  return (size_t)stages_of(wg_queries) * Geo<D>::kStageBytes + (size_t)Nk * 4 + (wg_queries / 32) * 4;
+}
+
+template <int kB, int D, int kWgQueries>
+basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
+  const size_t lds = lds_bytes<D>(kWgQueries, m.Nk);
+  m.wgs_per_head = ceil_div(m.Nq * kB, kWgQueries);
+  m.total_wgs = BHq * m.wgs_per_head;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
-  hipLaunchKernelGGL((attn_mfma_kernel<kB, D>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
+  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries>), dim3(m.total_wgs), dim3(kWgQueries * 2), lds, st, m);
   BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
   return BASA_OK;
+}
+
+// How much the lists of neighbouring query blocks (2g, 2g+1) have in common, on every 4th pair:
+// probe[0] += blocks in both lists, probe[1] += blocks in the two lists.  One wave per pair; a
+// lane looks its entries of the first list up in the second (both ascending) by bisection.
+__global__ __launch_bounds__(256) void list_overlap_kernel(const int32_t* __restrict__ row_count,
+                                                           const int32_t* __restrict__ row_cols, int cols_stride,
+                                                           int Nq, int pairs_total, int32_t* __restrict__ probe) {
+  const int pair = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 4, lane = threadIdx.x & 63;
+  if (pair >= pairs_total) return;
+  const int pairs_per_head = Nq / 2;
+  const int bh = pair / pairs_per_head, g = (pair - bh * pairs_per_head) * 2;
+  const int64_t r0 = (int64_t)bh * Nq + g, r1 = r0 + 1;
+  const int na = max(0, min(row_count[r0], cols_stride)), nb = max(0, min(row_count[r1], cols_stride));
+  const int32_t* A = row_cols + r0 * cols_stride;
+  const int32_t* Bv = row_cols + r1 * cols_stride;
+  int common = 0;
+  for (int i = lane; i < na; i += 64) {
+    const int v = A[i];
+    int lo = 0, hi = nb;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (Bv[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    common += (lo < nb && Bv[lo] == v) ? 1 : 0;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) common += __shfl_xor(common, off);
+  if (lane == 0) {
+    atomicAdd(&probe[0], common);
+    atomicAdd(&probe[1], na + nb);
+  }
+}
+__global__ void zero_probe_kernel(int32_t* probe) {
+  if (threadIdx.x < 2) probe[threadIdx.x] = 0;
 }
 
 template <int D>
@@ -474,7 +551,7 @@ basa_status launch_gathers(const AttnArgs& a, uint4* Kt, uint4* Vt, int BHkv, in
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B) {
   const int Nq = ceil_div(Lq, B), Nk = ceil_div(Lk, B);
   (void)BHq; (void)Nq;
-  return 2 * sz_kv(BHkv, Nk, B, d);
+  return 2 * sz_kv(BHkv, Nk, B, d) + 256;      // + the two counters of the list-overlap probe
 }
 
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
@@ -483,7 +560,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   const int Nq = ceil_div(a.q.L, B), Nk = ceil_div(a.k.L, B);
   if (BHq == 0 || Nq == 0) return BASA_OK;
   const int d = a.q.d;
-  const size_t lds = (size_t)(d == 128 ? Geo<128>::kRingBytes : Geo<64>::kRingBytes) + (size_t)Nk * 4 + kWaves * 4;
+  const size_t lds = d == 128 ? lds_bytes<128>(kSharedQueries, Nk) : lds_bytes<64>(kSharedQueries, Nk);
   {
     int dev = 0, max_lds = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -497,6 +574,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   char* ws = reinterpret_cast<char*>(a.ws);
   uint4* Kt = reinterpret_cast<uint4*>(ws);
   uint4* Vt = reinterpret_cast<uint4*>(ws + sz_kv(BHkv, Nk, B, d));
+  int32_t* probe = reinterpret_cast<int32_t*>(ws + 2 * sz_kv(BHkv, Nk, B, d));
 
   {
     ProfScope prof(K_GATHER, st);
@@ -512,12 +590,38 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.out = reinterpret_cast<__bf16*>(a.out); m.lse = a.lse;
   m.Nq = Nq; m.Nk = Nk; m.Lq = a.q.L; m.Lk = a.k.L;
   m.group = a.q.heads / a.k.heads;
-  m.wgs_per_head = ceil_div(Nq * B, kQueriesPerWg);
-  m.total_wgs = BHq * m.wgs_per_head;
+  m.wgs_per_head = 0; m.total_wgs = 0;
   m.scale_log2e = 1.4426950408889634f / sqrtf((float)d);
+  m.probe = nullptr; m.run_if_solo = 0;
+
+  // Which shape of workgroup: asked for, or (B = d = 128, block lists given, enough work to pay for
+  // three tiny launches) decided on the device from how much neighbouring lists overlap.
+  int variant = a.variant;
+  const bool can_probe = a.row_cols != nullptr && B == 128 && d == 128 && Nq >= 8 && (int64_t)BHq * Nq >= 2048;
+  if (variant == 0 && !can_probe) variant = 1;
+  if (variant == 0) {
+    const int pairs_total = BHq * (Nq / 2);
+    hipLaunchKernelGGL(zero_probe_kernel, dim3(1), dim3(64), 0, st, probe);
+    BASA_HIP_CHECK_LAUNCH("zero_probe_kernel");
+    hipLaunchKernelGGL(list_overlap_kernel, dim3(ceil_div(ceil_div(pairs_total, 4), 4)), dim3(256), 0, st, a.row_count,
+                       a.row_cols, a.cols_stride, Nq, pairs_total, probe);
+    BASA_HIP_CHECK_LAUNCH("list_overlap_kernel");
+    m.probe = probe;
+  }
   ProfScope prof(K_ATTN, st);
-  if (d == 128) return B == 128 ? launch_main<128, 128>(m, lds, st) : launch_main<64, 128>(m, lds, st);
-  return B == 128 ? launch_main<128, 64>(m, lds, st) : launch_main<64, 64>(m, lds, st);
+  basa_status s = BASA_OK;
+  if (variant != 2) {
+    m.run_if_solo = 0;
+    if (d == 128) s = B == 128 ? launch_main<128, 128, kSharedQueries>(m, BHq, st) : launch_main<64, 128, kSharedQueries>(m, BHq, st);
+    else s = B == 128 ? launch_main<128, 64, kSharedQueries>(m, BHq, st) : launch_main<64, 64, kSharedQueries>(m, BHq, st);
+    if (s != BASA_OK) return s;
+  }
+  if (variant != 1) {
+    m.run_if_solo = 1;
+    if (d == 128) s = B == 128 ? launch_main<128, 128, kSoloQueries>(m, BHq, st) : launch_main<64, 128, kSoloQueries>(m, BHq, st);
+    else s = B == 128 ? launch_main<128, 64, kSoloQueries>(m, BHq, st) : launch_main<64, 64, kSoloQueries>(m, BHq, st);
+  }
+  return s;
 }
 
 }  // namespace basa

@@ -102,6 +102,7 @@ struct AttnArgs {
   float* lse;                 // [BHq][Lq] or null
   void* ws;
   size_t ws_bytes;
+  int variant;                // matrix-core path: 0 = library's choice, 1 = 256 queries per workgroup, 2 = 128
 };
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B);
 basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st);

@@ -99,6 +99,11 @@ def test_attention_argument_validation(lib):
     assert call(q, k, fake_tensor(L=128))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, v, out=None)[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, v)[0] == "BASA_ERR_WORKSPACE"
+    for bad in (-1, 3):
+        pb = bd.params(128, attn_shape=bad)
+        st = lib.basa_sparse_attn(C.byref(q), C.byref(k), C.byref(v), dummy, dummy, 4, None, None, C.byref(pb),
+                                  dummy, None, dummy, 1 << 40, None)
+        assert lib.basa_status_string(st) == b"BASA_ERR_INVALID_ARG"
     st = lib.basa_dense_attn(C.byref(q), C.byref(k), C.byref(v), C.byref(p), dummy, None, dummy, 16, None)
     assert lib.basa_status_string(st) == b"BASA_ERR_WORKSPACE"
 
