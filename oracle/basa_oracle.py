@@ -60,20 +60,31 @@ def token_sort_keys(x: np.ndarray) -> np.ndarray:
     return (x64 * x64).sum(axis=-1).astype(np.float32)
 
 
-def norm_sort(x: np.ndarray, window: int = 0) -> np.ndarray:
+def norm_sort(x: np.ndarray, window: int = 0, segments=None) -> np.ndarray:
     """Permutation pi with keys non-decreasing along pi (Eq. 10).
 
     Reading: ties keep the original order (stable sort).  "(windowed) sort" of
     Alg. 1 step 1 is not defined in the paper; window = 0 is one sort over the
     whole sequence, window = W sorts each run of W consecutive tokens by itself.
+    segments = [0, s_1, s_2, ...] (ascending token indices) is the same with runs
+    of unequal length: tokens s_j .. s_{j+1}-1 (the last run ends at L) are sorted
+    among themselves, so a modality or a frame keeps its range of positions.
     """
     keys = token_sort_keys(x)
     L = keys.shape[0]
-    W = L if not window else int(window)
+    if segments is not None:
+        if window:
+            raise ValueError("window and segments exclude each other")
+        starts = [int(v) for v in segments]
+        if not starts or starts[0] != 0 or any(b <= a for a, b in zip(starts, starts[1:])) or starts[-1] >= max(L, 1):
+            raise ValueError("segments must start at 0, ascend strictly and stay below L")
+        bounds = starts + [L]
+    else:
+        W = L if not window else int(window)
+        bounds = list(range(0, L, W)) + [L]
     perm = np.empty(L, dtype=np.int64)
-    for w0 in range(0, L, W):
-        seg = keys[w0:w0 + W]
-        perm[w0:w0 + W] = w0 + np.argsort(seg, kind="stable")
+    for w0, w1 in zip(bounds, bounds[1:]):
+        perm[w0:w1] = w0 + np.argsort(keys[w0:w1], kind="stable")
     return perm
 
 
@@ -274,15 +285,15 @@ def sparse_attention(Q, K, V, perm_q, perm_k, cols, B: int, return_lse: bool = F
 # The whole operator (Alg. 1)
 # --------------------------------------------------------------------------- #
 def select(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK,
-           window: int = 0, mass_target: float | None = None, min_keep: int = 1):
+           window: int = 0, mass_target: float | None = None, min_keep: int = 1, segments=None):
     """Alg. 1 steps 1-11 for one head: permutations, block statistics, compensated
     logits, row distribution, top-kappa mask.  Returns a dict with every
     intermediate.  With mass_target the mask is the cumulative-mass one instead
     (select_top_mass), capped at the kappa that `sparsity` gives."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
-    perm_q = norm_sort(Q, window) if sort in (SORT_Q, SORT_QK) else identity_perm(Q.shape[0])
-    perm_k = norm_sort(K, window) if sort in (SORT_K, SORT_QK) else identity_perm(K.shape[0])
+    perm_q = norm_sort(Q, window, segments) if sort in (SORT_Q, SORT_QK) else identity_perm(Q.shape[0])
+    perm_k = norm_sort(K, window, segments) if sort in (SORT_K, SORT_QK) else identity_perm(K.shape[0])
     q_mean, q_var = block_stats(Q[perm_q], B)
     k_mean, k_var = block_stats(K[perm_k], B)
     logits = block_logits(q_mean, q_var, k_mean, k_var, beta)

@@ -125,6 +125,38 @@ def test_windowed_sort_stays_in_window():
     assert o.norm_sort(x, window=0).tolist() == o.norm_sort(x, window=100).tolist()
 
 
+def test_segment_sort_against_python_sorted_per_segment():
+    x = rand(97, 3)
+    x[40] = x[12]                                  # a tie across segments and one inside
+    x[13] = x[12]
+    keys = [np.float32(sum(float(v) * float(v) for v in row)) for row in x]
+    starts = [0, 5, 6, 50]
+    perm = o.norm_sort(x, segments=starts)
+    expect = []
+    for a, b in zip(starts, starts[1:] + [97]):
+        expect += sorted(range(a, b), key=lambda i: (keys[i], i))
+    assert perm.tolist() == expect
+    assert perm[5] == 5                            # a one-token segment stays where it is
+    # one segment is the global sort; equal segments are the windowed sort
+    assert o.norm_sort(x, segments=[0]).tolist() == o.norm_sort(x).tolist()
+    assert o.norm_sort(x, segments=[0, 32, 64, 96]).tolist() == o.norm_sort(x, window=32).tolist()
+    for bad in ([], [1, 5], [0, 5, 5], [0, 97], [0, 9, 3]):
+        with pytest.raises(ValueError):
+            o.norm_sort(x, segments=bad)
+    with pytest.raises(ValueError):
+        o.norm_sort(x, window=32, segments=[0, 32])
+
+
+def test_select_with_segments_only_changes_the_permutations():
+    Q, K = rand(70, 4), rand(70, 4)
+    starts = [0, 16, 48]
+    ref = o.select(Q, K, 8, 0.5, segments=starts)
+    assert ref["perm_q"].tolist() == o.norm_sort(Q, segments=starts).tolist()
+    assert ref["perm_k"].tolist() == o.norm_sort(K, segments=starts).tolist()
+    qm, qv = o.block_stats(Q[ref["perm_q"]], 8)
+    assert np.array_equal(qm, ref["q_mean"]) and np.array_equal(qv, ref["q_var"])
+
+
 def test_sort_key_is_fp32_rounded_squared_norm():
     x = np.array([[3.0, 4.0], [1e-3, 0.0]])
     k = o.token_sort_keys(x)
