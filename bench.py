@@ -142,8 +142,11 @@ def fidelity_report(w, Q, K, sparsities):
     of norm sorting and covariance compensation, on this workload's synthetic tensors."""
     dev = Q.device
     rows = []
-    for sort, sort_name in ((bd.SORT_NONE, "none"), (bd.SORT_QK, "QK")):
-        base = bd.basa_select(Q, K, w.block, 0.5, beta=0.0, sort=sort, want_scores=True)
+    variants = [(bd.SORT_NONE, "none", None), (bd.SORT_QK, "QK", None)]
+    if synth.segments_of(w) is not None:
+        variants.append((bd.SORT_QK, "QK per segment", synth.segments_of(w)))
+    for sort, sort_name, segments in variants:
+        base = bd.basa_select(Q, K, w.block, 0.5, beta=0.0, sort=sort, want_scores=True, segments=segments)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         m_hat, max_dev, _ = bd.basa_block_mass(Q, K, w.block, base.perm_q, base.perm_k,
@@ -159,7 +162,7 @@ def fidelity_report(w, Q, K, sparsities):
         for beta in (0.0, 1.0):
             for s in sparsities:
                 sel = base if (beta == 0.0 and s == 0.5) else bd.basa_select(Q, K, w.block, s, beta=beta, sort=sort,
-                                                                             want_scores=True)
+                                                                             want_scores=True, segments=segments)
                 recall, l1 = bd.basa_selection_fidelity(sel.scores, sel.mask_bits, m_hat)
                 rows.append({"workload": w.name, "sort": sort_name, "beta": beta, "sparsity": s,
                              "kept_fraction": sel.kappa / sel.n_k, "recall_mean": float(recall.mean()),

@@ -78,7 +78,17 @@ typedef struct {
                               * lists of neighbouring query blocks overlap), 1 = 256 queries
                               * sharing every K/V tile, 2 = 128 queries.  Same results up to
                               * fp32 summation order; other entry points ignore it.         */
+  int32_t n_segments;        /* 0: none.  1..BASA_MAX_SEGMENTS: the sort is segment-aware (the
+                                windowed sort of Alg. 1 step 1 with runs of unequal length, e.g.
+                                one run per modality or frame): tokens segment_starts[j] ..
+                                segment_starts[j+1]-1 (the last segment ends at L) are sorted
+                                among themselves and keep their range of positions.  Excludes
+                                window > 0; with two tensors (basa_select) L_q must equal L_k  */
+  int32_t reserved;          /* 0                                                             */
+  const int32_t* segment_starts;   /* HOST array of n_segments token indices: first 0, strictly
+                                ascending, last < L; read during the call only (NULL if none) */
 } basa_params;
+#define BASA_MAX_SEGMENTS 63
 
 /* Host helper: the per-query-block budget kappa (Alg. 1 input) for n_k key blocks at
  * sparsity s, by the formula above.  Returns -1 if s is outside [0,1) or n_k < 1. */

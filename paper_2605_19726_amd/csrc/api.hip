@@ -103,6 +103,18 @@ basa_status check_params(const basa_params* p, bool need_sparsity) {
     set_error("window %d must be 0 or a positive multiple of the block size", p->window);
     return BASA_ERR_INVALID_ARG;
   }
+  if (p->n_segments < 0 || p->n_segments > BASA_MAX_SEGMENTS) {
+    set_error("n_segments %d outside [0, %d]", p->n_segments, BASA_MAX_SEGMENTS); return BASA_ERR_INVALID_ARG;
+  }
+  if (p->n_segments > 0) {
+    if (!p->segment_starts) { set_error("n_segments > 0 with a null segment_starts"); return BASA_ERR_INVALID_ARG; }
+    if (p->window != 0) { set_error("window and segments exclude each other"); return BASA_ERR_INVALID_ARG; }
+    if (p->segment_starts[0] != 0) { set_error("segment_starts[0] must be 0"); return BASA_ERR_INVALID_ARG; }
+    for (int j = 1; j < p->n_segments; ++j)
+      if (p->segment_starts[j] <= p->segment_starts[j - 1]) {
+        set_error("segment_starts must ascend strictly (entry %d)", j); return BASA_ERR_INVALID_ARG;
+      }
+  }
   if (need_sparsity && !(p->sparsity >= 0.0 && p->sparsity < 1.0)) {
     set_error("sparsity %g outside [0, 1)", p->sparsity); return BASA_ERR_INVALID_ARG;
   }
@@ -114,6 +126,18 @@ basa_status check_params(const basa_params* p, bool need_sparsity) {
   }
   if (need_sparsity && p->min_keep < 0) {
     set_error("min_keep %d is negative", p->min_keep); return BASA_ERR_INVALID_ARG;
+  }
+  return BASA_OK;
+}
+
+// The segment list of p for a sequence of L tokens, in the form the kernels take.
+basa_status seg_list(const basa_params* p, int L, SegList* out) {
+  out->n = p->n_segments;
+  for (int j = 0; j < p->n_segments; ++j) out->bound[j] = p->segment_starts[j];
+  for (int j = p->n_segments; j <= BASA_MAX_SEGMENTS; ++j) out->bound[j] = L;
+  if (p->n_segments > 0 && p->segment_starts[p->n_segments - 1] >= L) {
+    set_error("last segment start %d is not below L = %d", p->segment_starts[p->n_segments - 1], L);
+    return BASA_ERR_INVALID_ARG;
   }
   return BASA_OK;
 }
@@ -223,7 +247,10 @@ basa_status basa_norm_sort(const basa_tensor* x, const basa_params* p, int32_t* 
     return BASA_ERR_WORKSPACE;
   }
   if (reinterpret_cast<uintptr_t>(ws) % 256) { set_error("workspace must be 256-byte aligned"); return BASA_ERR_INVALID_ARG; }
-  return launch_norm_sort(view_of(*x), p->window, perm, keys_out, ws, reinterpret_cast<hipStream_t>(stream));
+  SegList segs;
+  if ((s = seg_list(p, x->L, &segs)) != BASA_OK) return s;
+  if (x->L > kMaxSortLen) { set_error("sequences beyond %d tokens not supported", kMaxSortLen); return BASA_ERR_UNSUPPORTED; }
+  return launch_norm_sort(view_of(*x), p->window, segs, perm, keys_out, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
 basa_status basa_downsample(const basa_tensor* x, const int32_t* perm, const basa_params* p, float* mean,
@@ -256,7 +283,13 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   const int BHq = q->batch * q->heads, BHk = k->batch * k->heads;
   const int Nq = ceil_div(q->L, B), Nk = ceil_div(k->L, B);
   if (Nk > 4096) { set_error("more than 4096 key blocks per row (%d) not supported", Nk); return BASA_ERR_UNSUPPORTED; }
+  if (q->L > kMaxSortLen) { set_error("sequences beyond %d tokens not supported", kMaxSortLen); return BASA_ERR_UNSUPPORTED; }
   const int kappa = kappa_of(Nk, p->sparsity);
+  SegList segs;
+  if (p->n_segments > 0 && q->L != k->L) {
+    set_error("a segment-aware sort needs L_q == L_k (%d, %d)", q->L, k->L); return BASA_ERR_INVALID_ARG;
+  }
+  if ((s = seg_list(p, q->L, &segs)) != BASA_OK) return s;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* base = reinterpret_cast<char*>(ws);
   void* sort_ws = base + w.sort_off;
@@ -269,13 +302,13 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   const bool sort_k = p->sort == BASA_SORT_K || p->sort == BASA_SORT_QK;
   const bool same_len = q->L == k->L;       // then Q and K share every launch
   if (sort_q && sort_k && same_len) {
-    s = launch_norm_sort2(qv, kv, p->window, perm_q, perm_k, sort_ws, st);
+    s = launch_norm_sort2(qv, kv, p->window, segs, perm_q, perm_k, sort_ws, st);
     if (s != BASA_OK) return s;
   } else {
-    if (sort_q) s = launch_norm_sort(qv, p->window, perm_q, nullptr, sort_ws, st);
+    if (sort_q) s = launch_norm_sort(qv, p->window, segs, perm_q, nullptr, sort_ws, st);
     else s = launch_iota_perm(perm_q, BHq, q->L, st);
     if (s != BASA_OK) return s;
-    if (sort_k) s = launch_norm_sort(kv, p->window, perm_k, nullptr, sort_ws, st);
+    if (sort_k) s = launch_norm_sort(kv, p->window, segs, perm_k, nullptr, sort_ws, st);
     else s = launch_iota_perm(perm_k, BHk, k->L, st);
     if (s != BASA_OK) return s;
   }

@@ -55,10 +55,17 @@ struct ProfScope {
 
 // Sort keys + segmented sort.  Writes perm[bh][L]; optional keys_out[bh][L].
 size_t sort_workspace_bytes(int BH, int L);
-basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
+constexpr int kMaxSortLen = 1 << 27;      // token indices take 27 bits of a packed sort word
+// Segment starts of a segment-aware sort, passed to kernels by value: bound[0] = 0 < bound[1] <
+// ... < bound[n-1] < bound[n] = L; n <= 1 means one segment.
+struct SegList {
+  int n;
+  int bound[BASA_MAX_SEGMENTS + 1];
+};
+basa_status launch_norm_sort(const TensorView& x, int window, const SegList& segs, int32_t* perm, float* keys_out,
                              void* ws, hipStream_t st);
 // Two tensors of identical L, d and dtype through the same launches (ws sized for both).
-basa_status launch_norm_sort2(const TensorView& q, const TensorView& k, int window, int32_t* perm_q,
+basa_status launch_norm_sort2(const TensorView& q, const TensorView& k, int window, const SegList& segs, int32_t* perm_q,
                               int32_t* perm_k, void* ws, hipStream_t st);
 basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 

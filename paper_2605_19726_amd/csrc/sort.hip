@@ -2,10 +2,12 @@
 // merge sort of (key, index) pairs, one segment per (head, window).
 //
 // Key of a token = fp32 rounding of the fp64 sum of squares of its d values.  Each
-// pair is packed into one 64-bit word, key bits high and token index low: keys are
-// non-negative floats, whose bit patterns order like the values, so an unsigned
-// compare of the packed words orders by key and breaks ties by lower index, which
-// also makes every word of a segment distinct (no stability concerns in the sort).
+// pair is packed into one 64-bit word, [segment : 6][key bits without the sign : 31][token
+// index : 27]: keys are non-negative floats, whose bit patterns order like the values, so an
+// unsigned compare of the packed words orders by segment, then key, and breaks ties by lower
+// index, which also makes every word distinct (no stability concerns in the sort).  The
+// segment field is 0 unless the caller gave a list of segments of unequal length; those are
+// sorted as ONE sequence per head, and the segment field keeps every segment in its range.
 #include "common.hpp"
 
 namespace basa {
@@ -15,6 +17,12 @@ constexpr int kSortThreads = 256;
 constexpr int kTile = 4096;          // elements sorted per workgroup in LDS (32 KB)
 constexpr int kMergeItems = 8;       // outputs per thread in a merge pass
 constexpr int kMergeChunk = kSortThreads * kMergeItems;   // 2048 outputs per workgroup
+constexpr int kIdxBits = 27;
+static_assert((1 << kIdxBits) == kMaxSortLen && BASA_MAX_SEGMENTS < 64, "fields of the packed word");
+__device__ __forceinline__ uint64_t pack_word(int seg, float key, int idx) {
+  return ((uint64_t)(uint32_t)seg << 58) | ((uint64_t)(__float_as_uint(key) & 0x7fffffffu) << kIdxBits) | (uint32_t)idx;
+}
+__device__ __forceinline__ int32_t idx_of_word(uint64_t w) { return (int32_t)((uint32_t)w & ((1u << kIdxBits) - 1u)); }
 
 // ---------------------------------------------------------------------------------
 // Keys + tile sort in one kernel.  A workgroup owns one tile of up to kTile consecutive tokens
@@ -123,7 +131,8 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
                                                                       uint64_t* __restrict__ out,
                                                                       int32_t* __restrict__ perm0,
                                                                       int32_t* __restrict__ perm1,
-                                                                      float* __restrict__ keys_out, SegGeom g) {
+                                                                      float* __restrict__ keys_out, SegGeom g,
+                                                                      SegList sl) {
   constexpr int kElem = kBf16 ? 2 : 4;
   constexpr int LPR = kD * kElem / 16;          // lanes per row: 8, 16 or 32
   constexpr int kRowsPerIter = kSortThreads / LPR;
@@ -146,6 +155,10 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
   const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(second ? bh - BH0 : bh) * kElem;
   const int sub = threadIdx.x % LPR;
   const int rig = threadIdx.x / LPR;
+  // segment of the tile's first token; nearly every tile lies inside one segment
+  int seg_lo = 0;
+  for (int j = 1; j < sl.n; ++j) seg_lo += (start >= sl.bound[j]) ? 1 : 0;
+  const bool one_segment = sl.n <= 1 || start + n <= sl.bound[seg_lo + 1];
 
   // ---- phase 1: keys of tokens start .. start+n-1 into buf
   auto load_pass = [&](int pass, uint4 (&raw)[kIters]) {
@@ -208,7 +221,10 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
     const int loc = pass * kRowsPerPass + it_mine * kRowsPerIter + rig;
     if (sub < 8 && loc < n) {
       const float key = (float)acc[0];
-      buf[tile_slot(loc)] = ((uint64_t)__float_as_uint(key) << 32) | (uint32_t)(start + loc);
+      int sg = seg_lo;
+      if (!one_segment)
+        for (int j = seg_lo + 1; j < sl.n; ++j) sg += (start + loc >= sl.bound[j]) ? 1 : 0;
+      buf[tile_slot(loc)] = pack_word(sg, key, start + loc);
       if (keys_out) keys_out[hb + start + loc] = key;
     }
 #pragma unroll
@@ -220,7 +236,7 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
   // ---- phase 2: bitonic network over the kTile words
   sort_tile_in_lds(buf, threadIdx.x);
   if (perm_out) {
-    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[hb + start + i] = (int32_t)(uint32_t)buf[tile_slot(i)];
+    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[hb + start + i] = idx_of_word(buf[tile_slot(i)]);
   } else {
     for (int i = threadIdx.x; i < n; i += kSortThreads) out[hb + start + i] = buf[tile_slot(i)];
   }
@@ -298,7 +314,7 @@ __global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t
   __syncthreads();
   const int64_t obase = hb + a0 + diag0;
   if (perm_out) {
-    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[obase + i] = (int32_t)(uint32_t)buf[i];
+    for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[obase + i] = idx_of_word(buf[i]);
   } else {
     for (int i = threadIdx.x; i < n; i += kSortThreads) out[obase + i] = buf[i];
   }
@@ -324,7 +340,7 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st) {
 }
 
 // Sort one tensor (x1 == nullptr) or two tensors of identical L, d and dtype in the same launches.
-static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, int window, int32_t* perm0,
+static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, int window, const SegList& segs, int32_t* perm0,
                                   int32_t* perm1, float* keys_out, void* ws, hipStream_t st) {
   const int BH0 = x0.batch * x0.heads, BH1 = x1 ? x1->batch * x1->heads : 0, L = x0.L;
   const int BH = BH0 + BH1;
@@ -338,7 +354,7 @@ static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, in
 
   SegGeom g;
   g.L = L;
-  g.W = (window > 0 && window < L) ? window : L;
+  g.W = (window > 0 && window < L) ? window : L;      // a segment list is sorted as one run of L
   g.segs = ceil_div(L, g.W);
   g.tiles_per_seg = ceil_div(g.W, kTile);
   const bool single = g.tiles_per_seg == 1;
@@ -347,7 +363,7 @@ static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, in
   const dim3 grid(g.segs * g.tiles_per_seg, BH);
 #define BASA_KEYS(BF, D)                                                                              \
   hipLaunchKernelGGL((norm_tile_sort_kernel<BF, D>), grid, dim3(kSortThreads), 0, st, x0, xb, BH0, buf1, \
-                     single ? perm0 : nullptr, single ? perm1 : nullptr, keys_out, g)
+                     single ? perm0 : nullptr, single ? perm1 : nullptr, keys_out, g, segs)
   if (bf16 && x0.d == 128) BASA_KEYS(true, 128);
   else if (bf16 && x0.d == 64) BASA_KEYS(true, 64);
   else if (!bf16 && x0.d == 128) BASA_KEYS(false, 128);
@@ -373,14 +389,14 @@ static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, in
   return BASA_OK;
 }
 
-basa_status launch_norm_sort(const TensorView& x, int window, int32_t* perm, float* keys_out,
+basa_status launch_norm_sort(const TensorView& x, int window, const SegList& segs, int32_t* perm, float* keys_out,
                              void* ws, hipStream_t st) {
-  return norm_sort_impl(x, nullptr, window, perm, nullptr, keys_out, ws, st);
+  return norm_sort_impl(x, nullptr, window, segs, perm, nullptr, keys_out, ws, st);
 }
 
-basa_status launch_norm_sort2(const TensorView& q, const TensorView& k, int window, int32_t* perm_q,
-                              int32_t* perm_k, void* ws, hipStream_t st) {
-  return norm_sort_impl(q, &k, window, perm_q, perm_k, nullptr, ws, st);
+basa_status launch_norm_sort2(const TensorView& q, const TensorView& k, int window, const SegList& segs,
+                              int32_t* perm_q, int32_t* perm_k, void* ws, hipStream_t st) {
+  return norm_sort_impl(q, &k, window, segs, perm_q, perm_k, nullptr, ws, st);
 }
 
 }  // namespace basa

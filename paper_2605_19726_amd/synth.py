@@ -169,6 +169,17 @@ _HEAD_FN = {"salient": _head_salient, "lowrank": _head_lowrank,
             "multimodal": _head_multimodal, "video": _head_video}
 
 
+def segments_of(w: Workload):
+    """Token index at which each natural segment of the workload starts (the image and the text
+    of the multimodal sequence, the frames of the video), or None when there is only one."""
+    if w.kind == "multimodal" and 0 < w.image_side * w.image_side < w.L:
+        return [0, w.image_side * w.image_side]
+    if w.kind == "video" and w.video_thw[0] > 1:
+        frame = w.video_thw[1] * w.video_thw[2]
+        return [t * frame for t in range(w.video_thw[0])]
+    return None
+
+
 def make_qkv(w: Workload, device="cpu"):
     """Return (Q [1,Hq,L,d], K [1,Hkv,L,d], V [1,Hkv,L,d]) for workload `w`.
 

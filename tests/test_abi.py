@@ -82,6 +82,16 @@ def test_select_argument_validation(lib):
     assert call(q, k, bd.params(128, 0.5, mass_target=1.5))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=-0.1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=0.9, min_keep=-1))[0] == "BASA_ERR_INVALID_ARG"
+    seg = lambda starts, **kw: bd.params(128, 0.5, segments=starts, **kw)
+    assert call(q, k, seg([1, 5]))[0] == "BASA_ERR_INVALID_ARG"                 # must start at 0
+    assert call(q, k, seg([0, 5, 5]))[0] == "BASA_ERR_INVALID_ARG"              # must ascend strictly
+    assert call(q, k, seg([0, 1000]))[0] == "BASA_ERR_INVALID_ARG"              # last start must be below L = 256
+    assert call(q, k, seg([0, 128], window=128))[0] == "BASA_ERR_INVALID_ARG"   # one or the other
+    assert call(q, k, seg(list(range(64))))[0] == "BASA_ERR_INVALID_ARG"        # at most 63
+    assert call(q, fake_tensor(L=2000), seg([0, 5]))[0] == "BASA_ERR_INVALID_ARG"   # L_q != L_k
+    pn = bd.params(128, 0.5); pn.n_segments = 2
+    assert call(q, k, pn)[0] == "BASA_ERR_INVALID_ARG"                          # count without the array
+    assert call(q, k, seg([0, 5]), wsb=16)[0] == "BASA_ERR_WORKSPACE"           # a valid list gets past the checks
     assert call(q, k, p, rc=None)[0] == "BASA_ERR_INVALID_ARG"
     name, why = call(q, k, p, wsb=16)
     assert name == "BASA_ERR_WORKSPACE" and "need" in why

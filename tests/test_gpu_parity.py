@@ -59,6 +59,44 @@ def test_norm_sort_windowed_and_ties():
             assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), want), f"window={window}"
 
 
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_norm_sort_segments(dtype, d):
+    L = 20000 + 37
+    g = torch.Generator().manual_seed(77)
+    X = torch.randn((1, 2, L, d), generator=g).to(dtype).to(DEV)
+    X[0, 0, 9000:9064] = X[0, 0, 100:164]            # exact ties across segments and tiles
+    X[0, 1, 4090:4100] = X[0, 1, 4080:4090]          # and around a tile edge
+    cases = [[0], [0, 1], [0, L - 1], [0, 4096], [0, 4095, 4097], [0, 100, 101, 9000, 9032, 16384],
+             list(range(0, 63 * 300, 300)),           # the maximum of 63 segments, several per tile
+             [0] + list(range(5000, 5000 + 62))]      # one-token segments
+    for starts in cases:
+        perm = bd.basa_norm_sort(X, 128, segments=starts)
+        for h in range(2):
+            want = o.norm_sort(np64(X[0, h]), segments=starts)
+            assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), want), f"segments={starts[:8]}"
+
+
+def test_select_and_attention_with_segments():
+    # image + text segments as in the multimodal workload, scaled down; the segment edge is no
+    # multiple of the block, so one block of the sorted order holds tokens of both
+    w = C[2].scaled("seg", heads_q=4, heads_kv=2, L=6000 + 11, image_side=40)
+    Q, K, V = gen(w)
+    starts = [0, 1600, 3000]
+    sel = bd.basa_select(Q, K, w.block, 0.5, want_scores=True, segments=starts)
+    out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+    torch.cuda.synchronize()
+    gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
+    for h in range(4):
+        q, k, v = np64(Q[0, h]), np64(K[0, h // 2]), np64(V[0, h // 2])
+        ref = o.select(q, k, w.block, 0.5, segments=starts)
+        assert np.array_equal(sel.perm_q[0, h].cpu().numpy(), ref["perm_q"])
+        assert np.array_equal(sel.perm_k[0, h // 2].cpu().numpy(), ref["perm_k"])
+        assert mask_report(gpu_mask[0, h], ref)[0] == 0
+        cols = sel.row_cols[0, h].cpu().numpy().astype(np.int64)
+        O_ref = o.sparse_attention(q, k, v, ref["perm_q"], ref["perm_k"], cols, w.block)
+        check_output(np64(out[0, h]), O_ref, True, f"segments head {h}")
+
+
 def test_norm_sort_keys_zeros_subnormals_and_scales():
     """Sort keys stay bit-identical to the oracle's when rows hold exact zeros, bf16 subnormals,
     all-zero rows, and values spread over many binades (within what an fp64 sum adds exactly)."""

@@ -31,7 +31,12 @@ def _case(i):
     mass = float(rng.choice([0.0, 0.0, 0.6, 0.95]))
     min_keep = int(rng.choice([0, 1, 3]))
     scale = float(rng.choice([0.25, 1.0, 3.0]))
-    return dict(bf16=bf16, d=d, block=block, hq=hq, hk=hk, Lq=Lq, Lk=Lk, s=s, sort=sort, beta=beta, window=window,
+    segments = None
+    if Lq == Lk and Lk > 4 and rng.integers(4) == 0:       # drawn last: earlier cases keep their inputs
+        window = 0
+        cuts = np.sort(rng.choice(np.arange(1, Lk), size=int(rng.integers(1, 4)), replace=False))
+        segments = [0] + [int(v) for v in cuts]
+    return dict(segments=segments, bf16=bf16, d=d, block=block, hq=hq, hk=hk, Lq=Lq, Lk=Lk, s=s, sort=sort, beta=beta, window=window,
                 mass=mass, min_keep=min_keep, scale=scale, seed=int(rng.integers(1 << 30)))
 
 
@@ -44,7 +49,7 @@ def test_random_case(i):
     Q, K, V = mk(c["hq"], c["Lq"], c["scale"]), mk(c["hk"], c["Lk"], c["scale"]), mk(c["hk"], c["Lk"], 1.0)
     B = c["block"]
     sel = bd.basa_select(Q, K, B, c["s"], c["beta"], c["sort"], c["window"], want_scores=True,
-                         mass_target=c["mass"], min_keep=c["min_keep"])
+                         mass_target=c["mass"], min_keep=c["min_keep"], segments=c["segments"])
     out, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, B, sel.perm_q, sel.perm_k, want_lse=True,
                                     attn_shape=i % 3)
     torch.cuda.synchronize()
@@ -54,7 +59,8 @@ def test_random_case(i):
     for h in range(c["hq"]):
         q, k, v = np64(Q[0, h]), np64(K[0, h // group]), np64(V[0, h // group])
         ref = o.select(q, k, B, c["s"], c["beta"], c["sort"], c["window"],
-                       mass_target=c["mass"] if c["mass"] > 0 else None, min_keep=c["min_keep"])
+                       mass_target=c["mass"] if c["mass"] > 0 else None, min_keep=c["min_keep"],
+                       segments=c["segments"])
         assert np.array_equal(sel.perm_q[0, h].cpu().numpy(), ref["perm_q"]), what
         assert np.array_equal(sel.perm_k[0, h // group].cpu().numpy(), ref["perm_k"]), what
         sc = sel.scores[0, h].cpu().numpy().astype(np.float64)
