@@ -165,7 +165,12 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
  *                above cols_stride is cut to it, and a query block left without any valid
  *                key block gets zero output rows (lse -inf).  Entries must not repeat.
  *   perm_q/_k    nullable (NULL = identity).
- *   out          [batch, heads_q, L_q, d] contiguous, dtype of q.
+ *   out          [batch, heads_q, L_q, d], dtype of q, 16-byte aligned.
+ *   out_strides  nullable HOST array of 3: strides of out's batch, head and token axes in
+ *                elements (each a multiple of 16 bytes, token stride >= d; the d axis has
+ *                stride 1).  NULL = contiguous.  A token-major [batch, L_q, heads_q, d]
+ *                buffer, which a following projection reads directly, is {L*H*d, d, H*d}.
+ *                Rows of out must not alias each other or the inputs.
  *   lse          out, nullable, [batch, heads_q, L_q] float: log-sum-exp of the kept
  *                logits of every query (original order).
  *   ws           workspace of basa_attn_workspace_size() bytes.
@@ -174,8 +179,8 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
 basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                              const int32_t* row_count, const int32_t* row_cols,
                              int32_t cols_stride, const int32_t* perm_q, const int32_t* perm_k,
-                             const basa_params* p, void* out, float* lse, void* ws,
-                             size_t ws_bytes, void* stream);
+                             const basa_params* p, void* out, const int64_t* out_strides,
+                             float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Dense bidirectional attention (Eq. 1) through the same kernels with every key
@@ -183,8 +188,8 @@ basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const b
  * Only p->block is read.
  */
 basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
-                            const basa_params* p, void* out, float* lse, void* ws,
-                            size_t ws_bytes, void* stream);
+                            const basa_params* p, void* out, const int64_t* out_strides,
+                            float* lse, void* ws, size_t ws_bytes, void* stream);
 
 const char* basa_status_string(basa_status s);
 /* Reason of the last non-OK status returned on this thread (host string, owned by the

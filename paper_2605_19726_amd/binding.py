@@ -80,9 +80,10 @@ def load():
     lib.basa_select.restype = C.c_int
     lib.basa_select.argtypes = [T, T, P, V, V, V, V, V, V, V, V, C.c_size_t, V]
     lib.basa_sparse_attn.restype = C.c_int
-    lib.basa_sparse_attn.argtypes = [T, T, T, V, V, C.c_int32, V, V, P, V, V, V, C.c_size_t, V]
+    S3 = C.POINTER(C.c_int64)
+    lib.basa_sparse_attn.argtypes = [T, T, T, V, V, C.c_int32, V, V, P, V, S3, V, V, C.c_size_t, V]
     lib.basa_dense_attn.restype = C.c_int
-    lib.basa_dense_attn.argtypes = [T, T, T, P, V, V, V, C.c_size_t, V]
+    lib.basa_dense_attn.argtypes = [T, T, T, P, V, S3, V, V, C.c_size_t, V]
     lib.basa_status_string.restype = C.c_char_p
     lib.basa_status_string.argtypes = [C.c_int]
     lib.basa_last_error.restype = C.c_char_p
@@ -255,20 +256,31 @@ def basa_select(q: torch.Tensor, k: torch.Tensor, block: int, sparsity: float, b
     return s
 
 
+def _out_strides(out: torch.Tensor, q: torch.Tensor):
+    """out must index as [batch, heads_q, L_q, d] (any view whose last axis has stride 1)."""
+    if tuple(out.shape) != tuple(q.shape) or out.dtype != q.dtype or out.device != q.device:
+        raise ValueError("out must have the shape, dtype and device of q")
+    if out.stride(3) != 1:
+        raise ValueError("out: the d axis must have stride 1")
+    return (C.c_int64 * 3)(out.stride(0), out.stride(1), out.stride(2))
+
+
 def basa_sparse_attn(q, k, v, row_count, row_cols, block: int, perm_q=None, perm_k=None,
                      want_lse: bool = False, ws=None, out=None, attn_shape: int = 0):
+    """out: optional [batch, heads_q, L_q, d] view to write into (strided views are passed as such)."""
     lib = load()
     qd, kd, vd = tensor_desc(q), tensor_desc(k), tensor_desc(v)
     p = params(block, attn_shape=attn_shape)
     b, hq, Lq, d = q.shape
     if out is None:
         out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)
+    ostr = _out_strides(out, q)
     lse = torch.empty((b, hq, Lq), dtype=torch.float32, device=q.device) if want_lse else None
     if ws is None:
         ws = _ws(lib.basa_attn_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)), q.device)
     stride = 0 if row_cols is None else int(row_cols.shape[-1])
     _check(lib.basa_sparse_attn(C.byref(qd), C.byref(kd), C.byref(vd), _ptr(row_count), _ptr(row_cols),
-                                stride, _ptr(perm_q), _ptr(perm_k), C.byref(p), _ptr(out), _ptr(lse),
+                                stride, _ptr(perm_q), _ptr(perm_k), C.byref(p), _ptr(out), ostr, _ptr(lse),
                                 _ptr(ws), ws.numel(), _stream(q)))
     return (out, lse) if want_lse else out
 
@@ -280,12 +292,37 @@ def basa_dense_attn(q, k, v, block: int = 128, want_lse: bool = False, ws=None, 
     b, hq, Lq, d = q.shape
     if out is None:
         out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)
+    ostr = _out_strides(out, q)
     lse = torch.empty((b, hq, Lq), dtype=torch.float32, device=q.device) if want_lse else None
     if ws is None:
         ws = _ws(lib.basa_attn_workspace_size(C.byref(qd), C.byref(kd), C.byref(p)), q.device)
-    _check(lib.basa_dense_attn(C.byref(qd), C.byref(kd), C.byref(vd), C.byref(p), _ptr(out), _ptr(lse),
+    _check(lib.basa_dense_attn(C.byref(qd), C.byref(kd), C.byref(vd), C.byref(p), _ptr(out), ostr, _ptr(lse),
                                _ptr(ws), ws.numel(), _stream(q)))
     return (out, lse) if want_lse else out
+
+
+def ba_att(q, k, v, block: int = 128, sparsity: float = 0.5, beta: float = 1.0, sort: int = SORT_QK,
+           window: int = 0, mass_target: float = 0.0, min_keep: int = 0, segments=None, out=None):
+    """The whole operator (Alg. 1): basa_select, then basa_sparse_attn on its lists.  Returns (out, Selection)."""
+    sel = basa_select(q, k, block, sparsity, beta, sort, window, want_mask=False, want_mass=False,
+                      mass_target=mass_target, min_keep=min_keep, segments=segments)
+    o = basa_sparse_attn(q, k, v, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k, out=out)
+    return o, sel
+
+
+def ba_att_varlen(q, k, v, cu_seqlens, block: int = 128, sparsity: float = 0.5, **kw):
+    """Sequences of different lengths packed token-major: q [T, heads_q, d], k and v [T, heads_kv, d],
+    cu_seqlens the host list [0, t_1, ..., T] of sequence boundaries.  Every sequence is its own
+    problem (its own sort, block map and kappa) and runs as one pair of library calls on strided
+    views of the packed buffers, reading and writing them in place; the long sequences this method
+    is for each fill the device on their own.  Returns the packed output [T, heads_q, d]."""
+    out = torch.empty_like(q)
+    view = lambda x, a, b: x[a:b].permute(1, 0, 2).unsqueeze(0)          # [1, heads, L, d], no copy
+    for a, b in zip(cu_seqlens[:-1], cu_seqlens[1:]):
+        a, b = int(a), int(b)
+        if b > a:
+            ba_att(view(q, a, b), view(k, a, b), view(v, a, b), block, sparsity, out=view(out, a, b), **kw)
+    return out
 
 
 def basa_profile_enable(on: bool):

@@ -188,11 +188,20 @@ bool use_mfma(const basa_tensor* q) { return q->dtype == BASA_BF16; }   // d is 
 
 basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                         const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,
-                        const int32_t* perm_q, const int32_t* perm_k, int B, int variant, void* out, float* lse,
-                        void* ws, size_t ws_bytes, void* stream) {
+                        const int32_t* perm_q, const int32_t* perm_k, int B, int variant, void* out,
+                        const int64_t* out_strides, float* lse, void* ws, size_t ws_bytes, void* stream) {
   if (!out) { set_error("null output pointer"); return BASA_ERR_INVALID_ARG; }
   if (reinterpret_cast<uintptr_t>(out) % 16) { set_error("out must be 16-byte aligned"); return BASA_ERR_INVALID_ARG; }
   AttnArgs a;
+  a.out_sl = q->d; a.out_sh = (int64_t)q->L * q->d; a.out_sb = (int64_t)q->heads * q->L * q->d;
+  if (out_strides) {
+    const int64_t per16 = q->dtype == BASA_BF16 ? 8 : 4;
+    a.out_sb = out_strides[0]; a.out_sh = out_strides[1]; a.out_sl = out_strides[2];
+    if (a.out_sl < q->d || a.out_sl % per16 || a.out_sh % per16 || a.out_sb % per16 || a.out_sh < 0 || a.out_sb < 0) {
+      set_error("out_strides must be non-negative multiples of 16 bytes with the token stride >= d");
+      return BASA_ERR_INVALID_ARG;
+    }
+  }
   a.q = view_of(*q); a.k = view_of(*k); a.v = view_of(*v);
   a.row_count = row_count; a.row_cols = row_cols; a.cols_stride = cols_stride;
   a.perm_q = perm_q; a.perm_k = perm_k; a.B = B; a.out = out; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes;
@@ -329,24 +338,24 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
 basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                              const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,
                              const int32_t* perm_q, const int32_t* perm_k, const basa_params* p, void* out,
-                             float* lse, void* ws, size_t ws_bytes, void* stream) {
+                             const int64_t* out_strides, float* lse, void* ws, size_t ws_bytes, void* stream) {
   basa_status s;
   if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
   if (row_cols && !row_count) { set_error("row_cols given without row_count"); return BASA_ERR_INVALID_ARG; }
   if (row_cols && cols_stride < 1) { set_error("cols_stride must be >= 1"); return BASA_ERR_INVALID_ARG; }
   if (p->attn_shape < 0 || p->attn_shape > 2) { set_error("attn_shape must be 0, 1 or 2"); return BASA_ERR_INVALID_ARG; }
-  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, out, lse,
-                     ws, ws_bytes, stream);
+  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, out,
+                     out_strides, lse, ws, ws_bytes, stream);
 }
 
 basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
-                            const basa_params* p, void* out, float* lse, void* ws, size_t ws_bytes,
-                            void* stream) {
+                            const basa_params* p, void* out, const int64_t* out_strides, float* lse, void* ws,
+                            size_t ws_bytes, void* stream) {
   basa_status s;
   if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
-  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 1, out, lse, ws, ws_bytes, stream);
+  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 1, out, out_strides, lse, ws, ws_bytes, stream);
 }
 
 const char* basa_status_string(basa_status s) {

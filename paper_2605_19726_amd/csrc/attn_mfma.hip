@@ -152,6 +152,8 @@ struct MfmaArgs {
   __bf16* out; float* lse;
   int Nq, Nk, Lq, Lk, group, wgs_per_head, total_wgs;
   float scale_log2e;
+  int64_t out_sb, out_sh, out_sl;   // strides of out in elements
+  int heads_q;
   const int32_t* probe;      // nullable: {blocks in both lists, blocks in the lists} over sampled pairs
   int run_if_solo;           // with probe: this launch runs iff (lists overlap little) == run_if_solo
 };
@@ -243,6 +245,11 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
   }
 }
 
+__device__ __forceinline__ int64_t out_off(const MfmaArgs& a, int bhq, int row) {
+  const int b = bhq / a.heads_q, hh = bhq - b * a.heads_q;
+  return (int64_t)b * a.out_sb + (int64_t)hh * a.out_sh + (int64_t)row * a.out_sl;
+}
+
 // Dynamic LDS: [ring: kStages x 32 KB][seq: Nk words][wave_counts: kWaves words].
 // seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
 // this workgroup lists it).  While seq is being built the ring area holds the per-key-block
@@ -323,7 +330,7 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
     const int pos = gq * kB + (wave % WPG) * 32 + li;
     if (gq < a.Nq && pos < a.Lq) {
       const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-      uint4* op = reinterpret_cast<uint4*>(a.out + ((int64_t)bhq * a.Lq + orow) * D);
+      uint4* op = reinterpret_cast<uint4*>(a.out + out_off(a, bhq, orow));
       for (int i = 0; i < G::kChunksPerRow / 2; ++i) op[(G::kChunksPerRow / 2) * h + i] = make_uint4(0u, 0u, 0u, 0u);
       if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
     }
@@ -466,7 +473,7 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
   const int pos = gq * kB + (wave % WPG) * 32 + li;
   if (gq < a.Nq && pos < a.Lq) {
     const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-    __bf16* op = a.out + ((int64_t)bhq * a.Lq + orow) * D;
+    __bf16* op = a.out + out_off(a, bhq, orow);
 #pragma unroll
     for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
@@ -588,6 +595,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.row_count = a.row_count; m.row_cols = a.row_cols; m.cols_stride = a.cols_stride;
   m.perm_q = a.perm_q;
   m.out = reinterpret_cast<__bf16*>(a.out); m.lse = a.lse;
+  m.out_sb = a.out_sb; m.out_sh = a.out_sh; m.out_sl = a.out_sl; m.heads_q = a.q.heads;
   m.Nq = Nq; m.Nk = Nk; m.Lq = a.q.L; m.Lk = a.k.L;
   m.group = a.q.heads / a.k.heads;
   m.wgs_per_head = 0; m.total_wgs = 0;

@@ -114,12 +114,13 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
   if (!active) return;
   const float inv_l = l > 0.f ? 1.0f / l : 0.f;       // a row without any valid key block: zeros
   const int64_t orow = (int64_t)bhq * Lq + qrow;
+  const int64_t ooff = a.out_offset(bhq, qrow);
   if constexpr (kBf16) {
-    __bf16* o = reinterpret_cast<__bf16*>(a.out) + orow * kD;
+    __bf16* o = reinterpret_cast<__bf16*>(a.out) + ooff;
 #pragma unroll
     for (int t = 0; t < kD; ++t) o[t] = (__bf16)(acc[t] * inv_l);
   } else {
-    float4* o = reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + orow * kD);
+    float4* o = reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ooff);
 #pragma unroll
     for (int t = 0; t < kD; t += 4)
       o[t / 4] = make_float4(acc[t] * inv_l, acc[t + 1] * inv_l, acc[t + 2] * inv_l, acc[t + 3] * inv_l);

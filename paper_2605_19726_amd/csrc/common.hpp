@@ -105,7 +105,12 @@ struct AttnArgs {
   const int32_t* perm_q;      // [BHq][Lq] or null
   const int32_t* perm_k;      // [BHkv][Lk] or null
   int B;
-  void* out;                  // [BHq][Lq][d] contiguous, dtype of q
+  void* out;                  // [batch][heads_q][Lq][d], dtype of q, strides below (elements; d has stride 1)
+  int64_t out_sb, out_sh, out_sl;
+  __host__ __device__ inline int64_t out_offset(int bh, int64_t row) const {
+    const int b = bh / q.heads, h = bh - b * q.heads;
+    return (int64_t)b * out_sb + (int64_t)h * out_sh + row * out_sl;
+  }
   float* lse;                 // [BHq][Lq] or null
   void* ws;
   size_t ws_bytes;

@@ -103,20 +103,23 @@ def test_attention_argument_validation(lib):
     q, k, v = fake_tensor(), fake_tensor(), fake_tensor()
     p = bd.params(128)
     dummy = C.c_void_p(0x2000)
-    call = lambda q_, k_, v_, out=dummy, wsb=16: status_of(
+    strides = lambda *v_: (C.c_int64 * 3)(*v_)
+    call = lambda q_, k_, v_, out=dummy, wsb=16, ostr=None, p_=p: status_of(
         lib, lib.basa_sparse_attn, C.byref(q_), C.byref(k_), C.byref(v_), dummy, dummy, 4, None, None,
-        C.byref(p), out, None, dummy, wsb, None)
+        C.byref(p_), out, ostr, None, dummy, wsb, None)
     assert call(q, k, fake_tensor(L=128))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, v, out=None)[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, v, out=C.c_void_p(0x2004))[0] == "BASA_ERR_INVALID_ARG"            # misaligned
     assert call(q, k, v)[0] == "BASA_ERR_WORKSPACE"
     for bad in (-1, 3):
-        pb = bd.params(128, attn_shape=bad)
-        st = lib.basa_sparse_attn(C.byref(q), C.byref(k), C.byref(v), dummy, dummy, 4, None, None, C.byref(pb),
-                                  dummy, None, dummy, 1 << 40, None)
-        assert lib.basa_status_string(st) == b"BASA_ERR_INVALID_ARG"
-    st = lib.basa_dense_attn(C.byref(q), C.byref(k), C.byref(v), C.byref(p), dummy, None, dummy, 16, None)
+        assert call(q, k, v, wsb=1 << 40, p_=bd.params(128, attn_shape=bad))[0] == "BASA_ERR_INVALID_ARG"
+    # output strides: token-major is fine (and reaches the workspace check), the rest is refused
+    assert call(q, k, v, ostr=strides(256 * 2 * 128, 128, 2 * 128))[0] == "BASA_ERR_WORKSPACE"
+    assert call(q, k, v, ostr=strides(256 * 2 * 128, 128, 64))[0] == "BASA_ERR_INVALID_ARG"      # token stride < d
+    assert call(q, k, v, ostr=strides(256 * 2 * 128, 132, 2 * 128))[0] == "BASA_ERR_INVALID_ARG"  # not 16-byte
+    assert call(q, k, v, ostr=strides(-8, 128, 2 * 128))[0] == "BASA_ERR_INVALID_ARG"
+    st = lib.basa_dense_attn(C.byref(q), C.byref(k), C.byref(v), C.byref(p), dummy, None, None, dummy, 16, None)
     assert lib.basa_status_string(st) == b"BASA_ERR_WORKSPACE"
-
 
 def test_workspace_sizes(lib):
     q, k = fake_tensor(heads=4, L=1000), fake_tensor(heads=2, L=1000)

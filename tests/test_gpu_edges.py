@@ -365,3 +365,49 @@ def test_workgroup_shape_chosen_on_the_device(kind):
     for g in (0, 1, n // 2, n - 1):
         rows, O_ref, _ = o.sparse_attention_block(q, k, v, ident, ident, g, cols[h, g, :cnt[h, g]], B)
         check_output(np64(outs[2][0][0, h])[rows], O_ref, True, f"{kind} block {g}")
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64)])
+def test_token_major_output_through_out_strides(dtype, d):
+    """out as a strided view: a token-major [2, L, H, d] buffer (what the next projection reads)
+    with two extra slots per token that must stay untouched."""
+    Bt, H, L, block = 2, 4, 500, 64
+    Q, K, V = (_randn((Bt, H, L, d), 950 + i, dtype) for i in range(3))
+    sel = bd.basa_select(Q, K, block, 0.5)
+    want, lse_want = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k, want_lse=True)
+    buf = torch.full((Bt, L, H + 2, d), 7.0, dtype=dtype, device=DEV)
+    view = buf[:, :, 1:H + 1].permute(0, 2, 1, 3)                              # [Bt, H, L, d]
+    got, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k, want_lse=True,
+                                   out=view)
+    torch.cuda.synchronize()
+    assert got.data_ptr() == view.data_ptr()
+    assert torch.equal(view, want) and torch.equal(lse, lse_want)
+    assert (buf[:, :, 0] == 7).all() and (buf[:, :, H + 1] == 7).all()
+    dense_want = bd.basa_dense_attn(Q, K, V, block)
+    buf.fill_(7.0)
+    bd.basa_dense_attn(Q, K, V, block, out=view)
+    assert torch.equal(view, dense_want) and (buf[:, :, 0] == 7).all() and (buf[:, :, H + 1] == 7).all()
+    with pytest.raises(ValueError):
+        bd.basa_dense_attn(Q, K, V, block, out=buf[:, :, 1:H + 1].permute(0, 2, 3, 1))   # d not innermost
+
+
+def test_variable_length_batch_packed_token_major():
+    """Three sequences of different lengths packed token-major, each its own problem."""
+    Hq, Hk, d, block = 4, 2, 128, 64
+    lens = [700, 1, 1333]
+    cu = [0, 700, 701, 2034]
+    T = cu[-1]
+    g = torch.Generator().manual_seed(4242)
+    q = torch.randn((T, Hq, d), generator=g).to(torch.bfloat16).to(DEV)
+    k = torch.randn((T, Hk, d), generator=g).to(torch.bfloat16).to(DEV)
+    v = torch.randn((T, Hk, d), generator=g).to(torch.bfloat16).to(DEV)
+    out = bd.ba_att_varlen(q, k, v, cu, block, 0.5)
+    torch.cuda.synchronize()
+    assert out.shape == q.shape
+    for a, b in zip(cu[:-1], cu[1:]):
+        for h in range(Hq):
+            O_ref, _ = o.ba_att(np64(q[a:b, h]), np64(k[a:b, h // 2]), np64(v[a:b, h // 2]), block, 0.5)
+            check_output(np64(out[a:b, h]), O_ref, True, f"sequence [{a},{b}) head {h}")
+    # an empty sequence in the list is skipped
+    out2 = bd.ba_att_varlen(q, k, v, [0, 700, 700, 701, 2034], block, 0.5)
+    assert torch.equal(out, out2)
