@@ -161,19 +161,23 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
   const bool one_segment = sl.n <= 1 || start + n <= sl.bound[seg_lo + 1];
 
   // ---- phase 1: keys of tokens start .. start+n-1 into buf
+  // Every load is unconditional, its row clamped into the tile (a row past the end reads the
+  // tile's last row, whose key is never written; the pass after the last reads the last again,
+  // from cache): loads inside branches make the compiler wait for ALL outstanding loads at the
+  // join, the prefetch of the next pass included, and the double buffering is lost.
+  const int passes = (n + kRowsPerPass - 1) / kRowsPerPass;
   auto load_pass = [&](int pass, uint4 (&raw)[kIters]) {
+    const int p = min(pass, passes - 1);
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
-      const int loc = pass * kRowsPerPass + it * kRowsPerIter + rig;
-      raw[it] = make_uint4(0u, 0u, 0u, 0u);
-      if (loc < n) raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)(start + loc) * x.stride_l * kElem)[sub];
+      const int loc = min(p * kRowsPerPass + it * kRowsPerIter + rig, n - 1);
+      raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)(start + loc) * x.stride_l * kElem)[sub];
     }
   };
-  const int passes = (n + kRowsPerPass - 1) / kRowsPerPass;
   uint4 cur[kIters], nxt[kIters];
   load_pass(0, cur);
   for (int pass = 0; pass < passes; ++pass) {
-    if (pass + 1 < passes) load_pass(pass + 1, nxt);
+    load_pass(pass + 1, nxt);
     // per-lane partial sums of the kIters rows this lane contributes to
     double acc[kIters];
 #pragma unroll

@@ -1,5 +1,5 @@
 // Block pooling (Sec. 3.1 mean pooling; Sec. 3.4 per-dimension variances; Alg. 1
-// steps 3-4).  One workgroup gathers the B rows of one block of the ordered sequence
+// steps 3-4).  A workgroup gathers the B rows of a block of the ordered sequence
 // x[perm], keeps them in registers, and reduces twice: sum -> mean, then centred
 // squares -> population variance (two-pass, so no cancellation).
 //
@@ -22,100 +22,210 @@ struct StatsJob {
   int feat_is_query;
 };
 
+constexpr int kGroup = 8;      // consecutive blocks per workgroup
+
+// Element e of a 16-byte chunk as a float.
+template <bool kBf16>
+__device__ __forceinline__ float chunk_elem(const uint4& r, int e) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+  if constexpr (kBf16) return __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+  else return __uint_as_float(w[e]);
+}
+
+// A workgroup pools kGroup consecutive blocks of the ordered sequence, one after the other.  A row
+// is 16-byte chunks spread over LPR adjacent lanes; a thread holds chunk `sub` of ITERS rows.  The
+// rows of block b+1 (and the permutation entries of block b+2) are requested before block b is
+// reduced, so the workgroup has loads in flight all the time: the gather is bound by the number of
+// bytes in flight, and a kernel that loads, reduces and retires one block at a time has none in
+// flight for half of its life.  Sums over the rows held by a wave are taken with lane exchanges,
+// over the four waves through LDS.  The features of the kGroup blocks are collected in LDS and
+// written at the end as 128-byte runs (in the [k/4][g][k%4] layout one block's features are 16-byte
+// pieces 16 KB apart, which cost a fifth of the kernel when every block wrote its own).
 template <bool kBf16, int kD, int kB>
 __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob j1, int BH0, float beta) {
   constexpr int kElem = kBf16 ? 2 : 4;
   constexpr int LPR = kD * kElem / 16;       // lanes per row
   constexpr int RPI = 256 / LPR;             // rows per iteration
   constexpr int ITERS = kB / RPI;
-  constexpr int E = Chunk16<kBf16>::kElems;
-  static_assert(ITERS >= 1, "block too small for this tiling");
-  __shared__ float red[RPI][kD];
-  __shared__ float mean_s[kD];
+  constexpr int E = kBf16 ? 8 : 4;           // elements per chunk
+  static_assert(ITERS >= 1 && LPR <= 64, "block too small for this tiling");
+  __shared__ float red[2][2][4][kD];         // [block parity][mean | centred squares][wave][column]
+  __shared__ float4 stage[3 * kD / 4][kGroup];
 
   const bool second = (int)blockIdx.y >= BH0;
   const StatsJob& job = second ? j1 : j0;
   const TensorView& x = job.x;
-  const int32_t* perm = job.perm;
   float* mean_out = job.mean_out;
   float* var_out = job.var_out;
   float* feat_out = job.feat_out;
   const int feat_is_query = job.feat_is_query;
-  const int bh = second ? blockIdx.y - BH0 : blockIdx.y, g = blockIdx.x;
+  const int bh = second ? blockIdx.y - BH0 : blockIdx.y;
   const int L = x.L;
   const int N = (L + kB - 1) / kB;
+  const int g0 = blockIdx.x * kGroup;
+  const int nb = min(kGroup, N - g0);        // blocks of this workgroup that exist (>= 1 by the grid)
   const int sub = threadIdx.x % LPR, rig = threadIdx.x / LPR;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * kElem;
-  const int32_t* pm = perm ? perm + (int64_t)bh * L : nullptr;
-  const int n_valid = min(kB, L - g * kB);
+  const int32_t* pm = job.perm ? job.perm + (int64_t)bh * L : nullptr;
+  const int64_t row_bytes = x.stride_l * kElem;
 
-  Chunk16<kBf16> c[ITERS];
+  // Token rows of block b for this thread.  Every load below is unconditional, with its index
+  // clamped into the sequence (a block past the workgroup's last one reads the last one again,
+  // from cache; a position past L reads row L-1 and is masked out where it is used): a load inside
+  // a divergent branch is followed by a full wait, which serialises the eight loads of a thread.
+  auto load_rows = [&](int b, int (&rows)[ITERS]) {             // entries as stored, checked at use
+    const int p0 = (g0 + min(b, nb - 1)) * kB + rig;
+    if (pm) {
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    int pos = g * kB + it * RPI + rig;
-    if (pos < L) {
-      const int row = perm_at(pm, 0, pos, L);
-      c[it].load(base + (int64_t)row * x.stride_l * kElem, sub);
+      for (int it = 0; it < ITERS; ++it) rows[it] = pm[min(p0 + it * RPI, L - 1)];
     } else {
-      c[it].zero();
+#pragma unroll
+      for (int it = 0; it < ITERS; ++it) rows[it] = min(p0 + it * RPI, L - 1);
     }
-  }
-  float s[E];
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    float a = 0.f;
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) a += c[it].v[e];
-    s[e] = a;
-  }
-#pragma unroll
-  for (int e = 0; e < E; ++e) red[rig][sub * E + e] = s[e];
-  __syncthreads();
-  const float inv_n = 1.0f / (float)n_valid;
-  float mean_c = 0.f;
-  if (threadIdx.x < kD) {
-    float a = 0.f;
-#pragma unroll
-    for (int r = 0; r < RPI; ++r) a += red[r][threadIdx.x];
-    mean_c = a * inv_n;
-    mean_s[threadIdx.x] = mean_c;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const float m = mean_s[sub * E + e];
-    float a = 0.f;
+  };
+  auto load_chunks = [&](int b, const int (&rows)[ITERS], uint4 (&raw)[ITERS]) {
+    const int p0 = (g0 + min(b, nb - 1)) * kB + rig;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-      int pos = g * kB + it * RPI + rig;
-      float dv = c[it].v[e] - m;
-      a += (pos < L) ? dv * dv : 0.f;
+      // a malformed permutation entry falls back to the position itself
+      const int row = (unsigned)rows[it] < (unsigned)L ? rows[it] : min(p0 + it * RPI, L - 1);
+      raw[it] = reinterpret_cast<const uint4*>(base + row * row_bytes)[sub];
     }
-    red[rig][sub * E + e] = a;
-  }
-  __syncthreads();
-  if (threadIdx.x < kD) {
-    float a = 0.f;
+  };
+
+  // Order of issue matters: loads return in order, so the permutation entries of block b+2 are
+  // requested BEFORE the rows of block b+1; waiting for them later (to form the addresses of
+  // block b+2) then leaves the rows of block b+1 in flight instead of draining the queue.
+  int rows[ITERS], rows_after[ITERS];
+  uint4 cur[ITERS], nxt[ITERS];
+  load_rows(0, rows);
+  load_chunks(0, rows, cur);
+  load_rows(1, rows);
+  for (int b = 0; b < nb; ++b) {
+    load_rows(b + 2, rows_after);
+    load_chunks(b + 1, rows, nxt);
+    const int g = g0 + b;
+    const int n_valid = min(kB, L - g * kB);
+    const float inv_n = 1.0f / (float)n_valid;
+
+    // ---- per wave: mean and centred squares of the rows it holds (two passes over registers,
+    // lane exchanges only, so the four waves run through both without meeting)
+    constexpr int RPW = 64 / LPR;            // rows of one iteration held by a wave
+    int n_w = 0;                             // valid rows of this wave's share of the block
 #pragma unroll
-    for (int r = 0; r < RPI; ++r) a += red[r][threadIdx.x];
-    const float var_c = a * inv_n;
-    const int64_t o = ((int64_t)bh * N + g) * kD + threadIdx.x;
-    if (mean_out) mean_out[o] = mean_c;
-    if (var_out) var_out[o] = var_c;
-    if (feat_out) {
-      // feature k of block g lives at [k / 4][g][k % 4]: the score kernel reads 16-byte groups of
-      // 32 consecutive blocks with one coalesced load
-      float* f = feat_out + (int64_t)bh * N * (3 * kD) + (int64_t)g * 4 + (threadIdx.x & 3);
-      const int64_t c0 = (int64_t)(threadIdx.x >> 2) * N * 4, third = (int64_t)(kD / 4) * N * 4;
-      if (feat_is_query) {
-        f[c0] = mean_c * (1.0f / sqrtf((float)kD));
-        f[third + c0] = beta * var_c * (1.0f / (float)kD);
-        f[2 * third + c0] = beta * (mean_c * mean_c) * (1.0f / (float)kD);
+    for (int it = 0; it < ITERS; ++it) n_w += max(0, min(RPW, n_valid - it * RPI - wave * RPW));
+    const float inv_nw = n_w > 0 ? 1.0f / (float)n_w : 0.f;
+    float mean_w[E], m2_w[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      float a = 0.f;
+      if (n_valid == kB) {                     // every block but a ragged last one
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) a += chunk_elem<kBf16>(cur[it], e);
       } else {
-        f[c0] = mean_c;
-        f[third + c0] = mean_c * mean_c + var_c;
-        f[2 * third + c0] = var_c;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+          const int pos = g * kB + it * RPI + rig;
+          a += (pos < L) ? chunk_elem<kBf16>(cur[it], e) : 0.f;
+        }
       }
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) a += __shfl_xor(a, off);
+      mean_w[e] = a * inv_nw;
+    }
+    // (the raw chunks are made opaque so that the floats of the first pass are converted again,
+    // two integer ops each, rather than kept: 64 registers that the loads in flight need more)
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it)
+      asm volatile("" : "+v"(cur[it].x), "+v"(cur[it].y), "+v"(cur[it].z), "+v"(cur[it].w));
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const float m = mean_w[e];
+      float a = 0.f;
+      if (n_valid == kB) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+          const float dv = chunk_elem<kBf16>(cur[it], e) - m;
+          a = fmaf(dv, dv, a);
+        }
+      } else {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+          const int pos = g * kB + it * RPI + rig;
+          const float dv = chunk_elem<kBf16>(cur[it], e) - m;
+          a += (pos < L) ? dv * dv : 0.f;
+        }
+      }
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) a += __shfl_xor(a, off);
+      m2_w[e] = a;
+    }
+    float (*rd)[4][kD] = red[b & 1];         // [0] wave means, [1] wave sums of centred squares
+    if (lane < LPR) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        rd[0][wave][sub * E + e] = mean_w[e];
+        rd[1][wave][sub * E + e] = m2_w[e];
+      }
+    }
+    __syncthreads();
+    // the other half of red is written before the next barrier, this half after it: every read
+    // below is over by then
+    if (threadIdx.x < kD) {
+      // ---- the four waves' shares combined exactly: mean = sum n_w mean_w / n,
+      //      M2 = sum M2_w + sum n_w (mean_w - mean)^2   (no cancellation either)
+      const int c = threadIdx.x;
+      float nw[4], mw[4];
+      float acc = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        int cnt = 0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) cnt += max(0, min(RPW, n_valid - it * RPI - w * RPW));
+        nw[w] = (float)cnt;
+        mw[w] = rd[0][w][c];
+        acc = fmaf(nw[w], mw[w], acc);
+      }
+      const float mean_c = acc * inv_n;
+      float m2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float dm = mw[w] - mean_c;
+        m2 += rd[1][w][c] + nw[w] * dm * dm;
+      }
+      const float var_c = m2 * inv_n;
+      const int64_t o = ((int64_t)bh * N + g) * kD + c;
+      if (mean_out) mean_out[o] = mean_c;
+      if (var_out) var_out[o] = var_c;
+      if (feat_out) {
+        float* f = reinterpret_cast<float*>(&stage[c >> 2][b]) + (c & 3);
+        constexpr int third = (kD / 4) * kGroup * 4;            // floats between the three parts in stage
+        if (feat_is_query) {
+          f[0] = mean_c * (1.0f / sqrtf((float)kD));
+          f[third] = beta * var_c * (1.0f / (float)kD);
+          f[2 * third] = beta * (mean_c * mean_c) * (1.0f / (float)kD);
+        } else {
+          f[0] = mean_c;
+          f[third] = mean_c * mean_c + var_c;
+          f[2 * third] = var_c;
+        }
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      cur[it] = nxt[it];
+      rows[it] = rows_after[it];
+    }
+  }
+  if (feat_out) {
+    // feature k of block g lives at [k / 4][g][k % 4]: the score kernel reads 16-byte groups of
+    // 32 consecutive blocks with one coalesced load
+    __syncthreads();
+    float4* f4 = reinterpret_cast<float4*>(feat_out + (int64_t)bh * N * (3 * kD));
+    for (int i = threadIdx.x; i < (3 * kD / 4) * kGroup; i += 256) {
+      const int k4 = i / kGroup, gi = i % kGroup;
+      if (gi < nb) f4[(int64_t)k4 * N + g0 + gi] = stage[k4][gi];
     }
   }
 }
@@ -128,7 +238,7 @@ static basa_status block_stats_impl(const StatsJob& j0, const StatsJob* j1, int 
   const int BH1 = j1 ? j1->x.batch * j1->x.heads : 0;
   const int N = ceil_div(x.L, B);
   if (BH0 + BH1 == 0 || N == 0) return BASA_OK;
-  dim3 grid(N, BH0 + BH1);
+  dim3 grid(ceil_div(N, kGroup), BH0 + BH1);
   ProfScope prof(K_STATS, st);
   const bool bf = x.dtype == BASA_BF16;
   const StatsJob& jb = j1 ? *j1 : j0;
