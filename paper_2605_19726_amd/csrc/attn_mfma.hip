@@ -82,15 +82,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const in
   const int32_t* pm = perm ? perm + (int64_t)bh * x.L : nullptr;
   const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * 2;
   uint4 v[ITERS];
-#pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int pos = blockIdx.x * 64 + it * RPI + rig;
-    v[it] = make_uint4(0, 0, 0, 0);
-    if (pos < x.L) {
-      const int row = perm_at(pm, 0, pos, x.L);
-      v[it] = reinterpret_cast<const uint4*>(base + (int64_t)row * x.stride_l * 2)[sub];
-    }
-  }
+  gather_chunks<ITERS>(v, pm, base, x.L, (int64_t)x.stride_l * 2, blockIdx.x * 64 + rig, RPI, sub);
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int pos = blockIdx.x * 64 + it * RPI + rig;
@@ -110,17 +102,10 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(TensorView v, const int3
   const int sub = threadIdx.x % CPR, rig = threadIdx.x / CPR;
   const int32_t* pm = perm ? perm + (int64_t)bh * v.L : nullptr;
   const char* base = reinterpret_cast<const char*>(v.ptr) + v.head_offset(bh) * 2;
+  uint4 val[ITERS];
+  gather_chunks<ITERS>(val, pm, base, v.L, (int64_t)v.stride_l * 2, tile * kTileKeys + rig, RPI, sub);
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int kk = it * RPI + rig;
-    const int pos = tile * kTileKeys + kk;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (pos < v.L) {
-      const int row = perm_at(pm, 0, pos, v.L);
-      val = reinterpret_cast<const uint4*>(base + (int64_t)row * v.stride_l * 2)[sub];
-    }
-    *reinterpret_cast<uint4*>(&rows[kk][sub * 8]) = val;
-  }
+  for (int it = 0; it < ITERS; ++it) *reinterpret_cast<uint4*>(&rows[it * RPI + rig][sub * 8]) = val[it];
   __syncthreads();
   // 8 D output chunks of 8 slots; thread handles chunk (d = id/8, s8 = id%8):
   // 16-key group g16 = s8/2, lane half hh = s8%2, slot e <-> key 16 g16 + 8(e/4) + 4 hh + e%4

@@ -152,13 +152,39 @@ __device__ __forceinline__ int perm_at(const int32_t* __restrict__ pm, int64_t o
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);
 }
-// Load 16 bytes of a row as floats: 8 bf16 or 4 f32 values.
+// Chunk `sub` of the rows at sorted positions pos0, pos0 + step, ... (zeros past L).  All loads are
+// unconditional with clamped indices and issued back to back (first the permutation entries, then
+// the rows): a load inside a divergent branch is followed by a full wait, which serialises them.
+template <int ITERS>
+__device__ __forceinline__ void gather_chunks(uint4 (&v)[ITERS], const int32_t* pm, const char* base, int L,
+                                              int64_t row_bytes, int pos0, int step, int sub) {
+  int row[ITERS];
+  if (pm) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) row[it] = pm[min(pos0 + it * step, L - 1)];
+  } else {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) row[it] = min(pos0 + it * step, L - 1);
+  }
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int r = (unsigned)row[it] < (unsigned)L ? row[it] : min(pos0 + it * step, L - 1);   // malformed entry
+    v[it] = reinterpret_cast<const uint4*>(base + r * row_bytes)[sub];
+  }
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it)
+    if (pos0 + it * step >= L) v[it] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// 16 bytes of a row as floats: 8 bf16 or 4 f32 values.
 template <bool kBf16>
 struct Chunk16 {
   static constexpr int kElems = kBf16 ? 8 : 4;
   float v[kElems];
   __device__ __forceinline__ void load(const void* row_base, int chunk) {
-    uint4 raw = reinterpret_cast<const uint4*>(row_base)[chunk];
+    set(reinterpret_cast<const uint4*>(row_base)[chunk]);
+  }
+  __device__ __forceinline__ void set(const uint4& raw) {
     if constexpr (kBf16) {
       uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll

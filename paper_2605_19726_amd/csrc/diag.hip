@@ -191,16 +191,13 @@ __global__ __launch_bounds__(256) void diag_gather_rows_kernel(TensorView x, con
   const int sub = threadIdx.x & 15, rig = threadIdx.x >> 4;
   const int32_t* pm = perm ? perm + (int64_t)bh * x.L : nullptr;
   const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * 2;
+  uint4 v[4];
+  gather_chunks<4>(v, pm, base, x.L, (int64_t)x.stride_l * 2, blockIdx.x * 64 + rig, 16, sub);
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int pos = blockIdx.x * 64 + it * 16 + rig;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (pos < x.L) {
-      const int row = perm_at(pm, 0, pos, x.L);
-      v = reinterpret_cast<const uint4*>(base + (int64_t)row * x.stride_l * 2)[sub];
-    }
     const int cpos = swizzle ? (sub ^ (pos & 15)) : sub;
-    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * 16 + cpos] = v;
+    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * 16 + cpos] = v[it];
   }
 }
 
@@ -228,11 +225,11 @@ __global__ __launch_bounds__(256) void block_radius_kernel(TensorView x, const i
   const int n_valid = min(kB, L - g * kB);
 
   Chunk16<kBf16> c[ITERS];
+  {
+    uint4 raw[ITERS];
+    gather_chunks<ITERS>(raw, pm, base, L, (int64_t)x.stride_l * kElem, g * kB + rig, RPI, sub);
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int pos = g * kB + it * RPI + rig;
-    if (pos < L) c[it].load(base + (int64_t)perm_at(pm, 0, pos, L) * x.stride_l * kElem, sub);
-    else c[it].zero();
+    for (int it = 0; it < ITERS; ++it) c[it].set(raw[it]);       // rows past L are zeros
   }
 #pragma unroll
   for (int e = 0; e < E; ++e) {

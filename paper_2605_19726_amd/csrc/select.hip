@@ -125,17 +125,16 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   float e[MAXI];                        // logits first, then exp(l - max)
   uint32_t u[MAXI];
   float mx = -INFINITY;
+  // all loads first, unconditional with the index clamped into the row: a load inside a divergent
+  // branch is followed by a full wait, which would serialise the MAXI loads of a lane
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) e[i] = src[min(i * 64 + lane, Nk - 1)];
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
-    const int idx = i * 64 + lane;
-    if (idx < Nk) {
-      e[i] = src[idx] + 0.0f;          // -0 -> +0 so that equal values have equal images
-      u[i] = ordered_bits(e[i]);
-      mx = fmaxf(mx, e[i]);
-    } else {
-      e[i] = -INFINITY;
-      u[i] = 0u;                        // below the image of every float
-    }
+    const bool in_row = i * 64 + lane < Nk;
+    e[i] = in_row ? e[i] + 0.0f : -INFINITY;        // -0 -> +0 so that equal values have equal images
+    u[i] = in_row ? ordered_bits(e[i]) : 0u;        // 0 is below the image of every float
+    mx = fmaxf(mx, e[i]);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
