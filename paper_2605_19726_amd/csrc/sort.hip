@@ -293,11 +293,24 @@ __global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t
   const int as = split[0], ae = split[1];
   const int bs = diag0 - as, be = diag1 - ae;
   const int ca = ae - as, cb = be - bs;          // ca + cb == diag1 - diag0
-  for (int i = threadIdx.x; i < ca; i += kSortThreads) buf[i] = A[as + i];
-  for (int i = threadIdx.x; i < cb; i += kSortThreads) buf[ca + i] = Bv[bs + i];
+  const int n = ca + cb;
+  {
+    // the chunk's share of the two runs, side by side in LDS; the kMergeItems loads of a thread
+    // are unconditional (index clamped into the chunk, n >= 1) so that they are in flight together
+    uint64_t w[kMergeItems];
+#pragma unroll
+    for (int e = 0; e < kMergeItems; ++e) {
+      const int i = min(e * kSortThreads + (int)threadIdx.x, n - 1);
+      w[e] = i < ca ? A[as + i] : Bv[bs + i - ca];
+    }
+#pragma unroll
+    for (int e = 0; e < kMergeItems; ++e) {
+      const int i = e * kSortThreads + threadIdx.x;
+      if (i < n) buf[i] = w[e];
+    }
+  }
   __syncthreads();
 
-  const int n = ca + cb;
   const int d0 = min(threadIdx.x * kMergeItems, n);
   const int d1 = min(d0 + kMergeItems, n);
   int ia = merge_path(buf, ca, buf + ca, cb, d0);
