@@ -493,33 +493,40 @@ basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
   return BASA_OK;
 }
 
-// How much the lists of neighbouring query blocks (2g, 2g+1) have in common, on every 4th pair:
-// probe[0] += blocks in both lists, probe[1] += blocks in the two lists.  One wave per pair; a
-// lane looks its entries of the first list up in the second (both ascending) by bisection.
+// How much the lists of neighbouring query blocks (2g, 2g+1) have in common, on every 8th pair:
+// probe[0] += blocks in both lists, probe[1] += blocks in the two lists.  One wave per pair: the
+// first list becomes a bitmap in LDS, the entries of the second are looked up in it.
+constexpr int kProbeStride = 8, kProbeMaxBlocks = 8192;
 __global__ __launch_bounds__(256) void list_overlap_kernel(const int32_t* __restrict__ row_count,
                                                            const int32_t* __restrict__ row_cols, int cols_stride,
-                                                           int Nq, int pairs_total, int32_t* __restrict__ probe) {
-  const int pair = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 4, lane = threadIdx.x & 63;
-  if (pair >= pairs_total) return;
+                                                           int Nq, int Nk, int pairs_total, int32_t* __restrict__ probe) {
+  __shared__ uint32_t bits[4][kProbeMaxBlocks / 32];
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int pair = (blockIdx.x * 4 + wv) * kProbeStride;
+  const bool active = pair < pairs_total;               // no early exit: every wave meets the barriers
   const int pairs_per_head = Nq / 2;
-  const int bh = pair / pairs_per_head, g = (pair - bh * pairs_per_head) * 2;
+  const int bh = active ? pair / pairs_per_head : 0, g = active ? (pair - bh * pairs_per_head) * 2 : 0;
   const int64_t r0 = (int64_t)bh * Nq + g, r1 = r0 + 1;
-  const int na = max(0, min(row_count[r0], cols_stride)), nb = max(0, min(row_count[r1], cols_stride));
+  const int na = active ? max(0, min(row_count[r0], cols_stride)) : 0;
+  const int nb = active ? max(0, min(row_count[r1], cols_stride)) : 0;
   const int32_t* A = row_cols + r0 * cols_stride;
   const int32_t* Bv = row_cols + r1 * cols_stride;
-  int common = 0;
+  const unsigned limit = (unsigned)min(Nk, kProbeMaxBlocks);
+  for (int w = lane; w < kProbeMaxBlocks / 32; w += 64) bits[wv][w] = 0u;
+  __syncthreads();
   for (int i = lane; i < na; i += 64) {
-    const int v = A[i];
-    int lo = 0, hi = nb;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (Bv[mid] < v) lo = mid + 1; else hi = mid;
-    }
-    common += (lo < nb && Bv[lo] == v) ? 1 : 0;
+    const unsigned v = (unsigned)A[i];
+    if (v < limit) atomicOr(&bits[wv][v >> 5], 1u << (v & 31));
+  }
+  __syncthreads();
+  int common = 0;
+  for (int i = lane; i < nb; i += 64) {
+    const unsigned v = (unsigned)Bv[i];
+    if (v < limit) common += (bits[wv][v >> 5] >> (v & 31)) & 1u;
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) common += __shfl_xor(common, off);
-  if (lane == 0) {
+  if (active && lane == 0) {
     atomicAdd(&probe[0], common);
     atomicAdd(&probe[1], na + nb);
   }
@@ -596,8 +603,8 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
     const int pairs_total = BHq * (Nq / 2);
     hipLaunchKernelGGL(zero_probe_kernel, dim3(1), dim3(64), 0, st, probe);
     BASA_HIP_CHECK_LAUNCH("zero_probe_kernel");
-    hipLaunchKernelGGL(list_overlap_kernel, dim3(ceil_div(ceil_div(pairs_total, 4), 4)), dim3(256), 0, st, a.row_count,
-                       a.row_cols, a.cols_stride, Nq, pairs_total, probe);
+    hipLaunchKernelGGL(list_overlap_kernel, dim3(ceil_div(ceil_div(pairs_total, kProbeStride), 4)), dim3(256), 0, st,
+                       a.row_count, a.row_cols, a.cols_stride, Nq, Nk, pairs_total, probe);
     BASA_HIP_CHECK_LAUNCH("list_overlap_kernel");
     m.probe = probe;
   }
