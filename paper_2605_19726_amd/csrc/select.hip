@@ -3,10 +3,9 @@
 //
 // Scores: with the per-block features written by the pooling kernel the logit l' of a
 // block pair is a dot product, so the N_q x N_k map of a head is a small fp32 GEMM.
-// It runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32); each wave owns a 64x64
-// output tile and streams the features of its 128 blocks straight from L2 into registers
-// (the features are stored four to a group, groups of consecutive blocks adjacent, so that
-// every load of a half-wave is one contiguous 512-byte run).
+// It runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), the features staged through
+// LDS (they are stored four to a group, groups of consecutive blocks adjacent, so that every
+// load of a wave is one contiguous run).
 //
 // Selection: one wave per row of the map.  The kappa-th largest logit is found by a
 // 32-step bisection on an order-preserving integer image of the floats (ballot +
@@ -19,77 +18,123 @@ namespace basa {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
 // ---------------------------------------------------------------------------------
 // scores[bhq][gq][gk] = sum_k featQ[bhq][gq][k] * featK[bhq/group][gk][k], k < K
 // MFMA 32x32x2 operand roles: A[i][kk] lives in lane (i, kk), kk = lane/32; the k range
 // is split in halves, lanes 0-31 walk k in [0, K/2), lanes 32-63 walk [K/2, K).
+//
+// A workgroup of four waves owns a 128 x 256 tile of the map, a wave 64 x 128 of it (eight 32x32
+// accumulators).  The features of the tile's 128 + 256 blocks travel through LDS in stages of 16
+// k per half (48 KB, double buffered, filled with direct-to-LDS loads one stage ahead), so that
+// every feature is fetched once per workgroup: with each wave streaming its own operands from L2
+// the kernel was bound by L2 bandwidth (16 bytes per CU cycle), not by the matrix cores.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void block_scores_kernel(const float* __restrict__ featQ,
-                                                           const float* __restrict__ featK,
-                                                           float* __restrict__ scores, int group,
-                                                           int Nq, int Nk, int K, int S) {
+constexpr int kTQ = 128, kTK = 256;       // tile of the map per workgroup
+constexpr int kKS = 2;                    // feature groups (of 4) per half of the k range per stage
+constexpr int kQStage = 2 * kKS * kTQ;    // float4 per stage: [half][group][block]
+constexpr int kKStage = 2 * kKS * kTK;
+constexpr int kStage = kQStage + kKStage;
+constexpr int kScoresLdsBytes = 2 * kStage * 16;
+constexpr int kChunks = kStage / 64;      // direct-to-LDS loads of one wave-width (64 x 16 B) per stage
+
+__global__ __launch_bounds__(256, 2) void block_scores_kernel(const float* __restrict__ featQ,
+                                                              const float* __restrict__ featK,
+                                                              float* __restrict__ scores, int group,
+                                                              int Nq, int Nk, int K, int S) {
+  extern __shared__ __attribute__((aligned(16))) float4 stage_buf[];
   // consecutive workgroup ids go round-robin over the 8 XCDs: hand each XCD a contiguous range
   // of (head, tile) so that a head's features are pulled into one L2 only
-  const int total = gridDim.x, tiles_x = (Nk + 127) >> 7, tiles_y = (Nq + 127) >> 7;
+  const int total = gridDim.x, tiles_x = (Nk + kTK - 1) / kTK, tiles_y = (Nq + kTQ - 1) / kTQ;
   int logical = blockIdx.x;
   if ((total & 7) == 0) logical = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
   const int bhq = logical / (tiles_x * tiles_y);
   const int rem = logical - bhq * (tiles_x * tiles_y);
   const int ty = rem / tiles_x, tx = rem - ty * tiles_x;
   const int bhk = bhq / group;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int li = lane & 31, h = lane >> 5;
-  const int row0 = ty * 128 + (wave >> 1) * 64;
-  const int col0 = tx * 128 + (wave & 1) * 64;
-  if (row0 >= Nq || col0 >= Nk) return;
+  const int row_base = ty * kTQ, col_base = tx * kTK;
+  const int wq = wave >> 1, wk = wave & 1;       // this wave: rows wq*64.., columns wk*128..
 
-  // features are stored [K/4][N][4]: lane (li, h) reads the 16-byte group of its block, lanes of
-  // a half-wave read consecutive blocks (512 contiguous bytes)
+  // features are stored [K/4][N][4] floats: one 16-byte group per block, blocks adjacent
   const int half = K >> 1;
+  const int n_stages = half / (4 * kKS);
   const int64_t gq = (int64_t)Nq * 4, gk = (int64_t)Nk * 4;      // floats per group of 4 features
-  const float* a0 = featQ + (int64_t)bhq * Nq * S + (int64_t)(h * half >> 2) * gq + (int64_t)min(row0 + li, Nq - 1) * 4;
-  const float* a1 = featQ + (int64_t)bhq * Nq * S + (int64_t)(h * half >> 2) * gq + (int64_t)min(row0 + 32 + li, Nq - 1) * 4;
-  const float* b0 = featK + (int64_t)bhk * Nk * S + (int64_t)(h * half >> 2) * gk + (int64_t)min(col0 + li, Nk - 1) * 4;
-  const float* b1 = featK + (int64_t)bhk * Nk * S + (int64_t)(h * half >> 2) * gk + (int64_t)min(col0 + 32 + li, Nk - 1) * 4;
+  const float* fq = featQ + (int64_t)bhq * Nq * S;
+  const float* fk = featK + (int64_t)bhk * Nk * S;
 
-  floatx16 c00 = {0}, c01 = {0}, c10 = {0}, c11 = {0};
-  // operands of step k+4 are in flight while the 16 MFMAs of step k run
-  float4 va0 = *reinterpret_cast<const float4*>(a0), va1 = *reinterpret_cast<const float4*>(a1);
-  float4 vb0 = *reinterpret_cast<const float4*>(b0), vb1 = *reinterpret_cast<const float4*>(b1);
-  for (int k = 0; k < half; k += 4) {
-    const int kn = ((k + 4 < half) ? k + 4 : k) >> 2;
-    const float4 na0 = *reinterpret_cast<const float4*>(a0 + kn * gq);
-    const float4 na1 = *reinterpret_cast<const float4*>(a1 + kn * gq);
-    const float4 nb0 = *reinterpret_cast<const float4*>(b0 + kn * gk);
-    const float4 nb1 = *reinterpret_cast<const float4*>(b1 + kn * gk);
-    const float xa0[4] = {va0.x, va0.y, va0.z, va0.w};
-    const float xa1[4] = {va1.x, va1.y, va1.z, va1.w};
-    const float xb0[4] = {vb0.x, vb0.y, vb0.z, vb0.w};
-    const float xb1[4] = {vb1.x, vb1.y, vb1.z, vb1.w};
+  // stage s into buffer buf: chunk c = 64 consecutive blocks of one feature group; blocks past
+  // the end of the map read the last block (their outputs are never stored)
+  auto issue_stage = [&](int s, int buf) {
+    float4* dst = stage_buf + buf * kStage;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      c00 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa0[e], xb0[e], c00, 0, 0, 0);
-      c01 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa0[e], xb1[e], c01, 0, 0, 0);
-      c10 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb0[e], c10, 0, 0, 0);
-      c11 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb1[e], c11, 0, 0, 0);
+    for (int i = 0; i < kChunks / 4; ++i) {
+      const int c = i * 4 + wave;                 // wave-uniform
+      const float* src;
+      int off;
+      if (c < kQStage / 64) {
+        const int hh = c / (kKS * 2), j = (c >> 1) % kKS, part = c & 1;
+        const int grp = ((hh * half) >> 2) + s * kKS + j;
+        src = fq + grp * gq + (int64_t)min(row_base + part * 64 + lane, Nq - 1) * 4;
+        off = (hh * kKS + j) * kTQ + part * 64;
+      } else {
+        const int cc = c - kQStage / 64;
+        const int hh = cc / (kKS * 4), j = (cc >> 2) % kKS, part = cc & 3;
+        const int grp = ((hh * half) >> 2) + s * kKS + j;
+        src = fk + grp * gk + (int64_t)min(col_base + part * 64 + lane, Nk - 1) * 4;
+        off = kQStage + (hh * kKS + j) * kTK + part * 64;
+      }
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + off), 16, 0, 0);
     }
-    va0 = na0; va1 = na1; vb0 = nb0; vb1 = nb1;
+  };
+
+  floatx16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = floatx16{0};
+  issue_stage(0, 0);
+  for (int s = 0; s < n_stages; ++s) {
+    // my loads of stage s have landed; after the barrier everyone's have, and everyone is done
+    // with the other buffer (stage s-1), which the next loads overwrite
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (s + 1 < n_stages) issue_stage(s + 1, (s + 1) & 1);
+    const float4* Qs = stage_buf + (s & 1) * kStage;
+    const float4* Ks = Qs + kQStage;
+#pragma unroll
+    for (int j = 0; j < kKS; ++j) {
+      const float4 a0 = Qs[(h * kKS + j) * kTQ + wq * 64 + li];
+      const float4 a1 = Qs[(h * kKS + j) * kTQ + wq * 64 + 32 + li];
+      float4 b[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) b[t] = Ks[(h * kKS + j) * kTK + wk * 128 + 32 * t + li];
+      const float xa0[4] = {a0.x, a0.y, a0.z, a0.w};
+      const float xa1[4] = {a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float xb = e == 0 ? b[t].x : e == 1 ? b[t].y : e == 2 ? b[t].z : b[t].w;
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa0[e], xb, acc[t], 0, 0, 0);
+          acc[4 + t] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb, acc[4 + t], 0, 0, 0);
+        }
+      }
+    }
   }
   // accumulator register r of lane (j, h) holds row 8*(r/4) + 4*h + r%4, column j
   float* out = scores + (int64_t)bhq * Nq * Nk;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int ri = 8 * (r >> 2) + 4 * h + (r & 3);
-    const int rA = row0 + ri, rB = row0 + 32 + ri;
-    const int cA = col0 + li, cB = col0 + 32 + li;
-    if (rA < Nq) {
-      if (cA < Nk) out[(int64_t)rA * Nk + cA] = c00[r];
-      if (cB < Nk) out[(int64_t)rA * Nk + cB] = c01[r];
-    }
-    if (rB < Nq) {
-      if (cA < Nk) out[(int64_t)rB * Nk + cA] = c10[r];
-      if (cB < Nk) out[(int64_t)rB * Nk + cB] = c11[r];
+  for (int t = 0; t < 4; ++t) {
+    const int col = col_base + wk * 128 + 32 * t + li;
+    if (col >= Nk) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int ri = 8 * (r >> 2) + 4 * h + (r & 3);
+      const int rA = row_base + wq * 64 + ri, rB = rA + 32;
+      if (rA < Nq) out[(int64_t)rA * Nk + col] = acc[t][r];
+      if (rB < Nq) out[(int64_t)rB * Nk + col] = acc[4 + t][r];
     }
   }
 }
@@ -227,9 +272,16 @@ basa_status launch_block_scores(const float* featQ, const float* featK, float* s
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
                                 hipStream_t st) {
   if (BHq == 0 || Nq == 0 || Nk == 0) return BASA_OK;
-  dim3 grid(ceil_div(Nk, 128) * ceil_div(Nq, 128) * BHq);
+  if (kdim_used % (8 * kKS) != 0) {        // whole stages: 16 k per half
+    set_error("score map: contraction length %d is not a multiple of %d", kdim_used, 8 * kKS);
+    return BASA_ERR_UNSUPPORTED;
+  }
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_scores_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kScoresLdsBytes);
+  if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
+  dim3 grid(ceil_div(Nk, kTK) * ceil_div(Nq, kTQ) * BHq);
   ProfScope prof(K_SCORES, st);
-  hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), 0, st, featQ, featK, scores, group, Nq,
+  hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), kScoresLdsBytes, st, featQ, featK, scores, group, Nq,
                      Nk, kdim_used, feat_stride);
   BASA_HIP_CHECK_LAUNCH("block_scores_kernel");
   return BASA_OK;
