@@ -177,8 +177,8 @@ SelectWs carve_select(const basa_tensor* q, const basa_tensor* k, const basa_par
   size_t o = 0;
   w.sort_off = o;
   o += sort_workspace_bytes(BHq + BHk, q->L > k->L ? q->L : k->L);   // Q and K may be sorted together
-  w.featq_off = o; o += align_up((size_t)BHq * Nq * 3 * q->d * sizeof(float), 256);
-  w.featk_off = o; o += align_up((size_t)BHk * Nk * 3 * k->d * sizeof(float), 256);
+  w.featq_off = o; o += align_up((size_t)BHq * Nq * feat_bytes_per_block(q->d), 256);
+  w.featk_off = o; o += align_up((size_t)BHk * Nk * feat_bytes_per_block(k->d), 256);
   w.scores_off = o; o += align_up((size_t)BHq * Nq * Nk * sizeof(float), 256);
   w.total = o;
   return w;
@@ -302,8 +302,8 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* base = reinterpret_cast<char*>(ws);
   void* sort_ws = base + w.sort_off;
-  float* featq = reinterpret_cast<float*>(base + w.featq_off);
-  float* featk = reinterpret_cast<float*>(base + w.featk_off);
+  void* featq = base + w.featq_off;
+  void* featk = base + w.featk_off;
   float* sc = scores ? scores : reinterpret_cast<float*>(base + w.scores_off);
   const TensorView qv = view_of(*q), kv = view_of(*k);
 

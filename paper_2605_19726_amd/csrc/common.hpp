@@ -71,21 +71,25 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 
 // Block statistics.  Any of the outputs may be null.
 //   mean/var : [BH][N][d]
-//   feat     : [BH][3d/4][N][4] selection features, feature k of block g at [k/4][g][k%4]
+//   feat     : selection features as three bf16 parts whose sum is the fp32 value (part 0 its bf16
+//              rounding, part 1 the rounding of the rest, part 2 of what is left: 24 bits together),
+//              [BH][part 3][3d/8][N][8] bf16: feature k of block g at [part][k/8][g][k%8]; kFeatBytes(d)
+//              bytes per block
 //              (content depends on `feat_is_query`):
 //              query side (Qbar/sqrt(d), beta*VarQ/d, beta*Qbar^2/d),
 //              key side   (Kbar, Kbar^2+VarK, VarK)
 basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
-                               float* var, float* feat, int feat_is_query, float beta,
+                               float* var, void* feat, int feat_is_query, float beta,
                                hipStream_t st);
 
 // Selection features of Q (query side) and K (key side), identical L / d / dtype, in one launch.
-basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, float* feat_q,
-                                   const TensorView& k, const int32_t* perm_k, float* feat_k, int B,
+basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, void* feat_q,
+                                   const TensorView& k, const int32_t* perm_k, void* feat_k, int B,
                                    float beta, hipStream_t st);
 
 // Block logits: scores[BHq][Nq][Nk] = featQ . featK over `kdim` features.
-basa_status launch_block_scores(const float* featQ, const float* featK, float* scores, int BHq,
+inline size_t feat_bytes_per_block(int d) { return (size_t)3 * 3 * d * 2; }
+basa_status launch_block_scores(const void* featQ, const void* featK, float* scores, int BHq,
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
                                 hipStream_t st);
 

@@ -2,10 +2,10 @@
 // (Eq. 2, Eq. 13-14; Alg. 1 steps 5-11).
 //
 // Scores: with the per-block features written by the pooling kernel the logit l' of a
-// block pair is a dot product, so the N_q x N_k map of a head is a small fp32 GEMM.
-// It runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), the features staged through
-// LDS (they are stored four to a group, groups of consecutive blocks adjacent, so that every
-// load of a wave is one contiguous run).
+// block pair is a dot product, so the N_q x N_k map of a head is a small GEMM of fp32
+// accuracy.  It runs on the bf16 matrix cores over three-part splits of the features, which
+// are staged through LDS (eight to a group, groups of consecutive blocks adjacent, so that
+// every load of a wave is one contiguous run).
 //
 // Selection: one wave per row of the map.  The kappa-th largest logit is found by a
 // 32-step bisection on an order-preserving integer image of the floats (ballot +
@@ -18,33 +18,39 @@ namespace basa {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
 // ---------------------------------------------------------------------------------
 // scores[bhq][gq][gk] = sum_k featQ[bhq][gq][k] * featK[bhq/group][gk][k], k < K
-// MFMA 32x32x2 operand roles: A[i][kk] lives in lane (i, kk), kk = lane/32; the k range
-// is split in halves, lanes 0-31 walk k in [0, K/2), lanes 32-63 walk [K/2, K).
 //
-// A workgroup of four waves owns a 128 x 256 tile of the map, a wave 64 x 128 of it (eight 32x32
-// accumulators).  The features of the tile's 128 + 256 blocks travel through LDS in stages of 16
-// k per half (48 KB, double buffered, filled with direct-to-LDS loads one stage ahead), so that
-// every feature is fetched once per workgroup: with each wave streaming its own operands from L2
-// the kernel was bound by L2 bandwidth (16 bytes per CU cycle), not by the matrix cores.
+// Every feature arrives as three bf16 parts q = q0 + q1 + q2 (8 + 8 + 8 mantissa bits; the
+// pooling kernel splits them), and the fp32 product q*k is rebuilt from the six part products
+// that matter: q0k0 + (q0k1 + q1k0) + (q0k2 + q1k1 + q2k0); the three left out are below 2^-24
+// of |q k|, the size of an fp32 rounding.  bf16 products are exact in the fp32 accumulator, so
+// the map has fp32 accuracy at six bf16 MFMAs (32 cycles each, 16 k) where the fp32 matrix
+// instruction needs eight of 64 cycles: 2.7 times fewer matrix-core cycles.
+//
+// MFMA 32x32x16 operand roles: lane (i, h) holds A[i][8h .. 8h+7], and B likewise by column.
+// A workgroup of four waves owns a 128 x 256 tile of the map, a wave 64 x 128 of it (eight
+// 32x32 accumulators).  The parts of the tile's 128 + 256 blocks travel through LDS one k-step
+// (16 k: 36 KB) at a time, double buffered and filled with direct-to-LDS loads one step ahead,
+// so that every feature is fetched once per workgroup.
 // ---------------------------------------------------------------------------------
 constexpr int kTQ = 128, kTK = 256;       // tile of the map per workgroup
-constexpr int kKS = 2;                    // feature groups (of 4) per half of the k range per stage
-constexpr int kQStage = 2 * kKS * kTQ;    // float4 per stage: [half][group][block]
-constexpr int kKStage = 2 * kKS * kTK;
+constexpr int kQStage = 3 * 2 * kTQ;      // 16-byte groups per step: [part][k-half of the step][block]
+constexpr int kKStage = 3 * 2 * kTK;
 constexpr int kStage = kQStage + kKStage;
 constexpr int kScoresLdsBytes = 2 * kStage * 16;
-constexpr int kChunks = kStage / 64;      // direct-to-LDS loads of one wave-width (64 x 16 B) per stage
+constexpr int kChunks = kStage / 64;      // direct-to-LDS loads of one wave-width (64 x 16 B) per step
+static_assert(kChunks % 4 == 0 && (kQStage / 64) % 4 == 0, "chunks are dealt to the four waves in rounds");
 
-__global__ __launch_bounds__(256, 2) void block_scores_kernel(const float* __restrict__ featQ,
-                                                              const float* __restrict__ featK,
+__global__ __launch_bounds__(256, 2) void block_scores_kernel(const uint4* __restrict__ featQ,
+                                                              const uint4* __restrict__ featK,
                                                               float* __restrict__ scores, int group,
                                                               int Nq, int Nk, int K, int S) {
-  extern __shared__ __attribute__((aligned(16))) float4 stage_buf[];
+  extern __shared__ __attribute__((aligned(16))) uint4 stage_buf[];
   // consecutive workgroup ids go round-robin over the 8 XCDs: hand each XCD a contiguous range
   // of (head, tile) so that a head's features are pulled into one L2 only
   const int total = gridDim.x, tiles_x = (Nk + kTK - 1) / kTK, tiles_y = (Nq + kTQ - 1) / kTQ;
@@ -59,33 +65,30 @@ __global__ __launch_bounds__(256, 2) void block_scores_kernel(const float* __res
   const int row_base = ty * kTQ, col_base = tx * kTK;
   const int wq = wave >> 1, wk = wave & 1;       // this wave: rows wq*64.., columns wk*128..
 
-  // features are stored [K/4][N][4] floats: one 16-byte group per block, blocks adjacent
-  const int half = K >> 1;
-  const int n_stages = half / (4 * kKS);
-  const int64_t gq = (int64_t)Nq * 4, gk = (int64_t)Nk * 4;      // floats per group of 4 features
-  const float* fq = featQ + (int64_t)bhq * Nq * S;
-  const float* fk = featK + (int64_t)bhk * Nk * S;
+  // features: [part][S/8][N] groups of 8 bf16 (16 bytes); k-step s uses groups 2s and 2s+1
+  const int n_steps = K >> 4;
+  const int groups = S >> 3;
+  const uint4* fq = featQ + (int64_t)bhq * 3 * groups * Nq;
+  const uint4* fk = featK + (int64_t)bhk * 3 * groups * Nk;
 
-  // stage s into buffer buf: chunk c = 64 consecutive blocks of one feature group; blocks past
-  // the end of the map read the last block (their outputs are never stored)
-  auto issue_stage = [&](int s, int buf) {
-    float4* dst = stage_buf + buf * kStage;
+  // step s into buffer buf: chunk c = 64 consecutive blocks of one group of one part; blocks
+  // past the end of the map read the last block (their outputs are never stored)
+  auto issue_step = [&](int s, int buf) {
+    uint4* dst = stage_buf + buf * kStage;
 #pragma unroll
     for (int i = 0; i < kChunks / 4; ++i) {
       const int c = i * 4 + wave;                 // wave-uniform
-      const float* src;
+      const uint4* src;
       int off;
-      if (c < kQStage / 64) {
-        const int hh = c / (kKS * 2), j = (c >> 1) % kKS, part = c & 1;
-        const int grp = ((hh * half) >> 2) + s * kKS + j;
-        src = fq + grp * gq + (int64_t)min(row_base + part * 64 + lane, Nq - 1) * 4;
-        off = (hh * kKS + j) * kTQ + part * 64;
-      } else {
+      if (i < kQStage / 256) {                    // c = part*4 + khalf*2 + which 64 of the 128 rows
+        const int part = c >> 2, kh = (c >> 1) & 1, sub = c & 1;
+        src = fq + ((int64_t)part * groups + 2 * s + kh) * Nq + min(row_base + sub * 64 + lane, Nq - 1);
+        off = (part * 2 + kh) * kTQ + sub * 64;
+      } else {                                    // cc = part*8 + khalf*4 + which 64 of the 256 columns
         const int cc = c - kQStage / 64;
-        const int hh = cc / (kKS * 4), j = (cc >> 2) % kKS, part = cc & 3;
-        const int grp = ((hh * half) >> 2) + s * kKS + j;
-        src = fk + grp * gk + (int64_t)min(col_base + part * 64 + lane, Nk - 1) * 4;
-        off = kQStage + (hh * kKS + j) * kTK + part * 64;
+        const int part = cc >> 3, kh = (cc >> 2) & 1, sub = cc & 3;
+        src = fk + ((int64_t)part * groups + 2 * s + kh) * Nk + min(col_base + sub * 64 + lane, Nk - 1);
+        off = kQStage + (part * 2 + kh) * kTK + sub * 64;
       }
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + off), 16, 0, 0);
     }
@@ -94,32 +97,38 @@ __global__ __launch_bounds__(256, 2) void block_scores_kernel(const float* __res
   floatx16 acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = floatx16{0};
-  issue_stage(0, 0);
-  for (int s = 0; s < n_stages; ++s) {
-    // my loads of stage s have landed; after the barrier everyone's have, and everyone is done
-    // with the other buffer (stage s-1), which the next loads overwrite
+  issue_step(0, 0);
+  for (int s = 0; s < n_steps; ++s) {
+    // my loads of step s have landed; after the barrier everyone's have, and everyone is done
+    // with the other buffer (step s-1), which the next loads overwrite
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (s + 1 < n_stages) issue_stage(s + 1, (s + 1) & 1);
-    const float4* Qs = stage_buf + (s & 1) * kStage;
-    const float4* Ks = Qs + kQStage;
+    if (s + 1 < n_steps) issue_step(s + 1, (s + 1) & 1);
+    const uint4* Qs = stage_buf + (s & 1) * kStage;
+    const uint4* Ks = Qs + kQStage;
+    bf16x8 a[3][2], b[3][4];
 #pragma unroll
-    for (int j = 0; j < kKS; ++j) {
-      const float4 a0 = Qs[(h * kKS + j) * kTQ + wq * 64 + li];
-      const float4 a1 = Qs[(h * kKS + j) * kTQ + wq * 64 + 32 + li];
-      float4 b[4];
+    for (int part = 0; part < 3; ++part) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) b[t] = Ks[(h * kKS + j) * kTK + wk * 128 + 32 * t + li];
-      const float xa0[4] = {a0.x, a0.y, a0.z, a0.w};
-      const float xa1[4] = {a1.x, a1.y, a1.z, a1.w};
+      for (int u = 0; u < 2; ++u) {
+        const uint4 v = Qs[(part * 2 + h) * kTQ + wq * 64 + 32 * u + li];
+        a[part][u] = __builtin_bit_cast(bf16x8, v);
+      }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int t = 0; t < 4; ++t) {
+        const uint4 v = Ks[(part * 2 + h) * kTK + wk * 128 + 32 * t + li];
+        b[part][t] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+    // the smallest products first
+    constexpr int PQ[6] = {2, 1, 0, 1, 0, 0};
+    constexpr int PK[6] = {0, 1, 2, 0, 1, 0};
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const float xb = e == 0 ? b[t].x : e == 1 ? b[t].y : e == 2 ? b[t].z : b[t].w;
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa0[e], xb, acc[t], 0, 0, 0);
-          acc[4 + t] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa1[e], xb, acc[4 + t], 0, 0, 0);
-        }
+    for (int pr = 0; pr < 6; ++pr) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PQ[pr]][0], b[PK[pr]][t], acc[t], 0, 0, 0);
+        acc[4 + t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PQ[pr]][1], b[PK[pr]][t], acc[4 + t], 0, 0, 0);
       }
     }
   }
@@ -268,12 +277,12 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
 
 }  // namespace
 
-basa_status launch_block_scores(const float* featQ, const float* featK, float* scores, int BHq,
+basa_status launch_block_scores(const void* featQ, const void* featK, float* scores, int BHq,
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
                                 hipStream_t st) {
   if (BHq == 0 || Nq == 0 || Nk == 0) return BASA_OK;
-  if (kdim_used % (8 * kKS) != 0) {        // whole stages: 16 k per half
-    set_error("score map: contraction length %d is not a multiple of %d", kdim_used, 8 * kKS);
+  if (kdim_used % 16 != 0 || feat_stride % 8 != 0) {        // whole k-steps of 16
+    set_error("score map: contraction length %d is not a multiple of 16", kdim_used);
     return BASA_ERR_UNSUPPORTED;
   }
   const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_scores_kernel),
@@ -281,8 +290,8 @@ basa_status launch_block_scores(const float* featQ, const float* featK, float* s
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
   dim3 grid(ceil_div(Nk, kTK) * ceil_div(Nq, kTQ) * BHq);
   ProfScope prof(K_SCORES, st);
-  hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), kScoresLdsBytes, st, featQ, featK, scores, group, Nq,
-                     Nk, kdim_used, feat_stride);
+  hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), kScoresLdsBytes, st, reinterpret_cast<const uint4*>(featQ),
+                     reinterpret_cast<const uint4*>(featK), scores, group, Nq, Nk, kdim_used, feat_stride);
   BASA_HIP_CHECK_LAUNCH("block_scores_kernel");
   return BASA_OK;
 }

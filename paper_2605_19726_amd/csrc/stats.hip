@@ -18,7 +18,7 @@ struct StatsJob {
   const int32_t* perm;
   float* mean_out;
   float* var_out;
-  float* feat_out;
+  uint16_t* feat_out;        // bf16 parts, [3][3d/8][N][8]
   int feat_is_query;
 };
 
@@ -39,8 +39,8 @@ __device__ __forceinline__ float chunk_elem(const uint4& r, int e) {
 // bytes in flight, and a kernel that loads, reduces and retires one block at a time has none in
 // flight for half of its life.  Sums over the rows held by a wave are taken with lane exchanges,
 // over the four waves through LDS.  The features of the kGroup blocks are collected in LDS and
-// written at the end as 128-byte runs (in the [k/4][g][k%4] layout one block's features are 16-byte
-// pieces 16 KB apart, which cost a fifth of the kernel when every block wrote its own).
+// written at the end as 128-byte runs (in the [part][k/8][g][k%8] layout one block's features are
+// 16-byte pieces 16 KB apart, which cost a fifth of the kernel when every block wrote its own).
 template <bool kBf16, int kD, int kB>
 __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob j1, int BH0, float beta) {
   constexpr int kElem = kBf16 ? 2 : 4;
@@ -50,14 +50,14 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
   constexpr int E = kBf16 ? 8 : 4;           // elements per chunk
   static_assert(ITERS >= 1 && LPR <= 64, "block too small for this tiling");
   __shared__ float red[2][2][4][kD];         // [block parity][mean | centred squares][wave][column]
-  __shared__ float4 stage[3 * kD / 4][kGroup];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[3][3 * kD / 8][kGroup][8];   // [part][k/8][block][k%8]
 
   const bool second = (int)blockIdx.y >= BH0;
   const StatsJob& job = second ? j1 : j0;
   const TensorView& x = job.x;
   float* mean_out = job.mean_out;
   float* var_out = job.var_out;
-  float* feat_out = job.feat_out;
+  uint16_t* feat_out = job.feat_out;
   const int feat_is_query = job.feat_is_query;
   const int bh = second ? blockIdx.y - BH0 : blockIdx.y;
   const int L = x.L;
@@ -199,16 +199,28 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
       if (mean_out) mean_out[o] = mean_c;
       if (var_out) var_out[o] = var_c;
       if (feat_out) {
-        float* f = reinterpret_cast<float*>(&stage[c >> 2][b]) + (c & 3);
-        constexpr int third = (kD / 4) * kGroup * 4;            // floats between the three parts in stage
+        float f[3];
         if (feat_is_query) {
           f[0] = mean_c * (1.0f / sqrtf((float)kD));
-          f[third] = beta * var_c * (1.0f / (float)kD);
-          f[2 * third] = beta * (mean_c * mean_c) * (1.0f / (float)kD);
+          f[1] = beta * var_c * (1.0f / (float)kD);
+          f[2] = beta * (mean_c * mean_c) * (1.0f / (float)kD);
         } else {
           f[0] = mean_c;
-          f[third] = mean_c * mean_c + var_c;
-          f[2 * third] = var_c;
+          f[1] = mean_c * mean_c + var_c;
+          f[2] = var_c;
+        }
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+          // feature k = i*kD + c as three bf16 parts: each part is the rounding of what the parts
+          // before it left (the subtractions are exact in fp32)
+          const int k = i * kD + c;
+          float rest = f[i];
+#pragma unroll
+          for (int part = 0; part < 3; ++part) {
+            const __bf16 hi = (__bf16)rest;
+            stage[part][k >> 3][b][k & 7] = __builtin_bit_cast(uint16_t, hi);
+            rest -= (float)hi;
+          }
         }
       }
     }
@@ -219,13 +231,14 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
     }
   }
   if (feat_out) {
-    // feature k of block g lives at [k / 4][g][k % 4]: the score kernel reads 16-byte groups of
-    // 32 consecutive blocks with one coalesced load
+    // feature k of block g lives at [part][k / 8][g][k % 8]: the score kernel fetches 16-byte groups
+    // of 64 consecutive blocks with one coalesced load
     __syncthreads();
-    float4* f4 = reinterpret_cast<float4*>(feat_out + (int64_t)bh * N * (3 * kD));
-    for (int i = threadIdx.x; i < (3 * kD / 4) * kGroup; i += 256) {
-      const int k4 = i / kGroup, gi = i % kGroup;
-      if (gi < nb) f4[(int64_t)k4 * N + g0 + gi] = stage[k4][gi];
+    uint4* f4 = reinterpret_cast<uint4*>(feat_out + (int64_t)bh * N * (3 * 3 * kD));
+    const uint4* st4 = reinterpret_cast<const uint4*>(&stage[0][0][0][0]);
+    for (int i = threadIdx.x; i < 3 * (3 * kD / 8) * kGroup; i += 256) {
+      const int pg = i / kGroup, gi = i % kGroup;         // pg = part * (3d/8) + k/8
+      if (gi < nb) f4[(int64_t)pg * N + g0 + gi] = st4[i];
     }
   }
 }
@@ -258,17 +271,17 @@ static basa_status block_stats_impl(const StatsJob& j0, const StatsJob* j1, int 
 }
 
 basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
-                               float* var, float* feat, int feat_is_query, float beta,
+                               float* var, void* feat, int feat_is_query, float beta,
                                hipStream_t st) {
-  const StatsJob j{x, perm, mean, var, feat, feat_is_query};
+  const StatsJob j{x, perm, mean, var, reinterpret_cast<uint16_t*>(feat), feat_is_query};
   return block_stats_impl(j, nullptr, B, beta, st);
 }
 
-basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, float* feat_q,
-                                   const TensorView& k, const int32_t* perm_k, float* feat_k, int B,
+basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, void* feat_q,
+                                   const TensorView& k, const int32_t* perm_k, void* feat_k, int B,
                                    float beta, hipStream_t st) {
-  const StatsJob jq{q, perm_q, nullptr, nullptr, feat_q, 1};
-  const StatsJob jk{k, perm_k, nullptr, nullptr, feat_k, 0};
+  const StatsJob jq{q, perm_q, nullptr, nullptr, reinterpret_cast<uint16_t*>(feat_q), 1};
+  const StatsJob jk{k, perm_k, nullptr, nullptr, reinterpret_cast<uint16_t*>(feat_k), 0};
   return block_stats_impl(jq, &jk, B, beta, st);
 }
 
