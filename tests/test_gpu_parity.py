@@ -97,6 +97,28 @@ def test_select_and_attention_with_segments():
         check_output(np64(out[0, h]), O_ref, True, f"segments head {h}")
 
 
+@pytest.mark.parametrize("dtype,d", [(torch.float32, 128), (torch.bfloat16, 128), (torch.float32, 64)])
+def test_score_map_keeps_fp32_accuracy_over_a_wide_dynamic_range(dtype, d):
+    """The score map multiplies three-part bf16 splits of fp32 features on the bf16 matrix cores;
+    per-dimension scales over four decades and large offsets exercise every part of the split."""
+    L, block = 3000 + 17, 64
+    g = torch.Generator().manual_seed(2718)
+    scale = 10.0 ** (torch.rand((1, 1, 1, d), generator=g) * 4 - 2)           # 0.01 .. 100 per dimension
+    offset = torch.randn((1, 1, 1, d), generator=g) * 3
+    Q = ((torch.randn((1, 2, L, d), generator=g) + offset) * scale).to(dtype).to(DEV)
+    K = ((torch.randn((1, 2, L, d), generator=g) - offset) * scale.flip(-1)).to(dtype).to(DEV)
+    for beta in (1.0, 0.0):
+        sel = bd.basa_select(Q, K, block, 0.5, beta, want_scores=True)
+        for h in range(2):
+            ref = o.select(np64(Q[0, h]), np64(K[0, h]), block, 0.5, beta)
+            got = sel.scores[0, h].cpu().numpy().astype(np.float64)
+            err = np.abs(got - ref["logits"])
+            big = np.abs(ref["logits"]).max()
+            assert err.max() <= 1e-5 * max(1.0, big), (beta, h, err.max(), big)
+            # the typical error is that of fp32 arithmetic, far inside the bound
+            assert np.median(err) <= 2e-6 * max(1.0, big), (beta, h, np.median(err), big)
+
+
 def test_norm_sort_keys_zeros_subnormals_and_scales():
     """Sort keys stay bit-identical to the oracle's when rows hold exact zeros, bf16 subnormals,
     all-zero rows, and values spread over many binades (within what an fp64 sum adds exactly)."""
