@@ -238,11 +238,14 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
 #pragma unroll
     for (int i = 0; i < MAXI; ++i) cnt += __popcll(__ballot(u[i] >= cand));
     if (cnt >= keep) T = cand;
+    // exactly `keep` images at or above cand: they are the kept set, whatever the lower bits of
+    // the keep-th largest are (typically after about 8 + log2 N_k of the 32 steps)
+    if (cnt == keep) break;
   }
   int n_gt = 0;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) n_gt += __popcll(__ballot(u[i] > T));
-  const int need_eq = keep - n_gt;       // >= 1 by construction of T
+  const int need_eq = keep - n_gt;       // how many of the images equal to T are kept
 
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const int words = (Nk + 31) >> 5;
