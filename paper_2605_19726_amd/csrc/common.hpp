@@ -73,7 +73,7 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 //   mean/var : [BH][N][d]
 //   feat     : selection features as three bf16 parts whose sum is the fp32 value (part 0 its bf16
 //              rounding, part 1 the rounding of the rest, part 2 of what is left: 24 bits together),
-//              [BH][part 3][3d/8][N][8] bf16: feature k of block g at [part][k/8][g][k%8]; kFeatBytes(d)
+//              [BH][part 3][3d/8][N][8] bf16: feature k of block g at [part][k/8][g][k%8]; feat_bytes_per_block(d)
 //              bytes per block
 //              (content depends on `feat_is_query`):
 //              query side (Qbar/sqrt(d), beta*VarQ/d, beta*Qbar^2/d),
