@@ -33,6 +33,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # plain-copy calibration (profiles/attn_and_select_cfg4_s50.md); only valid for the workload it names.
 MEASURED_TRAFFIC_BYTES = {("cfg4_dlm_128k", 0.5): 35.7e9}
+# the same for all kernels of basa_select together (one key + tile-sort launch, five merge passes,
+# pooling, score map, row selection), from the same profile
+MEASURED_SELECT_TRAFFIC_BYTES = {("cfg4_dlm_128k", 0.5): 5.77e9}
 
 
 def executed_flops(w, kappa):
@@ -289,8 +292,8 @@ def cpu_baseline(w, sparsity, Q, K, V, pipe, n_units=24):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--sparsity", type=float, default=0.5)
     ap.add_argument("--sweep", action="store_true")
@@ -393,6 +396,7 @@ def main():
         "roofline_select": {"stage": "basa_select (all kernels)", "bound": "hbm",
                             "achieved": res["selection_gbs_total"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": res["selection_gbs_total"] / PEAK_HBM_GBS,
+                            "traffic": MEASURED_SELECT_TRAFFIC_BYTES.get((w.name, args.sparsity)),
                             "achieved_two_pass_qk_only": res["selection_gbs_two_pass"],
                             "bytes": res["selection_bytes"]},
         "kernel_ms_per_step": res["kernel_ms_per_step"],
