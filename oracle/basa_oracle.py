@@ -214,6 +214,39 @@ def select_top_mass(m: np.ndarray, mass_target: float, min_keep: int = 1, cap: i
     return dict(mask=mask, count=count, cols=cols, mass=mass, cum=cum)
 
 
+def budget_cap(count, budget_total: int, floor: int, kappa: int) -> int:
+    """Common per-row cap that fits a head's rows into a total budget of kept blocks.
+
+    Reading (the paper speaks of "computational budgets", Sec. 3.1 after Eq. 2, without a rule
+    for sharing one between rows): the rows that ask for the most are trimmed first, to a common
+    cap t, the largest t in [floor, kappa] with sum_r min(count_r, t) <= budget_total; rows that
+    ask for no more than t keep what they asked for.  If even t = floor does not fit, t = floor
+    (the per-row minimum wins over the budget).
+    """
+    count = [int(c) for c in count]
+    floor = max(1, min(int(floor), int(kappa)))
+    best = floor
+    for t in range(floor, int(kappa) + 1):
+        if sum(min(c, t) for c in count) <= budget_total:
+            best = t
+    return best
+
+
+def select_top_counts(m: np.ndarray, counts):
+    """Row r keeps its counts[r] key blocks of largest m' (equal values: lower index first).
+    Returns dict(mask, count, cols: list of ascending arrays, mass)."""
+    n_q, n_k = m.shape
+    mask = np.zeros((n_q, n_k), dtype=bool)
+    cols, mass = [], np.zeros(n_q)
+    for r in range(n_q):
+        order = np.argsort(-m[r], kind="stable")
+        keep = order[:int(counts[r])]
+        mask[r, keep] = True
+        cols.append(np.sort(keep))
+        mass[r] = m[r, keep].sum()
+    return dict(mask=mask, count=np.asarray(counts, dtype=np.int64), cols=cols, mass=mass)
+
+
 # --------------------------------------------------------------------------- #
 # Attention (Eq. 1; Sec. 2 block-sparse attention; Alg. 1 step 12)
 # --------------------------------------------------------------------------- #
@@ -285,7 +318,8 @@ def sparse_attention(Q, K, V, perm_q, perm_k, cols, B: int, return_lse: bool = F
 # The whole operator (Alg. 1)
 # --------------------------------------------------------------------------- #
 def select(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK,
-           window: int = 0, mass_target: float | None = None, min_keep: int = 1, segments=None):
+           window: int = 0, mass_target: float | None = None, min_keep: int = 1, segments=None,
+           budget_total: int = 0):
     """Alg. 1 steps 1-11 for one head: permutations, block statistics, compensated
     logits, row distribution, top-kappa mask.  Returns a dict with every
     intermediate.  With mass_target the mask is the cumulative-mass one instead
@@ -306,6 +340,12 @@ def select(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK
     out = dict(perm_q=perm_q, perm_k=perm_k, q_mean=q_mean, q_var=q_var, k_mean=k_mean,
                k_var=k_var, logits=logits, m=m, kappa=kappa)
     out.update(sel)
+    if budget_total:
+        # the head's rows share a total budget: a common cap on top of the per-row rule
+        asked = sel["count"] if mass_target is not None else np.full(m.shape[0], min(kappa, m.shape[1]))
+        cap = budget_cap(asked, budget_total, min_keep if mass_target is not None else 1, kappa)
+        out.update(select_top_counts(m, np.minimum(asked, cap)))
+        out["asked"], out["cap"] = asked, cap
     return out
 
 

@@ -157,6 +157,52 @@ def test_select_with_segments_only_changes_the_permutations():
     assert np.array_equal(qm, ref["q_mean"]) and np.array_equal(qv, ref["q_var"])
 
 
+def test_budget_cap_against_brute_force_and_its_properties():
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        n, kappa = int(rng.integers(1, 9)), int(rng.integers(1, 7))
+        floor = int(rng.integers(1, kappa + 1))
+        count = rng.integers(floor, kappa + 1, size=n)
+        G = int(rng.integers(0, n * kappa + 3))
+        t = o.budget_cap(count, G, floor, kappa)
+        total = lambda c: int(np.minimum(count, c).sum())
+        fits = [c for c in range(floor, kappa + 1) if total(c) <= G]
+        assert t == (max(fits) if fits else floor)
+        assert floor <= t <= kappa
+        if fits:
+            assert total(t) <= G and (t == kappa or total(t + 1) > G)
+        # rows that asked for no more than the cap keep what they asked for
+        assert (np.minimum(count, t)[count <= t] == count[count <= t]).all()
+        # a larger budget never lowers the cap
+        assert o.budget_cap(count, G + 1, floor, kappa) >= t
+    # closed forms: equal requests share the budget evenly; a budget that covers everything changes nothing
+    assert o.budget_cap([5, 5, 5, 5], 12, 1, 5) == 3
+    assert o.budget_cap([5, 2, 1], 8, 1, 5) == 5
+    assert o.budget_cap([5, 2, 1], 7, 1, 5) == 4
+    assert o.budget_cap([4, 4], 1, 2, 4) == 2                      # the per-row minimum wins
+
+
+def test_select_with_a_total_budget_trims_the_greediest_rows():
+    Q, K = rand(128, 4), rand(128, 4)
+    free = o.select(Q, K, 8, 0.0, mass_target=0.7, min_keep=2)
+    asked = free["count"]
+    assert asked.min() < asked.max() and asked.sum() - 5 >= 2 * len(asked)     # the case is not degenerate
+    G = int(asked.sum()) - 5
+    ref = o.select(Q, K, 8, 0.0, mass_target=0.7, min_keep=2, budget_total=G)
+    assert ref["count"].sum() <= G and (ref["count"] == np.minimum(asked, ref["cap"])).all()
+    for r in range(len(asked)):
+        # the kept set of a trimmed row is the head of its own ranking
+        top = o.select_top_kappa(ref["m"][r:r + 1], int(ref["count"][r]))
+        assert np.array_equal(top["mask"][0], ref["mask"][r])
+        assert set(ref["cols"][r]) <= set(free["cols"][r])
+    # fixed-count mode: the budget lowers the common count
+    fixed = o.select(Q, K, 8, 0.0, budget_total=16 * 3 + 2)
+    assert (fixed["count"] == 3).all()
+    # a budget nobody exceeds changes nothing
+    same = o.select(Q, K, 8, 0.0, mass_target=0.7, min_keep=2, budget_total=int(asked.sum()))
+    assert np.array_equal(same["mask"], free["mask"])
+
+
 def test_sort_key_is_fp32_rounded_squared_norm():
     x = np.array([[3.0, 4.0], [1e-3, 0.0]])
     k = o.token_sort_keys(x)
