@@ -84,7 +84,13 @@ typedef struct {
                                 segment_starts[j+1]-1 (the last segment ends at L) are sorted
                                 among themselves and keep their range of positions.  Excludes
                                 window > 0; with two tensors (basa_select) L_q must equal L_k  */
-  int32_t reserved;          /* 0                                                             */
+  int32_t budget_total;      /* 0: none.  G > 0: the rows of one (batch, head) keep at most G key
+                                blocks together.  The rows that ask for the most are trimmed
+                                first, to a common cap t: the largest t in [max(1, min_keep),
+                                kappa] with sum_r min(count_r, t) <= G (if even the smallest t
+                                does not fit, the per-row minimum wins); a trimmed row keeps its
+                                t blocks of largest m'.  With mass_target = 0 every row asks for
+                                kappa, so G lowers the common count to G / N_q                 */
   const int32_t* segment_starts;   /* HOST array of n_segments token indices: first 0, strictly
                                 ascending, last < L; read during the call only (NULL if none) */
 } basa_params;

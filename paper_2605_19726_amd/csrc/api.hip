@@ -124,6 +124,9 @@ basa_status check_params(const basa_params* p, bool need_sparsity) {
   if (need_sparsity && !(p->mass_target >= 0.0 && p->mass_target <= 1.0)) {
     set_error("mass_target %g outside [0, 1]", p->mass_target); return BASA_ERR_INVALID_ARG;
   }
+  if (need_sparsity && p->budget_total < 0) {
+    set_error("budget_total %d is negative", p->budget_total); return BASA_ERR_INVALID_ARG;
+  }
   if (need_sparsity && p->min_keep < 0) {
     set_error("min_keep %d is negative", p->min_keep); return BASA_ERR_INVALID_ARG;
   }
@@ -331,8 +334,16 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   }
   const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
   if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
-  return launch_row_select(sc, BHq * Nq, Nk, kappa, (float)p->mass_target, p->min_keep, mask_bits, row_count,
-                           row_cols, row_mass, st);
+  if ((s = launch_row_select(sc, BHq * Nq, Nk, kappa, (float)p->mass_target, p->min_keep, nullptr, mask_bits,
+                             row_count, row_cols, row_mass, st)) != BASA_OK) return s;
+  if (p->budget_total > 0) {
+    // the sort buffers are free by now: the trimmed per-row counts live there
+    int32_t* keep = reinterpret_cast<int32_t*>(sort_ws);
+    const int floor_keep = p->mass_target > 0.0 ? p->min_keep : 1;
+    if ((s = launch_budget_cap(row_count, BHq, Nq, kappa, floor_keep, p->budget_total, keep, st)) != BASA_OK) return s;
+    s = launch_row_select(sc, BHq * Nq, Nk, kappa, 0.f, 0, keep, mask_bits, row_count, row_cols, row_mass, st);
+  }
+  return s;
 }
 
 basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,

@@ -95,10 +95,16 @@ basa_status launch_block_scores(const void* featQ, const void* featK, float* sco
 
 // Row softmax mass + top-kappa selection from a score map; mass_target > 0 switches to the
 // cumulative-mass count per row (floor min_keep, cap kappa).  row_cols rows are kappa apart.
+// keep_in (nullable): per-row count that replaces both rules (used after launch_budget_cap).
 basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
-                              float mass_target, int min_keep, uint32_t* mask_bits,
+                              float mass_target, int min_keep, const int32_t* keep_in, uint32_t* mask_bits,
                               int32_t* row_count, int32_t* row_cols, float* row_mass,
                               hipStream_t st);
+
+// Total budget per (batch, head): keep_out[r] = min(row_count[r], t), t the largest cap in
+// [max(1, floor_keep), kappa] with sum_r min(row_count[r], t) <= budget (else the smallest cap).
+basa_status launch_budget_cap(const int32_t* row_count, int BHq, int Nq, int kappa, int floor_keep,
+                              int budget, int32_t* keep_out, hipStream_t st);
 
 // Attention.
 struct AttnArgs {

@@ -168,6 +168,7 @@ template <int MAXI>
 __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ scores,
                                                          int rows_total, int Nk, int kappa,
                                                          float mass_target, int min_keep,
+                                                         const int32_t* __restrict__ keep_in,
                                                          uint32_t* __restrict__ mask_bits,
                                                          int32_t* __restrict__ row_count,
                                                          int32_t* __restrict__ row_cols,
@@ -200,8 +201,8 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   }
   sum_all = wave_sum(sum_all);
 
-  int keep = kappa;
-  if (mass_target > 0.f) {
+  int keep = keep_in ? max(1, min(keep_in[row], kappa)) : kappa;
+  if (!keep_in && mass_target > 0.f) {
     const float need = mass_target * sum_all;
     // T2 = largest image T such that the logits with image >= T carry at least the target
     uint32_t T2 = 0;
@@ -278,7 +279,54 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Total budget of kept blocks per (batch, head): one workgroup per head builds the histogram of
+// the rows' counts and walks the caps t = lo .. kappa: total(t) = sum_{c <= t} c*hist[c] +
+// t * #{rows with c > t} never decreases with t, so the last t that fits is the answer.
+// ---------------------------------------------------------------------------------
+constexpr int kMaxCount = 4096;
+__global__ __launch_bounds__(256) void budget_cap_kernel(const int32_t* __restrict__ row_count, int Nq, int kappa,
+                                                         int floor_keep, int budget, int32_t* __restrict__ keep_out) {
+  __shared__ int hist[kMaxCount + 1];
+  __shared__ int cap_s;
+  const int32_t* cnt = row_count + (int64_t)blockIdx.x * Nq;
+  for (int i = threadIdx.x; i <= kappa; i += 256) hist[i] = 0;
+  __syncthreads();
+  for (int r = threadIdx.x; r < Nq; r += 256) atomicAdd(&hist[max(0, min(cnt[r], kappa))], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int lo = max(1, min(floor_keep, kappa));
+    int64_t below = 0;           // sum of the counts <= t
+    int rows_below = 0;          // rows with count <= t
+    for (int c = 0; c < lo; ++c) { below += (int64_t)c * hist[c]; rows_below += hist[c]; }
+    int cap = lo;
+    for (int t = lo; t <= kappa; ++t) {
+      below += (int64_t)t * hist[t];
+      rows_below += hist[t];
+      if (below + (int64_t)t * (Nq - rows_below) <= (int64_t)budget) cap = t;
+    }
+    cap_s = cap;
+  }
+  __syncthreads();
+  const int cap = cap_s;
+  for (int r = threadIdx.x; r < Nq; r += 256) keep_out[(int64_t)blockIdx.x * Nq + r] = min(cnt[r], cap);
+}
+
 }  // namespace
+
+basa_status launch_budget_cap(const int32_t* row_count, int BHq, int Nq, int kappa, int floor_keep,
+                              int budget, int32_t* keep_out, hipStream_t st) {
+  if (BHq == 0 || Nq == 0) return BASA_OK;
+  if (kappa > kMaxCount) {
+    set_error("a total budget supports at most %d key blocks per row (got %d)", kMaxCount, kappa);
+    return BASA_ERR_UNSUPPORTED;
+  }
+  ProfScope prof(K_ROW_SELECT, st);
+  hipLaunchKernelGGL(budget_cap_kernel, dim3(BHq), dim3(256), 0, st, row_count, Nq, kappa, floor_keep, budget,
+                     keep_out);
+  BASA_HIP_CHECK_LAUNCH("budget_cap_kernel");
+  return BASA_OK;
+}
 
 basa_status launch_block_scores(const void* featQ, const void* featK, float* scores, int BHq,
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
@@ -300,7 +348,7 @@ basa_status launch_block_scores(const void* featQ, const void* featK, float* sco
 }
 
 basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
-                              float mass_target, int min_keep, uint32_t* mask_bits,
+                              float mass_target, int min_keep, const int32_t* keep_in, uint32_t* mask_bits,
                               int32_t* row_count, int32_t* row_cols, float* row_mass,
                               hipStream_t st) {
   if (rows_total == 0) return BASA_OK;
@@ -308,7 +356,7 @@ basa_status launch_row_select(const float* scores, int rows_total, int Nk, int k
   ProfScope prof(K_ROW_SELECT, st);
 #define BASA_SEL(M)                                                                            \
   hipLaunchKernelGGL((row_select_kernel<M>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
-                     kappa, mass_target, min_keep, mask_bits, row_count, row_cols, row_mass)
+                     kappa, mass_target, min_keep, keep_in, mask_bits, row_count, row_cols, row_mass)
   if (Nk <= 256) BASA_SEL(4);
   else if (Nk <= 1024) BASA_SEL(16);
   else if (Nk <= 2048) BASA_SEL(32);

@@ -82,6 +82,7 @@ def test_select_argument_validation(lib):
     assert call(q, k, bd.params(128, 0.5, mass_target=1.5))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=-0.1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=0.9, min_keep=-1))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, budget_total=-1))[0] == "BASA_ERR_INVALID_ARG"
     seg = lambda starts, **kw: bd.params(128, 0.5, segments=starts, **kw)
     assert call(q, k, seg([1, 5]))[0] == "BASA_ERR_INVALID_ARG"                 # must start at 0
     assert call(q, k, seg([0, 5, 5]))[0] == "BASA_ERR_INVALID_ARG"              # must ascend strictly

@@ -296,6 +296,47 @@ def test_mass_selection_then_attention_with_ragged_row_counts():
             check_output(out_h[rows], O_ref, w.dtype == "bf16", f"head {h} block {g}")
 
 
+@pytest.mark.parametrize("mode", ["mass", "fixed"])
+def test_total_budget_trims_rows_to_a_common_cap(mode):
+    """budget_total: the integer rule is checked exactly on the counts the GPU itself asked for
+    (they may differ from the fp64 oracle's by one near the mass target), the kept sets against
+    the oracle's ranking of every row."""
+    w = SMALL[1]
+    Q, K, V = gen(w)
+    kw = dict(mass_target=0.8, min_keep=2) if mode == "mass" else {}
+    s_cap = 0.0 if mode == "mass" else 0.25
+    free = bd.basa_select(Q, K, w.block, s_cap, **kw)
+    asked = free.row_count.cpu().numpy().astype(np.int64)              # [1, H, Nq]
+    H, n_q = asked.shape[1], asked.shape[2]
+    floor = 2 if mode == "mass" else 1
+    for G in (int(asked[0, 0].sum()) - 7, n_q * floor + 3, 1, int(asked.max()) * n_q + 5):
+        sel = bd.basa_select(Q, K, w.block, s_cap, want_scores=True, budget_total=G, **kw)
+        out = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k)
+        torch.cuda.synchronize()
+        cnt = sel.row_count.cpu().numpy().astype(np.int64)
+        gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
+        group = H // K.shape[1]
+        for h in range(H):
+            cap = o.budget_cap(asked[0, h], G, floor, free.kappa)
+            assert np.array_equal(cnt[0, h], np.minimum(asked[0, h], cap)), (mode, G, h)
+            if cnt[0, h].sum() > G:
+                assert cap == floor                                     # only the per-row minimum may break the budget
+            ref = oracle_select(Q, K, h, w.block, s_cap, 1.0, o.SORT_QK)
+            cols = sel.row_cols[0, h].cpu().numpy().astype(np.int64)
+            for r in range(n_q):
+                top = o.select_top_kappa(ref["m"][r:r + 1], int(cnt[0, h, r]))
+                top["m"] = ref["m"][r:r + 1]
+                assert mask_report(gpu_mask[0, h, r:r + 1], top)[0] == 0, (mode, G, h, r)
+                assert np.array_equal(np.flatnonzero(gpu_mask[0, h, r]), cols[r, :cnt[0, h, r]])
+            lists = [cols[r, :cnt[0, h, r]] for r in range(n_q)]
+            O_ref = o.sparse_attention(np64(Q[0, h]), np64(K[0, h // group]), np64(V[0, h // group]),
+                                       sel.perm_q[0, h].cpu().numpy(), sel.perm_k[0, h // group].cpu().numpy(),
+                                       lists, w.block)
+            check_output(np64(out[0, h]), O_ref, w.dtype == "bf16", f"budget {G} head {h}")
+    if mode == "mass":
+        assert asked.min() < asked.max(), "rows should ask for different numbers of blocks on this input"
+
+
 # ------------------------------------------------------------------ attention
 def _oracle_attention(Q, K, V, h, sel, block):
     hk = h // (Q.shape[1] // K.shape[1])
