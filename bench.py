@@ -145,7 +145,9 @@ def fidelity_report(w, Q, K, sparsities):
     of norm sorting and covariance compensation, on this workload's synthetic tensors."""
     dev = Q.device
     rows = []
-    variants = [(bd.SORT_NONE, "none", None), (bd.SORT_QK, "QK", None)]
+    # the four sort modes of the paper's ablation (Tab. 7), plus a per-segment sort where the
+    # workload has segments
+    variants = [(bd.SORT_NONE, "none", None), (bd.SORT_Q, "Q", None), (bd.SORT_K, "K", None), (bd.SORT_QK, "QK", None)]
     if synth.segments_of(w) is not None:
         variants.append((bd.SORT_QK, "QK per segment", synth.segments_of(w)))
     for sort, sort_name, segments in variants:
