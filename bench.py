@@ -32,7 +32,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # plain-copy calibration (profiles/attn_and_select_cfg4_s50.md); only valid for the workload it names.
-MEASURED_TRAFFIC_BYTES = {("cfg4_dlm_128k", 0.5): 35.7e9}
+MEASURED_TRAFFIC_BYTES = {("cfg4_dlm_128k", 0.5): 36.4e9}
 # the same for all kernels of basa_select together (one key + tile-sort launch, five merge passes,
 # pooling, score map, row selection), from the same profile
 MEASURED_SELECT_TRAFFIC_BYTES = {("cfg4_dlm_128k", 0.5): 5.77e9}
