@@ -411,3 +411,25 @@ def test_variable_length_batch_packed_token_major():
     # an empty sequence in the list is skipped
     out2 = bd.ba_att_varlen(q, k, v, [0, 700, 700, 701, 2034], block, 0.5)
     assert torch.equal(out, out2)
+
+
+def test_two_runs_give_identical_bits():
+    """Nothing on the path depends on the order in which workgroups finish: two runs of selection
+    (fixed count, cumulative mass with a total budget, segments) and attention agree bit for bit."""
+    H, L, B, d = 8, 32768 + 50, 128, 128
+    Q, K, V = (_randn((1, H, L, d), 990 + i, torch.bfloat16) for i in range(3))
+    for kw in (dict(), dict(mass_target=0.9, min_keep=2, budget_total=40000), dict(segments=[0, 5000, 20001])):
+        runs = []
+        for _ in range(2):
+            sel = bd.basa_select(Q, K, B, 0.5, want_scores=True, **kw)
+            out, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, B, sel.perm_q, sel.perm_k, want_lse=True)
+            torch.cuda.synchronize()
+            runs.append((sel, out, lse))
+        (s0, o0, l0), (s1, o1, l1) = runs
+        for name in ("perm_q", "perm_k", "mask_bits", "row_count", "row_mass", "scores"):
+            assert torch.equal(getattr(s0, name), getattr(s1, name)), (kw, name)
+        # list entries past a row's count are not written: compare the counted part
+        cnt = s0.row_count[..., None]
+        live = torch.arange(s0.row_cols.shape[-1], device=DEV) < cnt
+        assert torch.equal(s0.row_cols * live, s1.row_cols * live), kw
+        assert torch.equal(o0, o1) and torch.equal(l0, l1), kw
