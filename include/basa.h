@@ -76,8 +76,8 @@ typedef struct {
   int32_t attn_shape;        /* basa_sparse_attn, bf16 only: shape of the attention workgroup.
                               * 0 = chosen by the library (on the device, from how much the
                               * lists of neighbouring query blocks overlap), 1 = 256 queries
-                              * sharing every K/V tile, 2 = 128 queries.  Same results up to
-                              * fp32 summation order; other entry points ignore it.         */
+                              * sharing every K/V tile, 2 = 128 queries.  The shapes give
+                              * identical results; other entry points ignore it.            */
   int32_t n_segments;        /* 0: none.  1..BASA_MAX_SEGMENTS: the sort is segment-aware (the
                                 windowed sort of Alg. 1 step 1 with runs of unequal length, e.g.
                                 one run per modality or frame): tokens segment_starts[j] ..

@@ -131,3 +131,29 @@ def test_workspace_sizes(lib):
     assert (2 + 2) * 1024 * 128 * 2 <= att <= (2 + 2) * 1024 * 128 * 2 + 1024
     assert sel >= 2 * 4 * 1000 * 8
     assert lib.basa_select_workspace_size(C.byref(fake_tensor(d=96)), C.byref(k), C.byref(p)) == 0
+
+
+def test_struct_layouts_match_the_c_header(tmp_path):
+    """The ctypes structures of the binding against the header as a C compiler lays it out."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    fields = {"basa_tensor": [f for f, _ in bd.BasaTensor._fields_], "basa_params": [f for f, _ in bd.BasaParams._fields_]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "basa.h"', 'int main(void) {']
+    for st, fl in fields.items():
+        lines.append(f'  printf("{st} %zu\\n", sizeof({st}));')
+        for f in fl:
+            lines.append(f'  printf("{st}.{f} %zu\\n", offsetof({st}, {f}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for st, cls in (("basa_tensor", bd.BasaTensor), ("basa_params", bd.BasaParams)):
+        assert int(got[st]) == C.sizeof(cls), st
+        for f, _ in cls._fields_:
+            assert int(got[f"{st}.{f}"]) == getattr(cls, f).offset, f"{st}.{f}"
