@@ -581,6 +581,105 @@ def test_selection_fidelity_limits():
     assert np.abs(zero).max() == 0.0
 
 
+# ---------------------------------------------------------------- value pins of the diagnostics (Eq. 3, Eq. 7-8, l1)
+def test_block_radius_and_max_norm_closed_form():
+    # Eq. 7 on blocks built from known points.  Block 0: {c, c + 2e1, c - 2e1} (mean c, every
+    # deviation 0 or 2, so R = 2; norms |c|, |c + 2e1|, |c - 2e1|).  Block 1: a 3-4-0 triangle
+    # {(0,0,0), (3,0,0), (0,4,0)}: mean (1, 4/3, 0), the farthest token from it is (0,4,0).
+    c = np.array([1.0, -2.0, 0.5])
+    e1 = np.array([1.0, 0.0, 0.0])
+    x = np.stack([c, c + 2 * e1, c - 2 * e1, np.zeros(3), np.array([3.0, 0, 0]), np.array([0, 4.0, 0])])
+    R, M = o.block_norm_metrics(x, 3)
+    assert abs(R[0] - 2.0) < 1e-15
+    assert abs(M[0] - math.sqrt(9.0 + 4.0 + 0.25)) < 1e-15               # |c + 2e1| = |(3, -2, 0.5)|
+    assert abs(R[1] - math.sqrt(1.0 + (8.0 / 3.0) ** 2)) < 1e-15
+    assert abs(M[1] - 4.0) < 1e-15
+    # the values that plausible wrong definitions would give on block 1, all different from R, M
+    rms = math.sqrt((1 + 16 / 9.0 + 4 + 16 / 9.0 + 1 + 64 / 9.0) / 3.0)
+    for wrong in (rms, 2 * R[1], 1.0 + 8.0 / 3.0):                         # RMS radius, diameter-like, l1 radius
+        assert abs(R[1] - wrong) > 0.1
+    for wrong in (7.0 / 3.0, math.sqrt(1.0 + 16.0 / 9.0)):                 # mean norm, norm of the mean
+        assert abs(M[1] - wrong) > 0.1
+
+
+def test_block_norm_metrics_and_bound_by_python_loops():
+    L_q, L_k, B, d = 23, 18, 5, 4                                          # ragged last blocks: 3 and 3 tokens
+    Q, K = rand(L_q, d, 1.4) + 0.3, rand(L_k, d, 0.7) - 0.2
+
+    def loops(x):
+        L = x.shape[0]
+        R, M = [], []
+        for g in range((L + B - 1) // B):
+            idx = range(g * B, min((g + 1) * B, L))
+            mean = [sum(x[i, t] for i in idx) / len(idx) for t in range(d)]
+            R.append(max(math.sqrt(sum((x[i, t] - mean[t]) ** 2 for t in range(d))) for i in idx))
+            M.append(max(math.sqrt(sum(x[i, t] ** 2 for t in range(d))) for i in idx))
+        return R, M
+
+    Rq, Mq = o.block_norm_metrics(Q, B)
+    Rk, Mk = o.block_norm_metrics(K, B)
+    wRq, wMq = loops(Q)
+    wRk, wMk = loops(K)
+    for got, want in ((Rq, wRq), (Mq, wMq), (Rk, wRk), (Mk, wMk)):
+        assert len(got) == len(want)
+        for a, b in zip(got, want):
+            assert abs(a - b) < 1e-14
+    U = o.deviation_bound(Q, K, B)
+    assert U.shape == (5, 4)
+    for a in range(5):
+        for b in range(4):
+            want = (wRq[a] * wMk[b] + wMq[a] * wRk[b] + wRq[a] * wRk[b]) / math.sqrt(d)      # Eq. 8
+            assert abs(U[a, b] - want) < 1e-13
+    # closed form: blocks {+a, -a} along one axis have mean 0 and R = M = |a|, so U = 3 |a|^2 / sqrt(d)
+    a = np.array([[2.0, 0.0], [-2.0, 0.0]])
+    assert abs(o.deviation_bound(a, a, 2)[0, 0] - 3 * 4.0 / math.sqrt(2)) < 1e-14
+
+
+def test_selection_fidelity_l1_and_recall_by_hand():
+    m = np.array([[0.7, 0.3], [0.25, 0.75]])
+    m_hat = np.array([[0.4, 0.6], [0.5, 0.5]])
+    mask = np.array([[True, False], [False, True]])
+    recall, l1 = o.selection_fidelity(m, mask, m_hat)
+    assert abs(l1[0] - 0.6) < 1e-15 and abs(l1[1] - 0.5) < 1e-15           # |.3| + |.3| ; |.25| + |.25|
+    assert abs(recall[0] - 0.4) < 1e-15 and abs(recall[1] - 0.5) < 1e-15
+    # against explicit loops on a ragged random case (the sum of abs differs from their max)
+    Q, K = rand(29, 3), rand(26, 3)
+    sel = o.select(Q, K, 4, 0.5, sort=o.SORT_NONE)
+    mh = o.oracle_block_mass(Q, K, 4)
+    recall, l1 = o.selection_fidelity(sel["m"], sel["mask"], mh)
+    for r in range(mh.shape[0]):
+        want = 0.0
+        for c in range(mh.shape[1]):
+            want += abs(sel["m"][r, c] - mh[r, c])
+        assert abs(l1[r] - want) < 1e-14
+        assert l1[r] > np.abs(sel["m"][r] - mh[r]).max() + 1e-6
+        assert abs(recall[r] - sum(mh[r, c] for c in range(mh.shape[1]) if sel["mask"][r, c])) < 1e-15
+
+
+def test_oracle_block_mass_ragged_blocks_by_python_loops():
+    # Eq. 3 with ragged last query AND key blocks: the mean is over the rows the block HAS
+    L_q, L_k, B, d = 11, 14, 4, 3                                          # last blocks: 3 queries, 2 keys
+    Q, K = rand(L_q, d, 1.2), rand(L_k, d, 0.9)
+    A = [[0.0] * L_k for _ in range(L_q)]
+    for i in range(L_q):
+        logit = [sum(Q[i, t] * K[j, t] for t in range(d)) / math.sqrt(d) for j in range(L_k)]
+        mx = max(logit)
+        e = [math.exp(v - mx) for v in logit]
+        z = sum(e)
+        A[i] = [v / z for v in e]
+    m_hat = o.oracle_block_mass(Q, K, B)
+    assert m_hat.shape == (3, 4)
+    for gq in range(3):
+        rows = range(gq * B, min((gq + 1) * B, L_q))
+        for gk in range(4):
+            cols = range(gk * B, min((gk + 1) * B, L_k))
+            want = sum(A[i][j] for i in rows for j in cols) / len(rows)
+            assert abs(m_hat[gq, gk] - want) < 1e-14
+        assert abs(sum(m_hat[gq]) - 1.0) < 1e-13                           # every row is a distribution
+    # dividing the ragged row by B instead of its 3 rows would give 3/4
+    assert abs(m_hat[2].sum() - 0.75) > 0.2
+
+
 # ---------------------------------------------------------------- drift guard (no paper values: see the script's header)
 def test_oracle_reproduces_its_stored_tiny_results():
     import importlib.util
