@@ -121,6 +121,27 @@ basa_status basa_norm_sort(const basa_tensor* x, const basa_params* p, int32_t* 
                            float* keys_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * basa_norm_sort for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs and results as basa_norm_sort; the two buffers of packed sort words live in a device
+ * array of BASA_STATIC_SCRATCH_BYTES that is part of the library image (every GPU the library
+ * runs on holds one copy until the process ends).  The call allocates and frees nothing, creates
+ * no events (the basa_profile_* timing aid does not see it) and does not synchronise.
+ *   - batch * heads * L above BASA_STATIC_SCRATCH_BYTES / 16 tokens (2 Mi with the default size):
+ *     BASA_ERR_WORKSPACE, nothing enqueued.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams,
+ *     two threads) race; serialise them.  Nothing has to start at zero, so no clearing is done.
+ *   - The array's address is resolved once per device, at the first call made with that device
+ *     current, or by basa_static_init(); a caller that records a graph calls basa_static_init()
+ *     before the capture begins.
+ */
+#define BASA_STATIC_SCRATCH_BYTES (32u << 20)
+size_t basa_static_scratch_size(void);
+basa_status basa_static_init(void);
+basa_status basa_norm_sort_static(const basa_tensor* x, const basa_params* p, int32_t* perm,
+                                  float* keys_out, void* stream);
+
+/*
  * Block pooling (Sec. 3.1 mean pooling; Sec. 3.4 "blockwise first/second moments";
  * Alg. 1 steps 3-4): per block of the ordered sequence x[perm], the mean and the
  * per-dimension population variance (divide by the block's token count).

@@ -28,6 +28,7 @@ EXPORTS = (
     "basa_version", "basa_profile_enable", "basa_profile_kernel_count", "basa_profile_kernel_name",
     "basa_profile_read", "basa_calibrate_mfma", "basa_calibrate_read", "basa_block_mass_workspace_size", "basa_block_mass",
     "basa_block_radius", "basa_deviation_bound", "basa_selection_fidelity", "basa_pearson_sums",
+    "basa_static_scratch_size", "basa_static_init", "basa_norm_sort_static",
 )
 
 
@@ -75,6 +76,12 @@ def load():
     lib.basa_sort_workspace_size.argtypes = [T, P]
     lib.basa_norm_sort.restype = C.c_int
     lib.basa_norm_sort.argtypes = [T, P, V, V, V, C.c_size_t, V]
+    lib.basa_static_scratch_size.restype = C.c_size_t
+    lib.basa_static_scratch_size.argtypes = []
+    lib.basa_static_init.restype = C.c_int
+    lib.basa_static_init.argtypes = []
+    lib.basa_norm_sort_static.restype = C.c_int
+    lib.basa_norm_sort_static.argtypes = [T, P, V, V, V]
     lib.basa_downsample.restype = C.c_int
     lib.basa_downsample.argtypes = [T, V, P, V, V, V]
     lib.basa_select.restype = C.c_int
@@ -191,6 +198,22 @@ def basa_norm_sort(x: torch.Tensor, block: int, window: int = 0, return_keys: bo
     _check(lib.basa_norm_sort(C.byref(xd), C.byref(p), _ptr(perm), _ptr(keys), _ptr(ws),
                               ws.numel(), _stream(x)))
     return (perm, keys) if return_keys else perm
+
+
+def basa_static_scratch_size() -> int:
+    return int(load().basa_static_scratch_size())
+
+
+def basa_static_init():
+    _check(load().basa_static_init())
+
+
+def basa_norm_sort_static(x: torch.Tensor, block: int, perm: torch.Tensor, window: int = 0,
+                          keys: Optional[torch.Tensor] = None, segments=None):
+    """basa_norm_sort on the library's static scratch; `perm` (and `keys`) are caller buffers, nothing is allocated."""
+    xd, p = tensor_desc(x), params(block, window=window, segments=segments)
+    _check(load().basa_norm_sort_static(C.byref(xd), C.byref(p), _ptr(perm), _ptr(keys), _stream(x)))
+    return perm
 
 
 def basa_downsample(x: torch.Tensor, block: int, perm: Optional[torch.Tensor] = None,

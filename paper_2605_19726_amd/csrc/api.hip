@@ -29,6 +29,7 @@ namespace {
 struct ProfRec { int id; hipEvent_t start, stop; };
 std::mutex g_prof_mu;
 bool g_prof_on = false;
+thread_local bool t_prof_off = false;      // set around calls that must not create events
 std::vector<ProfRec> g_prof_recs;
 const char* const kKernelNames[K_COUNT] = {
     "norm_tile_sort_kernel", "merge_pass_kernel", "block_stats_kernel",
@@ -38,7 +39,7 @@ const char* const kKernelNames[K_COUNT] = {
 
 ProfScope::ProfScope(int id, hipStream_t st) : slot_(-1), st_(st) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  if (!g_prof_on) return;
+  if (!g_prof_on || t_prof_off) return;
   ProfRec r;
   r.id = id;
   if (hipEventCreate(&r.start) != hipSuccess) return;
@@ -368,6 +369,79 @@ basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const ba
   if ((s = check_params(p, false)) != BASA_OK) return s;
   return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 1, out, out_strides, lse, ws, ws_bytes, stream);
 }
+
+
+}  // extern "C"
+
+// ---- the entry point that allocates nothing ------------------------------------------------
+// Scratch of the norm ranking (the two buffers of packed sort words) as a device array owned by
+// the library image: every GPU the library runs on holds its own copy, at its own address, until
+// the process ends.  `scratch` is a host-side stand-in for that array, never a device address:
+// host code uses the pointer that hipGetSymbolAddress returned for the current device.
+namespace basa {
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)BASA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};      // per device, resolved at the first use on that device
+
+basa_status static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d outside [0, %d)", dev, kMaxDevices); return BASA_ERR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(static scratch)");
+    if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256) { set_error("static scratch resolved to a misaligned address"); return BASA_ERR_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return BASA_OK;
+}
+}  // namespace
+}  // namespace basa
+
+extern "C" {
+
+size_t basa_static_scratch_size(void) { return kStaticScratchBytes; }
+
+basa_status basa_static_init(void) {
+  void* ptr = nullptr;
+  return static_scratch_of_current_device(&ptr);
+}
+
+basa_status basa_norm_sort_static(const basa_tensor* x, const basa_params* p, int32_t* perm, float* keys_out,
+                                  void* stream) {
+  basa_status s;
+  if ((s = check_tensor(x, "x")) != BASA_OK) return s;
+  if ((s = check_params(p, false)) != BASA_OK) return s;
+  if (!perm) { set_error("null perm output"); return BASA_ERR_INVALID_ARG; }
+  SegList segs;
+  if ((s = seg_list(p, x->L, &segs)) != BASA_OK) return s;
+  if (x->L > kMaxSortLen) { set_error("sequences beyond %d tokens not supported", kMaxSortLen); return BASA_ERR_UNSUPPORTED; }
+  const size_t need = sort_workspace_bytes(x->batch * x->heads, x->L);
+  if (need > kStaticScratchBytes) {
+    set_error("basa_norm_sort_static: batch*heads*L = %lld tokens need %zu bytes of scratch, the static array holds %zu "
+              "(at most %zu tokens); use basa_norm_sort with a caller workspace",
+              (long long)x->batch * x->heads * x->L, need, kStaticScratchBytes, kStaticScratchBytes / 16);
+    return BASA_ERR_WORKSPACE;
+  }
+  void* ptr = nullptr;
+  if ((s = static_scratch_of_current_device(&ptr)) != BASA_OK) return s;
+  // nothing in the scratch has to start at zero: the tile pass writes every word the merges read
+  t_prof_off = true;                       // the timing aid creates events; this call creates nothing
+  s = launch_norm_sort(view_of(*x), p->window, segs, perm, keys_out, ptr, reinterpret_cast<hipStream_t>(stream));
+  t_prof_off = false;
+  return s;
+}
+
+}  // extern "C"
+
+extern "C" {
 
 const char* basa_status_string(basa_status s) {
   switch (s) {

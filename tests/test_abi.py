@@ -157,3 +157,15 @@ def test_struct_layouts_match_the_c_header(tmp_path):
         assert int(got[st]) == C.sizeof(cls), st
         for f, _ in cls._fields_:
             assert int(got[f"{st}.{f}"]) == getattr(cls, f).offset, f"{st}.{f}"
+
+
+def test_static_norm_sort_validation_without_a_launch(lib):
+    # the size check comes before the scratch address is resolved, so no GPU is needed
+    assert lib.basa_static_scratch_size() == 32 << 20
+    p = bd.params(128)
+    call = lambda x_, perm=C.c_void_p(0x2000): status_of(lib, lib.basa_norm_sort_static, C.byref(x_), C.byref(p),
+                                                          perm, None, None)
+    assert call(fake_tensor(ptr=0))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(fake_tensor(), perm=None)[0] == "BASA_ERR_INVALID_ARG"
+    name, why = call(fake_tensor(heads=33, L=1 << 16))                    # 33 * 65536 tokens > 2 Mi
+    assert name == "BASA_ERR_WORKSPACE" and "static array holds" in why
