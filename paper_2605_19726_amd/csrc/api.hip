@@ -356,7 +356,7 @@ basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const b
   if ((s = check_params(p, false)) != BASA_OK) return s;
   if (row_cols && !row_count) { set_error("row_cols given without row_count"); return BASA_ERR_INVALID_ARG; }
   if (row_cols && cols_stride < 1) { set_error("cols_stride must be >= 1"); return BASA_ERR_INVALID_ARG; }
-  if (p->attn_shape < 0 || p->attn_shape > 2) { set_error("attn_shape must be 0, 1 or 2"); return BASA_ERR_INVALID_ARG; }
+  if (p->attn_shape < 0 || p->attn_shape > 3) { set_error("attn_shape must be 0, 1, 2 or 3"); return BASA_ERR_INVALID_ARG; }
   return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, out,
                      out_strides, lse, ws, ws_bytes, stream);
 }
@@ -367,7 +367,7 @@ basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const ba
   basa_status s;
   if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
-  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 1, out, out_strides, lse, ws, ws_bytes, stream);
+  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 3, out, out_strides, lse, ws, ws_bytes, stream);
 }
 
 

@@ -35,6 +35,8 @@
 // query's tile max exceeds its running max by more than 2^8, so the common iteration
 // touches O only through MFMA.  K/V tiles go through a 4-stage LDS ring used as two slots of
 // two tiles: one pair is computed while the next pair lands; one workgroup barrier per pair.
+#include <algorithm>
+#include <type_traits>
 #include "common.hpp"
 
 namespace basa {
@@ -46,13 +48,19 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTileKeys = 64;
+#ifndef BASA_ATTN_QR
+#define BASA_ATTN_QR 7
+#endif
 constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
 // Two shapes of workgroup.  SHARED: 8 waves own 256 queries = two (four) neighbouring query blocks
 // that share every K/V tile; best when their lists overlap, which they do for the full method.
 // SOLO: 4 waves own 128 queries = one query block of 128 (two of 64), two workgroups per compute
 // unit; every tile is fetched per 128 queries, but no wave ever waits for a tile that only its
 // neighbour lists - best when neighbouring lists have little in common.
-constexpr int kSharedQueries = 256, kSoloQueries = 128;
+constexpr int kSharedQueries = 256, kSoloQueries = 128, kWideQueries = 512;
+#ifndef BASA_ATTN_DEFAULT_LISTS
+#define BASA_ATTN_DEFAULT_LISTS 3      // shape taken for block lists the overlap probe does not cover
+#endif
 
 // Sizes that follow from the head dimension D.
 template <int D>
@@ -65,8 +73,16 @@ struct Geo {
   static constexpr int kDBlocks = D / 32;                    // 32-row blocks of O^T
   static constexpr int kChunksPerTile = kTileBytes / 1024;   // 1 KB direct-to-LDS loads per K (or V^T) tile
 };
-// Ring stages of a workgroup shape: SHARED walks tiles in pairs (two slots of two), SOLO one by one.
-constexpr int stages_of(int wg_queries) { return wg_queries == kSharedQueries ? 4 : 2; }
+// Ring stages of a workgroup: one of 512 threads has the compute unit to itself and walks tiles in
+// pairs (two slots of two); two workgroups of 256 threads share a compute unit and walk one by one.
+// With 64 queries per wave a tile keeps the workgroup busy twice as long, and one tile of prefetch
+// distance (two stages) covers the load.
+#ifndef BASA_ATTN_ST64
+#define BASA_ATTN_ST64 2
+#endif
+constexpr int stages_of(int threads, int qpw) { return threads == 512 ? (qpw == 32 ? 4 : BASA_ATTN_ST64) : 2; }
+// k-steps of Q^T a wave of 64 queries keeps in registers (the rest is parked in LDS): all for D = 64
+constexpr int q_reg_steps(int d, int qpw) { return (qpw == 64 && d == 128) ? BASA_ATTN_QR : d / 16; }
 
 // ---------------------------------------------------------------------------------
 // Gather kernels
@@ -230,36 +246,172 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
   }
 }
 
+// LDS byte address of a pointer into the workgroup's shared memory, and a 16-byte fragment read at one.
+typedef const __attribute__((address_space(3))) char* lds_cptr_t;
+typedef const __attribute__((address_space(3))) bf16x8* lds_frag_ptr_t;
+__device__ __forceinline__ uint32_t lds_addr(const char* p) { return (uint32_t)(uintptr_t)(lds_cptr_t)p; }
+__device__ __forceinline__ bf16x8 lds_frag(uint32_t addr) { return *(lds_frag_ptr_t)(uintptr_t)addr; }
+
+// Two query groups per wave (64 queries): the same arithmetic per query, but every K and V^T
+// fragment read from LDS feeds two MFMAs (one per group), and the 64-key tile is walked as two
+// 32-key halves so that only 32 score registers per group pair are live at a time.
+template <int D>
+struct WaveState2 {
+  floatx16 o[2][Geo<D>::kDBlocks];
+  float m_run[2], l_run[2];
+};
+
+// kQR of the k-steps take their Q^T fragments from registers; the others are read back from the
+// wave's lane-private LDS area at `qs` ([group 2][k-step][lane] 16 bytes): O (128 registers) and all
+// of Q (64) would leave the compiler too few of the 256 registers a wave has at two waves per SIMD.
+template <bool kMasked, int D, int kQR>
+__device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&qa)[kQR], const bf16x8 (&qb)[kQR],
+                                              const char* qs, const char* stage, int kaddr0, int vaddr0, float c,
+                                              int nvalid, int h) {
+  constexpr int kQL = Geo<D>::kKSteps - kQR;               // k-steps whose Q^T fragments live in LDS
+  // One LDS address per operand and tile; the k-step (group) is folded in by an xor at the point of
+  // use (ring stages start at multiples of 32 KB, so the xor of bits 5-8 commutes with adding the
+  // stage).  The two bases are opaque to the compiler, which would otherwise keep all twelve xor-ed
+  // addresses in registers for the whole kernel and add the stage offset to each in every tile.
+  uint32_t kbase = lds_addr(stage) + (uint32_t)kaddr0;
+  uint32_t vbase = lds_addr(stage) + (uint32_t)(Geo<D>::kTileBytes + vaddr0);
+  asm volatile("" : "+v"(kbase), "+v"(vbase));
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    if (kMasked && half == 1 && nvalid <= 32) break;        // wave-uniform: no key in the second half
+    // the parked fragments are read again in every half: kept in registers across the halves they
+    // would cost the 16 registers that parking them is meant to free
+    asm volatile("" ::: "memory");
+    floatx16 sa = {0}, sb = {0};
+#pragma unroll
+    for (int s = 0; s < Geo<D>::kKSteps; ++s) {
+      const bf16x8 kf = lds_frag((kbase ^ (uint32_t)(s << 5)) + half * 32 * Geo<D>::kRowBytes);
+      if (s < kQR) {
+        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qa[s < kQR ? s : 0], sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qb[s < kQR ? s : 0], sb, 0, 0, 0);
+      } else {
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(qs + (s - kQR) * 1024);
+        const bf16x8 fb = *reinterpret_cast<const bf16x8*>(qs + (kQL + s - kQR) * 1024);
+        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, fa, sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, fb, sb, 0, 0, 0);
+      }
+    }
+    if (kMasked && nvalid < kTileKeys) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int kk = 32 * half + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (kk >= nvalid) { sa[r] = -INFINITY; sb[r] = -INFINITY; }
+      }
+    }
+    float mxa = max3(sa[0], sa[1], sa[2]), mxb = max3(sb[0], sb[1], sb[2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) { mxa = max3(mxa, sa[r], sa[r + 1]); mxb = max3(mxb, sb[r], sb[r + 1]); }
+    mxa = fmaxf(mxa, sa[15]); mxb = fmaxf(mxb, sb[15]);
+    mxa = fmaxf(mxa, __shfl_xor(mxa, 32)); mxb = fmaxf(mxb, __shfl_xor(mxb, 32));
+    const float mca = mxa * c, mcb = mxb * c;
+    if (__builtin_amdgcn_ballot_w64(mca > st.m_run[0] + kLazyTau || mcb > st.m_run[1] + kLazyTau) != 0) {
+      const float na = fmaxf(st.m_run[0], mca), nb = fmaxf(st.m_run[1], mcb);
+      const float aa = __builtin_amdgcn_exp2f(st.m_run[0] - na), ab = __builtin_amdgcn_exp2f(st.m_run[1] - nb);
+      st.m_run[0] = na; st.m_run[1] = nb;
+      st.l_run[0] *= aa; st.l_run[1] *= ab;
+#pragma unroll
+      for (int i = 0; i < Geo<D>::kDBlocks; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { st.o[0][i][r] *= aa; st.o[1][i][r] *= ab; }
+    }
+    const float ma = st.m_run[0], mb = st.m_run[1];
+    bf16x8 pa[2], pb[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      pa[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sa[r], c, -ma));
+      pb[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sb[r], c, -mb));
+    }
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float la = st.l_run[0], lb = st.l_run[1];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      la = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pa[g], pa[g], 0, 1), ones, la, false);
+      la = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pa[g], pa[g], 2, 3), ones, la, false);
+      la = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pa[g], pa[g], 4, 5), ones, la, false);
+      la = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pa[g], pa[g], 6, 7), ones, la, false);
+      lb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 0, 1), ones, lb, false);
+      lb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 2, 3), ones, lb, false);
+      lb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 4, 5), ones, lb, false);
+      lb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 6, 7), ones, lb, false);
+    }
+    st.l_run[0] = la; st.l_run[1] = lb;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const uint32_t va = vbase ^ (uint32_t)((2 * half + g) << 5);
+#pragma unroll
+      for (int db = 0; db < Geo<D>::kDBlocks; ++db) {
+        const bf16x8 vv = lds_frag(va + db * 32 * 128);
+        st.o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pa[g], st.o[0][db], 0, 0, 0);
+        st.o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pb[g], st.o[1][db], 0, 0, 0);
+      }
+    }
+  }
+}
+
+// State of a wave by number of query groups, with uniform accessors for prologue and epilogue.
+template <int D, int NG> struct StateOf { typedef WaveState<D> type; };
+template <int D> struct StateOf<D, 2> { typedef WaveState2<D> type; };
+template <int D>
+__device__ __forceinline__ void init_state(WaveState<D>& st) {
+#pragma unroll
+  for (int i = 0; i < Geo<D>::kDBlocks; ++i) st.o[i] = floatx16{0};
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+}
+template <int D>
+__device__ __forceinline__ void init_state(WaveState2<D>& st) {
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+#pragma unroll
+    for (int i = 0; i < Geo<D>::kDBlocks; ++i) st.o[r][i] = floatx16{0};
+    st.m_run[r] = -INFINITY;
+    st.l_run[r] = 0.f;
+  }
+}
+template <int D> __device__ __forceinline__ float l_of(const WaveState<D>& st, int) { return st.l_run; }
+template <int D> __device__ __forceinline__ float m_of(const WaveState<D>& st, int) { return st.m_run; }
+template <int D> __device__ __forceinline__ const floatx16& o_of(const WaveState<D>& st, int, int db) { return st.o[db]; }
+template <int D> __device__ __forceinline__ float l_of(const WaveState2<D>& st, int r) { return st.l_run[r]; }
+template <int D> __device__ __forceinline__ float m_of(const WaveState2<D>& st, int r) { return st.m_run[r]; }
+template <int D> __device__ __forceinline__ const floatx16& o_of(const WaveState2<D>& st, int r, int db) { return st.o[r][db]; }
+
 __device__ __forceinline__ int64_t out_off(const MfmaArgs& a, int bhq, int row) {
   const int b = bhq / a.heads_q, hh = bhq - b * a.heads_q;
   return (int64_t)b * a.out_sb + (int64_t)hh * a.out_sh + (int64_t)row * a.out_sl;
 }
 
-// Dynamic LDS: [ring: kStages x 32 KB][seq: Nk words][wave_counts: kWaves words].
+// Dynamic LDS: [ring: kStages x 32 KB][parked Q^T fragments][seq: Nk words][wave_counts: kWaves words].
 // seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
 // this workgroup lists it).  While seq is being built the ring area holds the per-key-block
 // membership flags.
-template <int kB, int D, int kWgQueries>
-__global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 2) void attn_mfma_kernel(MfmaArgs a) {
+template <int kB, int D, int kWgQueries, int kQPW>
+__global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 : 2) void attn_mfma_kernel(MfmaArgs a) {
   using G = Geo<D>;
-  constexpr int kWaves = kWgQueries / 32, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
-  constexpr int kStages = stages_of(kWgQueries);
+  constexpr int kWaves = kWgQueries / kQPW, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
+  constexpr int kNG = kQPW / 32;             // 32-query groups per wave: 1 or 2
+  constexpr int kStages = stages_of(kThreads, kQPW);
+  constexpr int kQR = q_reg_steps(D, kQPW), kQL = G::kKSteps - kQR;
+  constexpr int kQParkBytes = kWaves * kNG * kQL * 1024;
   constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = kStages * kStageBytes;
   constexpr int kLoadsPerWave = 2 * G::kChunksPerTile / kWaves;
   constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4 (SOLO: 1 or 2)
   if (a.probe) {
-    // the other shape of workgroup is launched too; exactly one of the two does the work.  Union of
-    // a pair of lists = both lists - common blocks; SOLO pays about 1.17x per tile, so it wins
-    // when the union exceeds 1.2 lists.
-    const int common = a.probe[0], listed = a.probe[1];
-    const bool little_overlap = 20 * (int64_t)(listed - common) > 12 * (int64_t)listed;
+    // the other shape of workgroup is launched too; exactly one of the two does the work.  A
+    // 512-query workgroup walks the union of its 512 / B lists, a 128-query one its own list at
+    // about 1.16x the time per tile, so it wins when the union exceeds 1.16 average lists.
+    const int uni = a.probe[0], listed = a.probe[1];
+    const bool little_overlap = 100 * (int64_t)uni * (kWideQueries / kB) > 116 * (int64_t)listed;
     if ((int)little_overlap != a.run_if_solo) return;
   }
-  constexpr int WPG = kB / 32;               // waves per query block: 4 or 2
   constexpr int TPB = kB / kTileKeys;        // key tiles per key block: 2 or 1
   extern __shared__ __attribute__((aligned(16))) char smem[];
   uint32_t* flags = reinterpret_cast<uint32_t*>(smem);
-  uint32_t* seq = reinterpret_cast<uint32_t*>(smem + kRingBytes);
+  uint32_t* seq = reinterpret_cast<uint32_t*>(smem + kRingBytes + kQParkBytes);
   uint32_t* wave_counts = seq + a.Nk;
 
   // XCD-aware order: consecutive workgroup ids go round-robin over the 8 XCDs; give each
@@ -271,9 +423,9 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 31, h = lane >> 5;
-  const int grp = wave / WPG;                          // query block of this wave inside the wg
-  const int gq = wg * NQB + grp;                       // may be >= Nq in the last workgroup
+  const int grp = wave * kQPW / kB;                    // query block of this wave inside the wg
   const int nqb = min(NQB, a.Nq - wg * NQB);           // query blocks that exist
+  const int pos0 = wg * kQueriesPerWg + wave * kQPW + li;   // sorted position of this lane's first query (next: +32)
 
   // ---- union of the block lists of this workgroup's query blocks ------------------------
   for (int c = tid; c < a.Nk; c += kThreads) flags[c] = a.row_cols ? 0u : ((1u << nqb) - 1u);
@@ -312,12 +464,14 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
 
   if (n_union == 0) {
     // no valid key block in any list of this workgroup (malformed input): its rows become zeros
-    const int pos = gq * kB + (wave % WPG) * 32 + li;
-    if (gq < a.Nq && pos < a.Lq) {
-      const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-      uint4* op = reinterpret_cast<uint4*>(a.out + out_off(a, bhq, orow));
-      for (int i = 0; i < G::kChunksPerRow / 2; ++i) op[(G::kChunksPerRow / 2) * h + i] = make_uint4(0u, 0u, 0u, 0u);
-      if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
+    for (int r = 0; r < kNG; ++r) {
+      const int pos = pos0 + 32 * r;
+      if (pos < a.Lq) {
+        const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
+        uint4* op = reinterpret_cast<uint4*>(a.out + out_off(a, bhq, orow));
+        for (int i = 0; i < G::kChunksPerRow / 2; ++i) op[(G::kChunksPerRow / 2) * h + i] = make_uint4(0u, 0u, 0u, 0u);
+        if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
+      }
     }
     return;
   }
@@ -358,18 +512,21 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
   if (kStages == 4) issue_tile(tile_of(1), 1);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
-  bf16x8 qf[G::kKSteps];
-  {
+  bf16x8 qf[kNG][kQR];
+  char* qpark = smem + kRingBytes + (wave * kNG * kQL) * 1024 + lane * 16;    // this lane's parked fragments
+#pragma unroll
+  for (int r = 0; r < kNG; ++r) {
     // the query of sorted position qpos, read from the caller's tensor; positions past L_q
     // (padding of the last block, or a query block that does not exist) read row 0 and are never stored
-    const int qpos = min(gq, a.Nq - 1) * kB + (wave % WPG) * 32 + li;
+    const int qpos = pos0 + 32 * r;
     const int qrow = qpos < a.Lq ? perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq) : 0;
     const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q.ptr) +
                                                      (a.q.head_offset(bhq) + (int64_t)qrow * a.q.stride_l) * 2);
 #pragma unroll
     for (int s = 0; s < G::kKSteps; ++s) {
       uint4 t = qp[2 * s + h];
-      qf[s] = *reinterpret_cast<bf16x8*>(&t);
+      if (s < kQR) qf[r][s < kQR ? s : 0] = *reinterpret_cast<bf16x8*>(&t);
+      else *reinterpret_cast<uint4*>(qpark + (r * kQL + s - kQR) * 1024) = t;    // read back by this lane only
     }
   }
   // LDS byte offsets inside a stage.  K: row li (+32 for the second block), chunk 2s+h at
@@ -378,12 +535,26 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
   const int kaddr = li * G::kRowBytes + ((h ^ (li & (G::kChunksPerRow - 1))) << 4);
   const int vaddr = li * 128 + ((h ^ ((li >> 1) & 7)) << 4);
 
-  WaveState<D> st;
-#pragma unroll
-  for (int i = 0; i < G::kDBlocks; ++i) st.o[i] = floatx16{0};
-  st.m_run = -INFINITY;
-  st.l_run = 0.f;
+  typename StateOf<D, kNG>::type st;
+  init_state<D>(st);
   const float c = a.scale_log2e;
+  // one 64-key tile of the ring, for the one or two query groups of this wave
+  auto tile = [&](auto masked, const char* stage, int nvalid) {
+    if constexpr (kNG == 1) process_tile<decltype(masked)::value, D>(st, qf[0], stage, kaddr, vaddr, c, nvalid, h);
+    else {
+      // the lane half is needed by the masking code of the ragged tile only: taken from the thread
+      // index there, it does not occupy a register through the main loop
+      int h2 = 0;
+      if (decltype(masked)::value) {
+        int t2 = threadIdx.x;
+        asm volatile("" : "+v"(t2));
+        h2 = (t2 >> 5) & 1;
+      }
+      process_tile2<decltype(masked)::value, D, kQR>(st, qf[0], qf[kNG - 1], qpark, stage, kaddr, vaddr, c, nvalid, h2);
+    }
+  };
+  constexpr std::false_type kFull{};
+  constexpr std::true_type kRagged{};
   const uint32_t my_bit = 1u << (24 + grp);
 
   // All tiles but the last: never ragged.  The last tile is peeled so that the masking code
@@ -397,7 +568,34 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
   // slot; their loads are issued right after the barrier, which also says that every wave is
   // done with that other slot (pair p-1).  The union entries of later tiles are read from LDS
   // early and turned into scalars late, so their latency hides behind the arithmetic.
-  if constexpr (kStages == 4) {
+  if constexpr (kNG == 2) {
+    // 64 queries per wave: ONE call site for full tiles (a second inlined copy of the tile code
+    // costs the register allocator its footing).  Tiles travel in rounds of R = kStages / 2; the
+    // workgroup meets once per round, and round p + 1 lands in the other half of the ring while
+    // round p is computed.
+    constexpr int R = kStages / 2;
+    uint32_t e_cur = entry_of(0);
+    int t = 0;
+#pragma nounroll
+    for (; t + 1 < n_tiles; ++t) {
+      if (t % R == 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const int half_next = ((t / R) + 1) & 1;
+#pragma unroll
+        for (int j = 0; j < R; ++j) issue_tile(tile_of(t + R + j), half_next * R + j);
+      }
+      const uint32_t raw_n = seq[(t + 1) / TPB];
+      if (e_cur & my_bit) tile(kFull, smem + (((t / R) & 1) * R + t % R) * kStageBytes, kTileKeys);
+      e_cur = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_n);
+    }
+    if (t % R == 0) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
+    const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
+    if (e_cur & my_bit) tile(kRagged, smem + (((t / R) & 1) * R + t % R) * kStageBytes, nvalid);
+  } else if constexpr (kStages == 4) {
   uint32_t e_a = entry_of(0);
   uint32_t e_b = entry_of(min(1, n_tiles - 1));
   int t = 0;
@@ -414,8 +612,8 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
       issue_tile(b1 * TPB + (tf1 % TPB), 2 * slot_next + 1);
     }
     const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
-    if (e_a & my_bit) process_tile<false, D>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
-    if (e_b & my_bit) process_tile<false, D>(st, qf, slot + kStageBytes, kaddr, vaddr, c, kTileKeys, h);
+    if (e_a & my_bit) tile(kFull, slot, kTileKeys);
+    if (e_b & my_bit) tile(kFull, slot + kStageBytes, kTileKeys);
     e_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f0);
     e_b = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f1);
   }
@@ -425,12 +623,12 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
     __syncthreads();
     const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
     if (t + 1 < n_tiles) {
-      if (e_a & my_bit) process_tile<false, D>(st, qf, slot, kaddr, vaddr, c, kTileKeys, h);
+      if (e_a & my_bit) tile(kFull, slot, kTileKeys);
       const int nvalid = a.Lk - ((int)(e_b & 0xffffffu) * TPB + ((t + 1) % TPB)) * kTileKeys;
-      if (e_b & my_bit) process_tile<true, D>(st, qf, slot + kStageBytes, kaddr, vaddr, c, nvalid, h);
+      if (e_b & my_bit) tile(kRagged, slot + kStageBytes, nvalid);
     } else {
       const int nvalid = a.Lk - ((int)(e_a & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
-      if (e_a & my_bit) process_tile<true, D>(st, qf, slot, kaddr, vaddr, c, nvalid, h);
+      if (e_a & my_bit) tile(kRagged, slot, nvalid);
     }
   }
   } else {
@@ -443,92 +641,118 @@ __global__ __launch_bounds__(kWgQueries * 2, kWgQueries == kSharedQueries ? 1 : 
       const uint32_t raw_n = seq[(t + 1) / TPB];
       const uint32_t e_nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_n);
       issue_tile((int)(e_nxt & 0xffffffu) * TPB + ((t + 1) % TPB), (t + 1) & 1);
-      if (e_cur & my_bit) process_tile<false, D>(st, qf, smem + (t & 1) * kStageBytes, kaddr, vaddr, c, kTileKeys, h);
+      if (e_cur & my_bit) tile(kFull, smem + (t & 1) * kStageBytes, kTileKeys);
       e_cur = e_nxt;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
-    if (e_cur & my_bit) process_tile<true, D>(st, qf, smem + (t & 1) * kStageBytes, kaddr, vaddr, c, nvalid, h);
+    if (e_cur & my_bit) tile(kRagged, smem + (t & 1) * kStageBytes, nvalid);
   }
 
   // ---- epilogue: normalise, scatter rows to their original positions
-  const float l_tot = st.l_run + __shfl_xor(st.l_run, 32);
-  const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;    // a query block without any valid key block: zeros
-  const int pos = gq * kB + (wave % WPG) * 32 + li;
-  if (gq < a.Nq && pos < a.Lq) {
-    const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-    __bf16* op = a.out + out_off(a, bhq, orow);
+  // positions and lane halves are rebuilt from the thread index (opaque to the compiler): carried
+  // through the main loop they would take registers that the accumulators and Q^T fragments need
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int h_e = (tid_e >> 5) & 1;
+  const int pos_e = wg * kQueriesPerWg + (tid_e >> 6) * kQPW + (tid_e & 31);
 #pragma unroll
-    for (int db = 0; db < G::kDBlocks; ++db)
+  for (int r = 0; r < kNG; ++r) {
+    const float l_part = l_of(st, r), m_fin = m_of(st, r);
+    const float l_tot = l_part + __shfl_xor(l_part, 32);
+    const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;    // a query block without any valid key block: zeros
+    const int pos = pos_e + 32 * r;
+    const int h = h_e;
+    if (pos < a.Lq) {
+      const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
+      __bf16* op = a.out + out_off(a, bhq, orow);
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        bf16x4 pk;
+      for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(st.o[db][4 * r4 + e] * inv_l);
-        *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * r4 + 4 * h) = pk;
-      }
-    if (a.lse && h == 0)
-      a.lse[(int64_t)bhq * a.Lq + orow] = (st.m_run + __log2f(l_tot)) * 0.6931471805599453f;
+        for (int r4 = 0; r4 < 4; ++r4) {
+          bf16x4 pk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(o_of(st, r, db)[4 * r4 + e] * inv_l);
+          *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * r4 + 4 * h) = pk;
+        }
+      if (a.lse && h == 0)
+        a.lse[(int64_t)bhq * a.Lq + orow] = (m_fin + __log2f(l_tot)) * 0.6931471805599453f;
+    }
   }
 }
 
 size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk * B * d * 2, 256); }
 
 template <int D>
-size_t lds_bytes(int wg_queries, int Nk) {
-  return (size_t)stages_of(wg_queries) * Geo<D>::kStageBytes + (size_t)Nk * 4 + (wg_queries / 32) * 4;
+size_t lds_bytes(int threads, int qpw, int Nk) {
+  const size_t park = (size_t)(threads / 64) * (qpw / 32) * (D / 16 - q_reg_steps(D, qpw)) * 1024;
+  return (size_t)stages_of(threads, qpw) * Geo<D>::kStageBytes + park + (size_t)Nk * 4 + (threads / 64) * 4;
 }
 
-template <int kB, int D, int kWgQueries>
+template <int kB, int D, int kWgQueries, int kQPW>
 basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
-  const size_t lds = lds_bytes<D>(kWgQueries, m.Nk);
+  constexpr int kThreads = kWgQueries / kQPW * 64;
+  const size_t lds = lds_bytes<D>(kThreads, kQPW, m.Nk);
+  // while the union list is built, the per-key-block membership flags live in the ring area
+  if ((size_t)m.Nk * 4 > (size_t)stages_of(kThreads, kQPW) * Geo<D>::kStageBytes) {
+    set_error("attention: %d key blocks exceed the %zu this workgroup shape can list", m.Nk,
+              (size_t)stages_of(kThreads, kQPW) * Geo<D>::kStageBytes / 4);
+    return BASA_ERR_UNSUPPORTED;
+  }
   m.wgs_per_head = ceil_div(m.Nq * kB, kWgQueries);
   m.total_wgs = BHq * m.wgs_per_head;
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries>),
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries, kQPW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
-  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries>), dim3(m.total_wgs), dim3(kWgQueries * 2), lds, st, m);
+  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries, kQPW>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
   BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
   return BASA_OK;
 }
+// dispatch on block size and head dimension
+template <int kWgQueries, int kQPW>
+basa_status launch_shape(const MfmaArgs& m, int B, int d, int BHq, hipStream_t st) {
+  if (d == 128) return B == 128 ? launch_main<128, 128, kWgQueries, kQPW>(m, BHq, st) : launch_main<64, 128, kWgQueries, kQPW>(m, BHq, st);
+  return B == 128 ? launch_main<128, 64, kWgQueries, kQPW>(m, BHq, st) : launch_main<64, 64, kWgQueries, kQPW>(m, BHq, st);
+}
 
-// How much the lists of neighbouring query blocks (2g, 2g+1) have in common, on every 8th pair:
-// probe[0] += blocks in both lists, probe[1] += blocks in the two lists.  One wave per pair: the
-// first list becomes a bitmap in LDS, the entries of the second are looked up in it.
+// How much the lists of the query blocks that would share a 512-query workgroup have in common, on
+// every kProbeStride-th such group of gsz = 512 / B neighbouring blocks: probe[0] += blocks in the
+// union of the group's lists, probe[1] += blocks in its lists.  One wave per group: the lists are
+// or-ed into a bitmap in LDS, whose set bits are the union.
 constexpr int kProbeStride = 8, kProbeMaxBlocks = 8192;
 __global__ __launch_bounds__(256) void list_overlap_kernel(const int32_t* __restrict__ row_count,
                                                            const int32_t* __restrict__ row_cols, int cols_stride,
-                                                           int Nq, int Nk, int pairs_total, int32_t* __restrict__ probe) {
+                                                           int Nq, int Nk, int gsz, int groups_total,
+                                                           int32_t* __restrict__ probe) {
   __shared__ uint32_t bits[4][kProbeMaxBlocks / 32];
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int pair = (blockIdx.x * 4 + wv) * kProbeStride;
-  const bool active = pair < pairs_total;               // no early exit: every wave meets the barriers
-  const int pairs_per_head = Nq / 2;
-  const int bh = active ? pair / pairs_per_head : 0, g = active ? (pair - bh * pairs_per_head) * 2 : 0;
-  const int64_t r0 = (int64_t)bh * Nq + g, r1 = r0 + 1;
-  const int na = active ? max(0, min(row_count[r0], cols_stride)) : 0;
-  const int nb = active ? max(0, min(row_count[r1], cols_stride)) : 0;
-  const int32_t* A = row_cols + r0 * cols_stride;
-  const int32_t* Bv = row_cols + r1 * cols_stride;
+  const int group = (blockIdx.x * 4 + wv) * kProbeStride;
+  const bool active = group < groups_total;             // no early exit: every wave meets the barriers
+  const int groups_per_head = Nq / gsz;
+  const int bh = active ? group / groups_per_head : 0, g0 = active ? (group - bh * groups_per_head) * gsz : 0;
   const unsigned limit = (unsigned)min(Nk, kProbeMaxBlocks);
   for (int w = lane; w < kProbeMaxBlocks / 32; w += 64) bits[wv][w] = 0u;
   __syncthreads();
-  for (int i = lane; i < na; i += 64) {
-    const unsigned v = (unsigned)A[i];
-    if (v < limit) atomicOr(&bits[wv][v >> 5], 1u << (v & 31));
+  int listed = 0;
+  for (int r = 0; r < gsz; ++r) {
+    const int64_t row = (int64_t)bh * Nq + g0 + r;
+    const int n = active ? max(0, min(row_count[row], cols_stride)) : 0;
+    const int32_t* A = row_cols + row * cols_stride;
+    for (int i = lane; i < n; i += 64) {
+      const unsigned v = (unsigned)A[i];
+      if (v < limit) atomicOr(&bits[wv][v >> 5], 1u << (v & 31));
+    }
+    listed += n;
   }
   __syncthreads();
-  int common = 0;
-  for (int i = lane; i < nb; i += 64) {
-    const unsigned v = (unsigned)Bv[i];
-    if (v < limit) common += (bits[wv][v >> 5] >> (v & 31)) & 1u;
-  }
+  int uni = 0;
+  for (int w = lane; w < kProbeMaxBlocks / 32; w += 64) uni += __popc(bits[wv][w]);
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) common += __shfl_xor(common, off);
+  for (int off = 32; off > 0; off >>= 1) uni += __shfl_xor(uni, off);
   if (active && lane == 0) {
-    atomicAdd(&probe[0], common);
-    atomicAdd(&probe[1], na + nb);
+    atomicAdd(&probe[0], uni);
+    atomicAdd(&probe[1], listed);
   }
 }
 __global__ void zero_probe_kernel(int32_t* probe) {
@@ -559,7 +783,9 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   const int Nq = ceil_div(a.q.L, B), Nk = ceil_div(a.k.L, B);
   if (BHq == 0 || Nq == 0) return BASA_OK;
   const int d = a.q.d;
-  const size_t lds = d == 128 ? lds_bytes<128>(kSharedQueries, Nk) : lds_bytes<64>(kSharedQueries, Nk);
+  // the largest LDS request among the shapes that may be launched
+  const size_t lds = d == 128 ? std::max(lds_bytes<128>(512, 32, Nk), lds_bytes<128>(512, 64, Nk))
+                              : std::max(lds_bytes<64>(512, 32, Nk), lds_bytes<64>(512, 64, Nk));
   {
     int dev = 0, max_lds = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -597,29 +823,28 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   // Which shape of workgroup: asked for, or (B = d = 128, block lists given, enough work to pay for
   // three tiny launches) decided on the device from how much neighbouring lists overlap.
   int variant = a.variant;
-  const bool can_probe = a.row_cols != nullptr && B == 128 && d == 128 && Nq >= 8 && (int64_t)BHq * Nq >= 2048;
-  if (variant == 0 && !can_probe) variant = 1;
+  const int gsz = kWideQueries / B;
+  const bool can_probe = a.row_cols != nullptr && Nq >= 2 * gsz && (int64_t)BHq * Nq * B >= 2048 * 128;
+  if (variant == 0 && !can_probe) variant = a.row_cols ? BASA_ATTN_DEFAULT_LISTS : 3;   // no lists: every block shares every tile
   if (variant == 0) {
-    const int pairs_total = BHq * (Nq / 2);
+    const int groups_total = BHq * (Nq / gsz);
     hipLaunchKernelGGL(zero_probe_kernel, dim3(1), dim3(64), 0, st, probe);
     BASA_HIP_CHECK_LAUNCH("zero_probe_kernel");
-    hipLaunchKernelGGL(list_overlap_kernel, dim3(ceil_div(ceil_div(pairs_total, kProbeStride), 4)), dim3(256), 0, st,
-                       a.row_count, a.row_cols, a.cols_stride, Nq, Nk, pairs_total, probe);
+    hipLaunchKernelGGL(list_overlap_kernel, dim3(ceil_div(ceil_div(groups_total, kProbeStride), 4)), dim3(256), 0, st,
+                       a.row_count, a.row_cols, a.cols_stride, Nq, Nk, gsz, groups_total, probe);
     BASA_HIP_CHECK_LAUNCH("list_overlap_kernel");
     m.probe = probe;
   }
   ProfScope prof(K_ATTN, st);
   basa_status s = BASA_OK;
-  if (variant != 2) {
+  if (variant == 1) return launch_shape<kSharedQueries, 32>(m, B, d, BHq, st);
+  if (variant == 0 || variant == 3) {
     m.run_if_solo = 0;
-    if (d == 128) s = B == 128 ? launch_main<128, 128, kSharedQueries>(m, BHq, st) : launch_main<64, 128, kSharedQueries>(m, BHq, st);
-    else s = B == 128 ? launch_main<128, 64, kSharedQueries>(m, BHq, st) : launch_main<64, 64, kSharedQueries>(m, BHq, st);
-    if (s != BASA_OK) return s;
+    if ((s = launch_shape<kWideQueries, 64>(m, B, d, BHq, st)) != BASA_OK) return s;
   }
-  if (variant != 1) {
+  if (variant == 0 || variant == 2) {
     m.run_if_solo = 1;
-    if (d == 128) s = B == 128 ? launch_main<128, 128, kSoloQueries>(m, BHq, st) : launch_main<64, 128, kSoloQueries>(m, BHq, st);
-    else s = B == 128 ? launch_main<128, 64, kSoloQueries>(m, BHq, st) : launch_main<64, 64, kSoloQueries>(m, BHq, st);
+    s = launch_shape<kSoloQueries, 32>(m, B, d, BHq, st);
   }
   return s;
 }

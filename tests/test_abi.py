@@ -112,7 +112,7 @@ def test_attention_argument_validation(lib):
     assert call(q, k, v, out=None)[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, v, out=C.c_void_p(0x2004))[0] == "BASA_ERR_INVALID_ARG"            # misaligned
     assert call(q, k, v)[0] == "BASA_ERR_WORKSPACE"
-    for bad in (-1, 3):
+    for bad in (-1, 4):
         assert call(q, k, v, wsb=1 << 40, p_=bd.params(128, attn_shape=bad))[0] == "BASA_ERR_INVALID_ARG"
     # output strides: token-major is fine (and reaches the workspace check), the rest is refused
     assert call(q, k, v, ostr=strides(256 * 2 * 128, 128, 2 * 128))[0] == "BASA_ERR_WORKSPACE"

@@ -51,7 +51,7 @@ def test_random_case(i):
     sel = bd.basa_select(Q, K, B, c["s"], c["beta"], c["sort"], c["window"], want_scores=True,
                          mass_target=c["mass"], min_keep=c["min_keep"], segments=c["segments"])
     out, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, B, sel.perm_q, sel.perm_k, want_lse=True,
-                                    attn_shape=i % 3)
+                                    attn_shape=i % 4)
     torch.cuda.synchronize()
     gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
     group = c["hq"] // c["hk"]
