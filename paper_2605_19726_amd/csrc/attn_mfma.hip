@@ -307,6 +307,7 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
 #pragma unroll
     for (int r = 3; r < 15; r += 2) { mxa = max3(mxa, sa[r], sa[r + 1]); mxb = max3(mxb, sb[r], sb[r + 1]); }
     mxa = fmaxf(mxa, sa[15]); mxb = fmaxf(mxb, sb[15]);
+    // (exchanging the halves with v_permlane32_swap instead of the LDS permute measured 1 % slower)
     mxa = fmaxf(mxa, __shfl_xor(mxa, 32)); mxb = fmaxf(mxb, __shfl_xor(mxb, 32));
     const float mca = mxa * c, mcb = mxb * c;
     if (__builtin_amdgcn_ballot_w64(mca > st.m_run[0] + kLazyTau || mcb > st.m_run[1] + kLazyTau) != 0) {
