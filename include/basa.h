@@ -100,7 +100,8 @@ typedef struct {
  * sparsity s, by the formula above.  Returns -1 if s is outside [0,1) or n_k < 1. */
 int32_t basa_kappa(int32_t n_k, double sparsity);
 
-/* Bytes of workspace basa_select needs for these shapes (0 on invalid arguments). */
+/* Bytes of workspace basa_select needs for these shapes (0 on invalid arguments).  Each stage has
+ * its own size call, so that a caller who runs one stage does not reserve the others' scratch. */
 size_t basa_select_workspace_size(const basa_tensor* q, const basa_tensor* k, const basa_params* p);
 /* Bytes of workspace basa_sparse_attn / basa_dense_attn need (0 on invalid arguments). */
 size_t basa_attn_workspace_size(const basa_tensor* q, const basa_tensor* k, const basa_params* p);
@@ -145,12 +146,15 @@ basa_status basa_norm_sort_static(const basa_tensor* x, const basa_params* p, in
  * Block pooling (Sec. 3.1 mean pooling; Sec. 3.4 "blockwise first/second moments";
  * Alg. 1 steps 3-4): per block of the ordered sequence x[perm], the mean and the
  * per-dimension population variance (divide by the block's token count).
- *   perm   nullable [batch, heads, L] int32; NULL = original order.
- *   mean   out [batch, heads, N, d] float.
- *   var    out, nullable, [batch, heads, N, d] float.
+ *   perm      nullable [batch, heads, L] int32; NULL = original order.
+ *   mean      out [batch, heads, N, d] float.
+ *   var       out, nullable, [batch, heads, N, d] float.
+ *   x_sorted  out, nullable: the ordered sequence itself, x_sorted[b, h, i, :] = x[b, h, perm[i], :],
+ *             contiguous [batch, heads, L, d] in the dtype of x, 16-byte aligned, not aliasing x
+ *             (the pooling pass holds every row anyway; materialising it costs the write only).
  */
 basa_status basa_downsample(const basa_tensor* x, const int32_t* perm, const basa_params* p,
-                            float* mean, float* var, void* stream);
+                            float* mean, float* var, void* x_sorted, void* stream);
 
 /*
  * Block selection (Alg. 1 steps 1-11): norm ranking of Q and/or K (p->sort), block
@@ -251,7 +255,7 @@ basa_status basa_profile_read(double* total_ms /*host*/, int32_t* launches /*hos
  *                Sec. 3.2 bounds by U (Eq. 8) and Fig. 2 correlates with it.
  *   lse          out, nullable, [batch, heads_q, L_q] float, original token order:
  *                log-sum-exp of every query's scaled logits over all keys.
- *   ws           workspace of basa_block_mass_workspace_size() bytes.
+ *   ws           workspace of basa_block_mass_workspace_size() bytes (0 on invalid arguments).
  */
 size_t basa_block_mass_workspace_size(const basa_tensor* q, const basa_tensor* k);
 basa_status basa_block_mass(const basa_tensor* q, const basa_tensor* k, const int32_t* perm_q,

@@ -83,7 +83,7 @@ def load():
     lib.basa_norm_sort_static.restype = C.c_int
     lib.basa_norm_sort_static.argtypes = [T, P, V, V, V]
     lib.basa_downsample.restype = C.c_int
-    lib.basa_downsample.argtypes = [T, V, P, V, V, V]
+    lib.basa_downsample.argtypes = [T, V, P, V, V, V, V]
     lib.basa_select.restype = C.c_int
     lib.basa_select.argtypes = [T, T, P, V, V, V, V, V, V, V, V, C.c_size_t, V]
     lib.basa_sparse_attn.restype = C.c_int
@@ -217,15 +217,17 @@ def basa_norm_sort_static(x: torch.Tensor, block: int, perm: torch.Tensor, windo
 
 
 def basa_downsample(x: torch.Tensor, block: int, perm: Optional[torch.Tensor] = None,
-                    want_var: bool = True):
+                    want_var: bool = True, want_sorted: bool = False):
+    """(mean, var), or (mean, var, x_sorted) with want_sorted."""
     lib = load()
     xd, p = tensor_desc(x), params(block)
     b, h, L, d = x.shape
     N = n_blocks(L, block)
     mean = torch.empty((b, h, N, d), dtype=torch.float32, device=x.device)
     var = torch.empty((b, h, N, d), dtype=torch.float32, device=x.device) if want_var else None
-    _check(lib.basa_downsample(C.byref(xd), _ptr(perm), C.byref(p), _ptr(mean), _ptr(var), _stream(x)))
-    return mean, var
+    xs = torch.empty((b, h, L, d), dtype=x.dtype, device=x.device) if want_sorted else None
+    _check(lib.basa_downsample(C.byref(xd), _ptr(perm), C.byref(p), _ptr(mean), _ptr(var), _ptr(xs), _stream(x)))
+    return (mean, var, xs) if want_sorted else (mean, var)
 
 
 class Selection:

@@ -267,12 +267,16 @@ basa_status basa_norm_sort(const basa_tensor* x, const basa_params* p, int32_t* 
 }
 
 basa_status basa_downsample(const basa_tensor* x, const int32_t* perm, const basa_params* p, float* mean,
-                            float* var, void* stream) {
+                            float* var, void* x_sorted, void* stream) {
   basa_status s;
   if ((s = check_tensor(x, "x")) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
   if (!mean) { set_error("null mean output"); return BASA_ERR_INVALID_ARG; }
-  return launch_block_stats(view_of(*x), perm, p->block, mean, var, nullptr, 0, 0.f,
+  if (x_sorted && reinterpret_cast<uintptr_t>(x_sorted) % 16) {
+    set_error("x_sorted must be 16-byte aligned"); return BASA_ERR_INVALID_ARG;
+  }
+  if (x_sorted && x_sorted == x->ptr) { set_error("x_sorted must not alias x"); return BASA_ERR_INVALID_ARG; }
+  return launch_block_stats(view_of(*x), perm, p->block, mean, var, nullptr, 0, 0.f, x_sorted,
                             reinterpret_cast<hipStream_t>(stream));
 }
 
@@ -330,8 +334,8 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   if (same_len) {
     if ((s = launch_select_features(qv, pq, featq, kv, pk, featk, B, p->beta, st)) != BASA_OK) return s;
   } else {
-    if ((s = launch_block_stats(qv, pq, B, nullptr, nullptr, featq, 1, p->beta, st)) != BASA_OK) return s;
-    if ((s = launch_block_stats(kv, pk, B, nullptr, nullptr, featk, 0, p->beta, st)) != BASA_OK) return s;
+    if ((s = launch_block_stats(qv, pq, B, nullptr, nullptr, featq, 1, p->beta, nullptr, st)) != BASA_OK) return s;
+    if ((s = launch_block_stats(kv, pk, B, nullptr, nullptr, featk, 0, p->beta, nullptr, st)) != BASA_OK) return s;
   }
   const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
   if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
@@ -491,7 +495,7 @@ basa_status basa_profile_read(double* total_ms, int32_t* launches, int32_t n) {
 const char* basa_version(void) { return "basa 0.1 gfx950"; }
 
 size_t basa_block_mass_workspace_size(const basa_tensor* q, const basa_tensor* k) {
-  if (!q || !k) return 0;
+  if (check_qk(q, k) != BASA_OK) return 0;
   return block_mass_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L);
 }
 

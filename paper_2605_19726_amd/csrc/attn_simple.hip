@@ -2,8 +2,8 @@
 // One thread owns one query of the block: its Q row and output accumulator live in
 // registers, K/V rows of the kept key blocks are gathered through perm_k into LDS
 // 16 keys at a time, softmax is the online (running max / running sum) form.
-// This is the exact-arithmetic path for f32 tensors and the fallback for bf16 shapes
-// the matrix-core kernel does not cover; it is not tuned for speed.
+// This is the exact-arithmetic path for f32 tensors (bf16 tensors always take the matrix-core
+// kernel); it is not tuned for speed.
 #include "common.hpp"
 
 namespace basa {

@@ -78,8 +78,9 @@ basa_status launch_iota_perm(int32_t* perm, int BH, int L, hipStream_t st);
 //              (content depends on `feat_is_query`):
 //              query side (Qbar/sqrt(d), beta*VarQ/d, beta*Qbar^2/d),
 //              key side   (Kbar, Kbar^2+VarK, VarK)
+//   x_sorted : the ordered sequence x[perm] itself, contiguous [BH][L][d] in the dtype of x
 basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
-                               float* var, void* feat, int feat_is_query, float beta,
+                               float* var, void* feat, int feat_is_query, float beta, void* x_sorted,
                                hipStream_t st);
 
 // Selection features of Q (query side) and K (key side), identical L / d / dtype, in one launch.

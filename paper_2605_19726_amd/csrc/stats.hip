@@ -20,6 +20,7 @@ struct StatsJob {
   float* var_out;
   uint16_t* feat_out;        // bf16 parts, [3][3d/8][N][8]
   int feat_is_query;
+  void* sorted_out;          // nullable: the ordered sequence x[perm], contiguous [BH][L][d], dtype of x
 };
 
 constexpr int kGroup = 8;      // consecutive blocks per workgroup
@@ -59,6 +60,7 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
   float* var_out = job.var_out;
   uint16_t* feat_out = job.feat_out;
   const int feat_is_query = job.feat_is_query;
+  uint4* sorted_out = reinterpret_cast<uint4*>(job.sorted_out);
   const int bh = second ? blockIdx.y - BH0 : blockIdx.y;
   const int L = x.L;
   const int N = (L + kB - 1) / kB;
@@ -108,6 +110,14 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
     const int g = g0 + b;
     const int n_valid = min(kB, L - g * kB);
     const float inv_n = 1.0f / (float)n_valid;
+    if (sorted_out) {
+      // the rows are in registers exactly as loaded: the materialised ordered sequence is a copy
+#pragma unroll
+      for (int it = 0; it < ITERS; ++it) {
+        const int pos = g * kB + it * RPI + rig;
+        if (pos < L) sorted_out[((int64_t)bh * L + pos) * LPR + sub] = cur[it];
+      }
+    }
 
     // ---- per wave: mean and centred squares of the rows it holds (two passes over registers,
     // lane exchanges only, so the four waves run through both without meeting)
@@ -271,17 +281,17 @@ static basa_status block_stats_impl(const StatsJob& j0, const StatsJob* j1, int 
 }
 
 basa_status launch_block_stats(const TensorView& x, const int32_t* perm, int B, float* mean,
-                               float* var, void* feat, int feat_is_query, float beta,
+                               float* var, void* feat, int feat_is_query, float beta, void* x_sorted,
                                hipStream_t st) {
-  const StatsJob j{x, perm, mean, var, reinterpret_cast<uint16_t*>(feat), feat_is_query};
+  const StatsJob j{x, perm, mean, var, reinterpret_cast<uint16_t*>(feat), feat_is_query, x_sorted};
   return block_stats_impl(j, nullptr, B, beta, st);
 }
 
 basa_status launch_select_features(const TensorView& q, const int32_t* perm_q, void* feat_q,
                                    const TensorView& k, const int32_t* perm_k, void* feat_k, int B,
                                    float beta, hipStream_t st) {
-  const StatsJob jq{q, perm_q, nullptr, nullptr, reinterpret_cast<uint16_t*>(feat_q), 1};
-  const StatsJob jk{k, perm_k, nullptr, nullptr, reinterpret_cast<uint16_t*>(feat_k), 0};
+  const StatsJob jq{q, perm_q, nullptr, nullptr, reinterpret_cast<uint16_t*>(feat_q), 1, nullptr};
+  const StatsJob jk{k, perm_k, nullptr, nullptr, reinterpret_cast<uint16_t*>(feat_k), 0, nullptr};
   return block_stats_impl(jq, &jk, B, beta, st);
 }
 

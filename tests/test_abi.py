@@ -169,3 +169,19 @@ def test_static_norm_sort_validation_without_a_launch(lib):
     assert call(fake_tensor(), perm=None)[0] == "BASA_ERR_INVALID_ARG"
     name, why = call(fake_tensor(heads=33, L=1 << 16))                    # 33 * 65536 tokens > 2 Mi
     assert name == "BASA_ERR_WORKSPACE" and "static array holds" in why
+
+
+def test_downsample_validation_without_a_launch(lib):
+    p = bd.params(128)
+    x = fake_tensor()
+    V = C.c_void_p
+    call = lambda x_, mean=V(0x2000), xs=None: status_of(lib, lib.basa_downsample, C.byref(x_), None, C.byref(p),
+                                                         mean, None, xs, None)
+    assert call(x, mean=None)[0] == "BASA_ERR_INVALID_ARG"
+    assert call(x, xs=V(0x3004))[0] == "BASA_ERR_INVALID_ARG"             # misaligned x_sorted
+    assert call(x, xs=V(0x1000))[0] == "BASA_ERR_INVALID_ARG"             # x_sorted aliases x
+    assert call(fake_tensor(d=96))[0] == "BASA_ERR_UNSUPPORTED"
+    # a bad descriptor gives no workspace size instead of a number
+    assert lib.basa_block_mass_workspace_size(C.byref(fake_tensor(ptr=0)), C.byref(x)) == 0
+    assert lib.basa_block_mass_workspace_size(C.byref(x), C.byref(fake_tensor(heads=3))) == 0
+    assert lib.basa_block_mass_workspace_size(C.byref(x), C.byref(x)) > 0

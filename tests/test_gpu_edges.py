@@ -440,3 +440,18 @@ def test_two_runs_give_identical_bits():
         live = torch.arange(s0.row_cols.shape[-1], device=DEV) < cnt
         assert torch.equal(s0.row_cols * live, s1.row_cols * live), kw
         assert torch.equal(o0, o1) and torch.equal(l0, l1), kw
+
+
+def test_downsample_x_sorted_from_strided_fp32_and_ragged_input():
+    """x_sorted of a non-contiguous fp32 tensor with a ragged last block and a batch of two: a plain
+    gather, compared with torch indexing bit for bit; the statistics do not change with it."""
+    Bt, H, L, d, block = 2, 3, 64 * 5 + 17, 64, 64
+    big = _randn((Bt, H + 1, L + 3, d), 1234, torch.float32)
+    x = big[:, :H, 2:L + 2]
+    assert not x.is_contiguous()
+    perm = bd.basa_norm_sort(x, block)
+    mean, var, xs = bd.basa_downsample(x, block, perm, want_sorted=True)
+    mean0, var0 = bd.basa_downsample(x, block, perm)
+    want = torch.gather(x, 2, perm.long()[..., None].expand(-1, -1, -1, d))
+    assert xs.is_contiguous() and torch.equal(xs, want)
+    assert torch.equal(mean, mean0) and torch.equal(var, var0)
