@@ -358,6 +358,140 @@ def ba_att(Q, K, V, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT
 
 
 # --------------------------------------------------------------------------- #
+# Causal variant (Sec. 6 names autoregressive attention as future work; the paper's method is
+# bidirectional).  Reading, all of it ours: causality is a property of ORIGINAL positions, so
+# after any sorting the query at original index i may attend to the key at original index j
+# iff j <= i + (L_k - L_q) (ends aligned when the lengths differ).  Block selection keeps its
+# form (same statistics, same compensated logits of Eq. 2 / Eq. 14 over ALL tokens of a block);
+# a block pair in which no token pair is visible is removed before the row softmax and the
+# ranking, and a row keeps min(kappa, number of its live blocks) blocks.  No block is forced in:
+# a query none of whose visible keys lie in its block's kept blocks attends to nothing and gets
+# a zero output row and lse = -inf.
+# --------------------------------------------------------------------------- #
+def causal_offset(L_q: int, L_k: int) -> int:
+    return int(L_k) - int(L_q)
+
+
+def dense_causal_attention(Q, K, V, return_lse: bool = False):
+    """Eq. 1 restricted to keys j <= i + (L_k - L_q); rows without a visible key are zero."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    L_q, d = Q.shape
+    L_k = K.shape[0]
+    off = causal_offset(L_q, L_k)
+    S = (Q @ K.T) / math.sqrt(d)
+    vis = np.arange(L_k)[None, :] <= (np.arange(L_q)[:, None] + off)
+    S = np.where(vis, S, -np.inf)
+    O = np.zeros((L_q, V.shape[1]))
+    lse = np.full(L_q, -np.inf)
+    for i in range(L_q):
+        if not vis[i].any():
+            continue
+        mx = S[i].max()
+        p = np.exp(S[i] - mx)
+        den = p.sum()
+        O[i] = (p / den) @ V
+        lse[i] = mx + math.log(den)
+    return (O, lse) if return_lse else O
+
+
+def causal_live_blocks(perm_q, perm_k, B: int) -> np.ndarray:
+    """live[g_q, g_k]: some query of block g_q (sorted order) may see some key of block g_k, i.e.
+    the smallest original key index of g_k is <= the largest original query index of g_q + offset."""
+    perm_q = np.asarray(perm_q)
+    perm_k = np.asarray(perm_k)
+    L_q, L_k = perm_q.shape[0], perm_k.shape[0]
+    off = causal_offset(L_q, L_k)
+    n_q, n_k = num_blocks(L_q, B), num_blocks(L_k, B)
+    q_max = np.array([perm_q[g * B:min((g + 1) * B, L_q)].max() for g in range(n_q)])
+    k_min = np.array([perm_k[g * B:min((g + 1) * B, L_k)].min() for g in range(n_k)])
+    return k_min[None, :] <= (q_max[:, None] + off)
+
+
+def select_causal(Q, K, B: int, sparsity: float, beta: float = 1.0, sort: int = SORT_QK, window: int = 0):
+    """Alg. 1 steps 1-11 under the causal reading above.  Returns the dict of `select` with the
+    logits of dead block pairs at -inf, `live`, per-row `count` and `cols` as a list of arrays."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    perm_q = norm_sort(Q, window) if sort in (SORT_Q, SORT_QK) else identity_perm(Q.shape[0])
+    perm_k = norm_sort(K, window) if sort in (SORT_K, SORT_QK) else identity_perm(K.shape[0])
+    q_mean, q_var = block_stats(Q[perm_q], B)
+    k_mean, k_var = block_stats(K[perm_k], B)
+    live = causal_live_blocks(perm_q, perm_k, B)
+    logits = np.where(live, block_logits(q_mean, q_var, k_mean, k_var, beta), -np.inf)
+    n_q, n_k = logits.shape
+    kappa = kappa_from_sparsity(n_k, sparsity)
+    m = np.zeros_like(logits)
+    count = np.zeros(n_q, dtype=np.int64)
+    mask = np.zeros((n_q, n_k), dtype=bool)
+    cols, mass = [], np.zeros(n_q)
+    theta = np.zeros(n_q)
+    for r in range(n_q):
+        n_live = int(live[r].sum())
+        if n_live == 0:                       # every key lies after every query of the block
+            cols.append(np.zeros(0, dtype=np.int64))
+            continue
+        z = logits[r] - logits[r][live[r]].max()
+        e = np.where(live[r], np.exp(z), 0.0)
+        m[r] = e / e.sum()
+        count[r] = min(kappa, n_live)
+        # ranking among the live blocks only; equal values: lower index first
+        order = [c for c in np.argsort(-m[r], kind="stable") if live[r, c]]
+        keep = np.array(order[:count[r]], dtype=np.int64)
+        mask[r, keep] = True
+        cols.append(np.sort(keep))
+        mass[r] = m[r, keep].sum()
+        theta[r] = m[r, order[count[r] - 1]]
+    return dict(perm_q=perm_q, perm_k=perm_k, q_mean=q_mean, q_var=q_var, k_mean=k_mean, k_var=k_var,
+                logits=logits, m=m, kappa=kappa, live=live, count=count, mask=mask, cols=cols, mass=mass,
+                theta=theta)
+
+
+def sparse_attention_causal_block(Q, K, V, perm_q, perm_k, g_q: int, cols_row, B: int):
+    """Alg. 1 step 12 for one query block under the causal reading: the block's queries attend to
+    the tokens of the listed key blocks whose original index does not exceed their own (+ offset);
+    the softmax is over those tokens.  Returns (rows_original, O_rows, lse)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    L_q, d = Q.shape
+    L_k = K.shape[0]
+    off = causal_offset(L_q, L_k)
+    qpos = np.arange(g_q * B, min((g_q + 1) * B, L_q))
+    rows = np.asarray(perm_q)[qpos]
+    O = np.zeros((rows.shape[0], V.shape[1]))
+    lse = np.full(rows.shape[0], -np.inf)
+    if len(cols_row) == 0:
+        return rows, O, lse
+    kpos = np.concatenate([np.arange(c * B, min((c + 1) * B, L_k)) for c in cols_row])
+    krows = np.asarray(perm_k)[kpos]
+    S = (Q[rows] @ K[krows].T) / math.sqrt(d)
+    vis = krows[None, :] <= (rows[:, None] + off)
+    S = np.where(vis, S, -np.inf)
+    for a in range(rows.shape[0]):
+        if not vis[a].any():
+            continue
+        mx = S[a].max()
+        p = np.exp(S[a] - mx)
+        den = p.sum()
+        O[a] = (p / den) @ V[krows]
+        lse[a] = mx + math.log(den)
+    return rows, O, lse
+
+
+def sparse_attention_causal(Q, K, V, perm_q, perm_k, cols, B: int, return_lse: bool = False):
+    L_q = np.asarray(Q).shape[0]
+    O = np.zeros((L_q, np.asarray(V).shape[1]))
+    lse = np.full(L_q, -np.inf)
+    for g in range(num_blocks(L_q, B)):
+        rows, o, l = sparse_attention_causal_block(Q, K, V, perm_q, perm_k, g, cols[g], B)
+        O[rows] = o
+        lse[rows] = l
+    return (O, lse) if return_lse else O
+
+
+# --------------------------------------------------------------------------- #
 # Analysis quantities (Sec. 3.1 Eq. 3; Sec. 3.2 Eq. 5-8).  Tiny inputs only.
 # --------------------------------------------------------------------------- #
 def oracle_block_mass(Q, K, B: int) -> np.ndarray:

@@ -680,6 +680,140 @@ def test_oracle_block_mass_ragged_blocks_by_python_loops():
     assert abs(m_hat[2].sum() - 0.75) > 0.2
 
 
+# ---------------------------------------------------------------- causal variant (our reading; Sec. 6 future work)
+def loop_causal_attention(Q, K, V):
+    L_q, L_k, d = Q.shape[0], K.shape[0], Q.shape[1]
+    off = L_k - L_q
+    O = [[0.0] * V.shape[1] for _ in range(L_q)]
+    lse = [-math.inf] * L_q
+    for i in range(L_q):
+        js = [j for j in range(L_k) if j <= i + off]
+        if not js:
+            continue
+        logit = [sum(Q[i, t] * K[j, t] for t in range(d)) / math.sqrt(d) for j in js]
+        mx = max(logit)
+        e = [math.exp(v - mx) for v in logit]
+        z = sum(e)
+        for c in range(V.shape[1]):
+            O[i][c] = sum(e[a] * V[j, c] for a, j in enumerate(js)) / z
+        lse[i] = mx + math.log(z)
+    return np.array(O), np.array(lse)
+
+
+@pytest.mark.parametrize("L_q,L_k", [(13, 13), (5, 12), (12, 5), (1, 9)])
+def test_dense_causal_attention_matches_python_loops(L_q, L_k):
+    Q, K, V = rand(L_q, 3, 1.5), rand(L_k, 3, 1.5), rand(L_k, 4)
+    O, lse = o.dense_causal_attention(Q, K, V, return_lse=True)
+    O_ref, lse_ref = loop_causal_attention(Q, K, V)
+    np.testing.assert_allclose(O, O_ref, atol=1e-13)
+    np.testing.assert_array_equal(np.isinf(lse), np.isinf(lse_ref))
+    fin = np.isfinite(lse_ref)
+    np.testing.assert_allclose(lse[fin], lse_ref[fin], atol=1e-13)
+    if L_q > L_k:                                  # the first L_q - L_k queries precede every key
+        assert np.abs(O[:L_q - L_k]).max() == 0 and np.isinf(lse[:L_q - L_k]).all()
+
+
+def test_dense_causal_closed_forms():
+    L, d = 9, 4
+    Q, K, V = rand(L, d), rand(L, d), rand(L, 3)
+    O, lse = o.dense_causal_attention(Q, K, V, return_lse=True)
+    np.testing.assert_allclose(O[0], V[0], atol=1e-15)                       # the first token sees itself only
+    assert abs(lse[0] - float(Q[0] @ K[0]) / math.sqrt(d)) < 1e-14
+    O0, lse0 = o.dense_causal_attention(Q, np.zeros_like(K), V, return_lse=True)   # equal logits: prefix means
+    for i in range(L):
+        np.testing.assert_allclose(O0[i], V[:i + 1].mean(axis=0), atol=1e-14)
+        assert abs(lse0[i] - math.log(i + 1)) < 1e-14
+    # one query that follows every key: plain attention of that query
+    q1 = rand(1, d)
+    np.testing.assert_allclose(o.dense_causal_attention(q1, K, V), o.dense_attention(q1, K, V), atol=1e-14)
+    # the last query of a square problem sees everything too
+    np.testing.assert_allclose(O[-1], o.dense_attention(Q[-1:], K, V)[0], atol=1e-14)
+
+
+def test_causal_live_blocks_bruteforce():
+    rng = np.random.default_rng(3)
+    for L_q, L_k, B in ((22, 22, 4), (10, 19, 4), (19, 10, 4)):
+        pq, pk = rng.permutation(L_q), rng.permutation(L_k)
+        live = o.causal_live_blocks(pq, pk, B)
+        off = L_k - L_q
+        for gq in range(live.shape[0]):
+            for gk in range(live.shape[1]):
+                want = any(pk[j] <= pq[i] + off for i in range(gq * B, min((gq + 1) * B, L_q))
+                           for j in range(gk * B, min((gk + 1) * B, L_k)))
+                assert live[gq, gk] == want
+    # original order, equal lengths, B divides L: the block-lower-triangular pattern
+    ident = np.arange(24)
+    assert np.array_equal(o.causal_live_blocks(ident, ident, 4), np.tril(np.ones((6, 6), dtype=bool)))
+
+
+@pytest.mark.parametrize("sort", [o.SORT_NONE, o.SORT_Q, o.SORT_K, o.SORT_QK])
+@pytest.mark.parametrize("L_q,L_k,B", [(48, 48, 8), (45, 45, 8), (20, 37, 8)])
+def test_causal_zero_sparsity_equals_dense_causal_for_every_sort_mode(sort, L_q, L_k, B):
+    # sorting permutes keys (with their values) and output rows; visibility follows original positions
+    Q, K, V = rand(L_q, 5, 1.3), rand(L_k, 5, 1.3), rand(L_k, 3)
+    sel = o.select_causal(Q, K, B, 0.0, sort=sort)
+    O, lse = o.sparse_attention_causal(Q, K, V, sel["perm_q"], sel["perm_k"], sel["cols"], B, return_lse=True)
+    O_ref, lse_ref = o.dense_causal_attention(Q, K, V, return_lse=True)
+    np.testing.assert_allclose(O, O_ref, atol=1e-12)
+    np.testing.assert_allclose(lse, lse_ref, atol=1e-12)
+    assert all(np.array_equal(c, np.nonzero(l)[0]) for c, l in zip(sel["cols"], sel["live"]))   # all live blocks, no dead one
+
+
+def test_causal_selection_ranks_live_blocks_only():
+    L, B, d = 64, 8, 4
+    Q, K = rand(L, d, 1.5), rand(L, d, 1.5)
+    for sort in (o.SORT_NONE, o.SORT_QK):
+        plain = o.select(Q, K, B, 0.5, sort=sort)
+        sel = o.select_causal(Q, K, B, 0.5, sort=sort)
+        assert sel["kappa"] == 4
+        for r in range(8):
+            live = [c for c in range(8) if sel["live"][r, c]]
+            assert sel["count"][r] == min(4, len(live)) == len(sel["cols"][r])
+            # brute force: the live blocks by decreasing plain logit (ties: lower index)
+            want = sorted(sorted(live, key=lambda c: (-plain["logits"][r, c], c))[:sel["count"][r]])
+            assert list(sel["cols"][r]) == want
+            assert np.isinf(sel["logits"][r][~sel["live"][r]]).all() and (sel["m"][r][~sel["live"][r]] == 0).all()
+            assert abs(sel["m"][r].sum() - 1.0) < 1e-13
+            # the distribution over the live blocks is the softmax of their plain logits
+            z = np.array([plain["logits"][r, c] for c in live])
+            ref = np.exp(z - z.max()) / np.exp(z - z.max()).sum()
+            np.testing.assert_allclose(sel["m"][r][live], ref, atol=1e-14)
+    # without sorting, row g sees blocks 0..g: the first rows keep fewer than kappa
+    sel = o.select_causal(Q, K, B, 0.5, sort=o.SORT_NONE)
+    assert list(sel["count"]) == [1, 2, 3, 4, 4, 4, 4, 4]
+
+
+def test_sparse_causal_attention_against_python_loops_and_empty_rows():
+    L, B, d = 40, 8, 4
+    Q, K, V = rand(L, d, 1.4), rand(L, d, 1.4), rand(L, 3)
+    sel = o.select_causal(Q, K, B, 0.5)
+    pq, pk = sel["perm_q"], sel["perm_k"]
+    O, lse = o.sparse_attention_causal(Q, K, V, pq, pk, sel["cols"], B, return_lse=True)
+    for g in range(5):
+        for i in range(g * B, (g + 1) * B):
+            qi = pq[i]
+            js = [pk[j] for c in sel["cols"][g] for j in range(c * B, (c + 1) * B) if pk[j] <= qi]
+            if not js:
+                assert np.abs(O[qi]).max() == 0 and np.isinf(lse[qi])
+                continue
+            logit = [float(Q[qi] @ K[j]) / math.sqrt(d) for j in js]
+            mx = max(logit)
+            e = [math.exp(v - mx) for v in logit]
+            want = sum(w * V[j] for w, j in zip(e, js)) / sum(e)
+            np.testing.assert_allclose(O[qi], want, atol=1e-13)
+            assert abs(lse[qi] - (mx + math.log(sum(e)))) < 1e-13
+    # a list that holds no visible key for the earliest queries: zero rows, lse -inf
+    ident = np.arange(L)
+    rows, Ob, lb = o.sparse_attention_causal_block(Q, K, V, ident, ident, 0, [0], B)
+    assert np.isfinite(lb).all()                                         # the diagonal block: every query sees itself
+    rows, Ob, lb = o.sparse_attention_causal_block(Q, K, V, ident, ident, 1, [2], B)
+    assert np.abs(Ob).max() == 0 and np.isinf(lb).all()                  # a block that lies wholly in the future
+    # constant values: every row with a visible key returns the constant
+    Vc = np.full((L, 2), 0.75)
+    Oc, lc = o.sparse_attention_causal(Q, K, Vc, pq, pk, sel["cols"], B, return_lse=True)
+    np.testing.assert_allclose(Oc[np.isfinite(lc)], 0.75, atol=1e-14)
+
+
 # ---------------------------------------------------------------- drift guard (no paper values: see the script's header)
 def test_oracle_reproduces_its_stored_tiny_results():
     import importlib.util
