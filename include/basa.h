@@ -93,6 +93,17 @@ typedef struct {
                                 kappa, so G lowers the common count to G / N_q                 */
   const int32_t* segment_starts;   /* HOST array of n_segments token indices: first 0, strictly
                                 ascending, last < L; read during the call only (NULL if none) */
+  int32_t causal;            /* 0: bidirectional attention, the paper's method.  1: the autoregressive
+                                variant the paper names as future work (Sec. 6), under this
+                                library's own reading: the query at ORIGINAL index i may attend to
+                                the key at original index j iff j <= i + (L_k - L_q), whatever the
+                                sorting did to their positions.  basa_select then drops every block
+                                pair without a visible token pair before the row softmax and the
+                                ranking, and a row keeps min(kappa, its live blocks) (row_count may
+                                be 0 when L_q > L_k); basa_sparse_attn / basa_dense_attn mask token
+                                by token, and a query none of whose visible keys lie in the listed
+                                blocks gets a zero output row and lse = -inf.  The `scores` output
+                                of basa_select stays unmasked                                   */
 } basa_params;
 #define BASA_MAX_SEGMENTS 63
 

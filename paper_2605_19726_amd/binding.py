@@ -43,7 +43,7 @@ class BasaParams(C.Structure):
                 ("beta", C.c_float), ("sparsity", C.c_double), ("mass_target", C.c_double),
                 ("min_keep", C.c_int32), ("attn_shape", C.c_int32),
                 ("n_segments", C.c_int32), ("budget_total", C.c_int32),
-                ("segment_starts", C.POINTER(C.c_int32))]
+                ("segment_starts", C.POINTER(C.c_int32)), ("causal", C.c_int32)]
 
 
 class BasaError(RuntimeError):
@@ -150,10 +150,11 @@ def tensor_desc(x: torch.Tensor) -> BasaTensor:
 
 def params(block: int, sparsity: float = 0.0, beta: float = 1.0, sort: int = SORT_QK,
            window: int = 0, mass_target: float = 0.0, min_keep: int = 0, attn_shape: int = 0,
-           segments=None, budget_total: int = 0) -> BasaParams:
+           segments=None, budget_total: int = 0, causal: bool = False) -> BasaParams:
     """segments: host sequence of segment start tokens ([0, s1, s2, ...]) for a segment-aware sort."""
     p = BasaParams(int(block), int(sort), int(window), float(beta), float(sparsity),
-                   float(mass_target), int(min_keep), int(attn_shape), 0, int(budget_total), None)
+                   float(mass_target), int(min_keep), int(attn_shape), 0, int(budget_total), None,
+                   1 if causal else 0)
     if segments is not None:
         arr = (C.c_int32 * len(segments))(*[int(v) for v in segments])
         p.n_segments = len(segments)
@@ -251,11 +252,12 @@ def attn_workspace_size(q, k, p: BasaParams) -> int:
 def basa_select(q: torch.Tensor, k: torch.Tensor, block: int, sparsity: float, beta: float = 1.0,
                 sort: int = SORT_QK, window: int = 0, want_mask: bool = True,
                 want_mass: bool = True, want_scores: bool = False, ws=None, out: Selection = None,
-                mass_target: float = 0.0, min_keep: int = 0, segments=None, budget_total: int = 0):
+                mass_target: float = 0.0, min_keep: int = 0, segments=None, budget_total: int = 0,
+                causal: bool = False):
     lib = load()
     qd, kd = tensor_desc(q), tensor_desc(k)
     p = params(block, sparsity, beta, sort, window, mass_target, min_keep, segments=segments,
-               budget_total=budget_total)
+               budget_total=budget_total, causal=causal)
     b, hq, Lq, _ = q.shape
     hk, Lk = k.shape[1], k.shape[2]
     n_q, n_k = n_blocks(Lq, block), n_blocks(Lk, block)
@@ -292,11 +294,11 @@ def _out_strides(out: torch.Tensor, q: torch.Tensor):
 
 
 def basa_sparse_attn(q, k, v, row_count, row_cols, block: int, perm_q=None, perm_k=None,
-                     want_lse: bool = False, ws=None, out=None, attn_shape: int = 0):
+                     want_lse: bool = False, ws=None, out=None, attn_shape: int = 0, causal: bool = False):
     """out: optional [batch, heads_q, L_q, d] view to write into (strided views are passed as such)."""
     lib = load()
     qd, kd, vd = tensor_desc(q), tensor_desc(k), tensor_desc(v)
-    p = params(block, attn_shape=attn_shape)
+    p = params(block, attn_shape=attn_shape, causal=causal)
     b, hq, Lq, d = q.shape
     if out is None:
         out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)
@@ -311,10 +313,10 @@ def basa_sparse_attn(q, k, v, row_count, row_cols, block: int, perm_q=None, perm
     return (out, lse) if want_lse else out
 
 
-def basa_dense_attn(q, k, v, block: int = 128, want_lse: bool = False, ws=None, out=None):
+def basa_dense_attn(q, k, v, block: int = 128, want_lse: bool = False, ws=None, out=None, causal: bool = False):
     lib = load()
     qd, kd, vd = tensor_desc(q), tensor_desc(k), tensor_desc(v)
-    p = params(block)
+    p = params(block, causal=causal)
     b, hq, Lq, d = q.shape
     if out is None:
         out = torch.empty((b, hq, Lq, d), dtype=q.dtype, device=q.device)
@@ -328,11 +330,12 @@ def basa_dense_attn(q, k, v, block: int = 128, want_lse: bool = False, ws=None, 
 
 
 def ba_att(q, k, v, block: int = 128, sparsity: float = 0.5, beta: float = 1.0, sort: int = SORT_QK,
-           window: int = 0, mass_target: float = 0.0, min_keep: int = 0, segments=None, out=None):
+           window: int = 0, mass_target: float = 0.0, min_keep: int = 0, segments=None, out=None,
+           causal: bool = False):
     """The whole operator (Alg. 1): basa_select, then basa_sparse_attn on its lists.  Returns (out, Selection)."""
     sel = basa_select(q, k, block, sparsity, beta, sort, window, want_mask=False, want_mass=False,
-                      mass_target=mass_target, min_keep=min_keep, segments=segments)
-    o = basa_sparse_attn(q, k, v, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k, out=out)
+                      mass_target=mass_target, min_keep=min_keep, segments=segments, causal=causal)
+    o = basa_sparse_attn(q, k, v, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k, out=out, causal=causal)
     return o, sel
 
 

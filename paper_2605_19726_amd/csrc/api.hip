@@ -131,6 +131,7 @@ basa_status check_params(const basa_params* p, bool need_sparsity) {
   if (need_sparsity && p->min_keep < 0) {
     set_error("min_keep %d is negative", p->min_keep); return BASA_ERR_INVALID_ARG;
   }
+  if (p->causal != 0 && p->causal != 1) { set_error("causal must be 0 or 1"); return BASA_ERR_INVALID_ARG; }
   return BASA_OK;
 }
 
@@ -171,7 +172,7 @@ basa_status check_qkv(const basa_tensor* q, const basa_tensor* k, const basa_ten
 }
 
 struct SelectWs {
-  size_t sort_off, featq_off, featk_off, scores_off, total;
+  size_t sort_off, featq_off, featk_off, scores_off, range_off, total;
 };
 
 SelectWs carve_select(const basa_tensor* q, const basa_tensor* k, const basa_params* p) {
@@ -184,6 +185,7 @@ SelectWs carve_select(const basa_tensor* q, const basa_tensor* k, const basa_par
   w.featq_off = o; o += align_up((size_t)BHq * Nq * feat_bytes_per_block(q->d), 256);
   w.featk_off = o; o += align_up((size_t)BHk * Nk * feat_bytes_per_block(k->d), 256);
   w.scores_off = o; o += align_up((size_t)BHq * Nq * Nk * sizeof(float), 256);
+  w.range_off = o; o += align_up(((size_t)BHq * Nq + (size_t)BHk * Nk) * sizeof(int32_t), 256);   // causal: block index ranges
   w.total = o;
   return w;
 }
@@ -192,7 +194,7 @@ bool use_mfma(const basa_tensor* q) { return q->dtype == BASA_BF16; }   // d is 
 
 basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_tensor* v,
                         const int32_t* row_count, const int32_t* row_cols, int32_t cols_stride,
-                        const int32_t* perm_q, const int32_t* perm_k, int B, int variant, void* out,
+                        const int32_t* perm_q, const int32_t* perm_k, int B, int variant, int causal, void* out,
                         const int64_t* out_strides, float* lse, void* ws, size_t ws_bytes, void* stream) {
   if (!out) { set_error("null output pointer"); return BASA_ERR_INVALID_ARG; }
   if (reinterpret_cast<uintptr_t>(out) % 16) { set_error("out must be 16-byte aligned"); return BASA_ERR_INVALID_ARG; }
@@ -210,6 +212,7 @@ basa_status attn_common(const basa_tensor* q, const basa_tensor* k, const basa_t
   a.row_count = row_count; a.row_cols = row_cols; a.cols_stride = cols_stride;
   a.perm_q = perm_q; a.perm_k = perm_k; a.B = B; a.out = out; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes;
   a.variant = variant;
+  a.causal = causal; a.causal_off = k->L - q->L;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (use_mfma(q)) {
     const size_t need = attn_mfma_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L, q->d, B);
@@ -339,14 +342,22 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
   }
   const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
   if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
-  if ((s = launch_row_select(sc, BHq * Nq, Nk, kappa, (float)p->mass_target, p->min_keep, nullptr, mask_bits,
+  LiveBlocks live{nullptr, nullptr, Nq, q->heads / k->heads, k->L - q->L};
+  if (p->causal) {
+    int32_t* q_max = reinterpret_cast<int32_t*>(base + w.range_off);
+    int32_t* k_min = q_max + (size_t)BHq * Nq;
+    if ((s = launch_block_index_range(perm_q, BHq, q->L, B, 1, q_max, st)) != BASA_OK) return s;
+    if ((s = launch_block_index_range(perm_k, BHk, k->L, B, 0, k_min, st)) != BASA_OK) return s;
+    live.q_max = q_max; live.k_min = k_min;
+  }
+  if ((s = launch_row_select(sc, BHq * Nq, Nk, kappa, (float)p->mass_target, p->min_keep, nullptr, live, mask_bits,
                              row_count, row_cols, row_mass, st)) != BASA_OK) return s;
   if (p->budget_total > 0) {
     // the sort buffers are free by now: the trimmed per-row counts live there
     int32_t* keep = reinterpret_cast<int32_t*>(sort_ws);
     const int floor_keep = p->mass_target > 0.0 ? p->min_keep : 1;
     if ((s = launch_budget_cap(row_count, BHq, Nq, kappa, floor_keep, p->budget_total, keep, st)) != BASA_OK) return s;
-    s = launch_row_select(sc, BHq * Nq, Nk, kappa, 0.f, 0, keep, mask_bits, row_count, row_cols, row_mass, st);
+    s = launch_row_select(sc, BHq * Nq, Nk, kappa, 0.f, 0, keep, live, mask_bits, row_count, row_cols, row_mass, st);
   }
   return s;
 }
@@ -361,7 +372,7 @@ basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const b
   if (row_cols && !row_count) { set_error("row_cols given without row_count"); return BASA_ERR_INVALID_ARG; }
   if (row_cols && cols_stride < 1) { set_error("cols_stride must be >= 1"); return BASA_ERR_INVALID_ARG; }
   if (p->attn_shape < 0 || p->attn_shape > 3) { set_error("attn_shape must be 0, 1, 2 or 3"); return BASA_ERR_INVALID_ARG; }
-  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, out,
+  return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, p->causal, out,
                      out_strides, lse, ws, ws_bytes, stream);
 }
 
@@ -371,7 +382,8 @@ basa_status basa_dense_attn(const basa_tensor* q, const basa_tensor* k, const ba
   basa_status s;
   if ((s = check_qkv(q, k, v)) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
-  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 3, out, out_strides, lse, ws, ws_bytes, stream);
+  return attn_common(q, k, v, nullptr, nullptr, 0, nullptr, nullptr, p->block, 3, p->causal, out, out_strides, lse, ws,
+                     ws_bytes, stream);
 }
 
 

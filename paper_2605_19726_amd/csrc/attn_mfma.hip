@@ -36,6 +36,7 @@
 // touches O only through MFMA.  K/V tiles go through a 4-stage LDS ring used as two slots of
 // two tiles: one pair is computed while the next pair lands; one workgroup barrier per pair.
 #include <algorithm>
+#include <climits>
 #include <type_traits>
 #include "common.hpp"
 
@@ -48,6 +49,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTileKeys = 64;
+constexpr int kIxStride = kTileKeys + 4;    // causal: ints per tile of the key-index array (64 indices, min, max, 2 unused)
 #ifndef BASA_ATTN_QR
 #define BASA_ATTN_QR 7
 #endif
@@ -155,7 +157,9 @@ struct MfmaArgs {
   float scale_log2e;
   int64_t out_sb, out_sh, out_sl;   // strides of out in elements
   int heads_q;
-  const int32_t* probe;      // nullable: {blocks in both lists, blocks in the lists} over sampled pairs
+  const int32_t* kix;        // causal: [BHkv][tiles][kIxStride] original key indices of a tile, then their min and max
+  int causal_off;            // causal: L_k - L_q
+  const int32_t* probe;      // nullable: {blocks in the union of a group's lists, blocks in its lists} over sampled groups
   int run_if_solo;           // with probe: this launch runs iff (lists overlap little) == run_if_solo
 };
 
@@ -175,9 +179,13 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 
 // One 64-key tile: S^T, softmax, O^T update, reading the LDS stage at `stage`.  kMasked:
 // keys at tile positions >= nvalid do not exist (ragged end of the sequence) and get -inf.
-template <bool kMasked, int D>
+// kCausal: kix holds the original index of each of the tile's 64 keys (INT_MAX where the sequence
+// has ended, which subsumes the ragged mask); a key is visible to this lane's query iff its index
+// does not exceed q_lim.
+template <bool kMasked, int D, bool kCausal = false>
 __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf)[Geo<D>::kKSteps], const char* stage,
-                                             int kaddr0, int vaddr0, float c, int nvalid, int h) {
+                                             int kaddr0, int vaddr0, float c, int nvalid, int h,
+                                             const int* kix = nullptr, int q_lim = 0) {
   const char* ks = stage;
   const char* vs = stage + Geo<D>::kTileBytes;
 
@@ -199,6 +207,19 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
       if (32 + kk >= nvalid) s1[r] = -INFINITY;
     }
   }
+  if constexpr (kCausal) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int4 i0 = *reinterpret_cast<const int4*>(kix + 8 * g4 + 4 * h);
+      const int4 i1 = *reinterpret_cast<const int4*>(kix + 32 + 8 * g4 + 4 * h);
+      const int a0[4] = {i0.x, i0.y, i0.z, i0.w}, a1[4] = {i1.x, i1.y, i1.z, i1.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (a0[e] > q_lim) s0[4 * g4 + e] = -INFINITY;
+        if (a1[e] > q_lim) s1[4 * g4 + e] = -INFINITY;
+      }
+    }
+  }
   // ---- online softmax in the log2 domain, lazy running max
   float mx = max3(s0[0], s1[0], s0[1]);
 #pragma unroll
@@ -207,7 +228,8 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
   const float mc = mx * c;
   if (__builtin_amdgcn_ballot_w64(mc > st.m_run + kLazyTau) != 0) {
     const float m_new = fmaxf(st.m_run, mc);
-    const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);
+    // (causal: a lane whose query still sees nothing has -inf on both sides; its state stays as it is)
+    const float alpha = (kCausal && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run - m_new);
     st.m_run = m_new;
     st.l_run *= alpha;
 #pragma unroll
@@ -215,7 +237,8 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[i][r] *= alpha;
   }
-  const float m_use = st.m_run;
+  // (causal: a query that has seen no key yet subtracts 0, so that exp2 sees -inf, never inf - inf)
+  const float m_use = (kCausal && st.m_run == -INFINITY) ? 0.f : st.m_run;
   bf16x8 pb[4];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -390,9 +413,14 @@ __device__ __forceinline__ int64_t out_off(const MfmaArgs& a, int bhq, int row) 
 // seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
 // this workgroup lists it).  While seq is being built the ring area holds the per-key-block
 // membership flags.
-template <int kB, int D, int kWgQueries, int kQPW>
+// kCausal (128-query shape only): the ring is followed by the original key indices of each stage's
+// tile, every score is masked by original position, and a tile is skipped (no key visible to any
+// query of the wave) or takes the unmasked code (every key visible to every query) where its
+// index range allows.
+template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false>
 __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 : 2) void attn_mfma_kernel(MfmaArgs a) {
   using G = Geo<D>;
+  static_assert(!kCausal || (kQPW == 32 && kWgQueries == kSoloQueries), "the causal path is built on the 128-query shape");
   constexpr int kWaves = kWgQueries / kQPW, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
   constexpr int kNG = kQPW / 32;             // 32-query groups per wave: 1 or 2
   constexpr int kStages = stages_of(kThreads, kQPW);
@@ -414,6 +442,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   uint32_t* flags = reinterpret_cast<uint32_t*>(smem);
   uint32_t* seq = reinterpret_cast<uint32_t*>(smem + kRingBytes + kQParkBytes);
   uint32_t* wave_counts = seq + a.Nk;
+  int* kix_lds = reinterpret_cast<int*>(smem + ((kRingBytes + kQParkBytes + a.Nk * 4 + kWaves * 4 + 15) & ~15));   // kCausal
 
   // XCD-aware order: consecutive workgroup ids go round-robin over the 8 XCDs; give each
   // XCD a contiguous range of (head, query blocks) so that its L2 sees one head at a time.
@@ -502,6 +531,13 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
       char* dst = smem + stage * kStageBytes + cb * 1024;
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
     }
+    if constexpr (kCausal) {
+      // the tile's key indices, minimum and maximum: kIxStride ints = 17 lanes of 16 bytes
+      if (wave == 0 && lane < kIxStride / 4) {
+        const int32_t* src = a.kix + ((int64_t)bhk * tiles_per_head + tile) * kIxStride + lane * 4;
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(kix_lds + stage * kIxStride), 16, 0, 0);
+      }
+    }
   };
   auto tile_of = [&](int t) -> int {
     const int tt = min(t, n_tiles - 1);
@@ -514,6 +550,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[kNG][kQR];
+  int q_lim = INT_MIN;          // kCausal: the largest original key index this lane's query may see
   char* qpark = smem + kRingBytes + (wave * kNG * kQL) * 1024 + lane * 16;    // this lane's parked fragments
 #pragma unroll
   for (int r = 0; r < kNG; ++r) {
@@ -521,6 +558,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
     // (padding of the last block, or a query block that does not exist) read row 0 and are never stored
     const int qpos = pos0 + 32 * r;
     const int qrow = qpos < a.Lq ? perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq) : 0;
+    if (kCausal && qpos < a.Lq) q_lim = qrow + a.causal_off;
     const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q.ptr) +
                                                      (a.q.head_offset(bhq) + (int64_t)qrow * a.q.stride_l) * 2);
 #pragma unroll
@@ -569,7 +607,39 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   // slot; their loads are issued right after the barrier, which also says that every wave is
   // done with that other slot (pair p-1).  The union entries of later tiles are read from LDS
   // early and turned into scalars late, so their latency hides behind the arithmetic.
-  if constexpr (kNG == 2) {
+  if constexpr (kCausal) {
+    // the visible range of this wave's queries (lanes without a query see nothing and ask for nothing)
+    int wq_min = q_lim == INT_MIN ? INT_MAX : q_lim, wq_max = q_lim;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      wq_min = min(wq_min, __shfl_xor(wq_min, off));
+      wq_max = max(wq_max, __shfl_xor(wq_max, off));
+    }
+    wq_min = __builtin_amdgcn_readfirstlane(wq_min);
+    wq_max = __builtin_amdgcn_readfirstlane(wq_max);
+    uint32_t e_cur = entry_of(0);
+#pragma nounroll
+    for (int t = 0; t < n_tiles; ++t) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      uint32_t e_nxt = e_cur;
+      if (t + 1 < n_tiles) {
+        e_nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)seq[(t + 1) / TPB]);
+        issue_tile((int)(e_nxt & 0xffffffu) * TPB + ((t + 1) % TPB), (t + 1) & 1);
+      }
+      if (e_cur & my_bit) {
+        const int* kx = kix_lds + (t & 1) * kIxStride;
+        const int t_min = __builtin_amdgcn_readfirstlane(kx[kTileKeys]);
+        const int t_max = __builtin_amdgcn_readfirstlane(kx[kTileKeys + 1]);      // INT_MAX if the tile is ragged
+        const char* stage = smem + (t & 1) * kStageBytes;
+        if (t_min <= wq_max) {
+          if (t_max <= wq_min) process_tile<false, D>(st, qf[0], stage, kaddr, vaddr, c, kTileKeys, h);
+          else process_tile<false, D, true>(st, qf[0], stage, kaddr, vaddr, c, kTileKeys, h, kx, q_lim);
+        }
+      }
+      e_cur = e_nxt;
+    }
+  } else if constexpr (kNG == 2) {
     // 64 queries per wave: ONE call site for full tiles (a second inlined copy of the tile code
     // costs the register allocator its footing).  Tiles travel in rounds of R = kStages / 2; the
     // workgroup meets once per round, and round p + 1 lands in the other half of the ring while
@@ -686,15 +756,16 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
 size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk * B * d * 2, 256); }
 
 template <int D>
-size_t lds_bytes(int threads, int qpw, int Nk) {
+size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false) {
   const size_t park = (size_t)(threads / 64) * (qpw / 32) * (D / 16 - q_reg_steps(D, qpw)) * 1024;
-  return (size_t)stages_of(threads, qpw) * Geo<D>::kStageBytes + park + (size_t)Nk * 4 + (threads / 64) * 4;
+  const size_t base = (size_t)stages_of(threads, qpw) * Geo<D>::kStageBytes + park + (size_t)Nk * 4 + (threads / 64) * 4;
+  return causal ? ((base + 15) & ~(size_t)15) + (size_t)stages_of(threads, qpw) * kIxStride * 4 : base;
 }
 
-template <int kB, int D, int kWgQueries, int kQPW>
+template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false>
 basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
   constexpr int kThreads = kWgQueries / kQPW * 64;
-  const size_t lds = lds_bytes<D>(kThreads, kQPW, m.Nk);
+  const size_t lds = lds_bytes<D>(kThreads, kQPW, m.Nk, kCausal);
   // while the union list is built, the per-key-block membership flags live in the ring area
   if ((size_t)m.Nk * 4 > (size_t)stages_of(kThreads, kQPW) * Geo<D>::kStageBytes) {
     set_error("attention: %d key blocks exceed the %zu this workgroup shape can list", m.Nk,
@@ -703,18 +774,38 @@ basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
   }
   m.wgs_per_head = ceil_div(m.Nq * kB, kWgQueries);
   m.total_wgs = BHq * m.wgs_per_head;
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries, kQPW>),
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries, kQPW, kCausal>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
-  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries, kQPW>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
+  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries, kQPW, kCausal>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
   BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
   return BASA_OK;
 }
 // dispatch on block size and head dimension
-template <int kWgQueries, int kQPW>
+template <int kWgQueries, int kQPW, bool kCausal = false>
 basa_status launch_shape(const MfmaArgs& m, int B, int d, int BHq, hipStream_t st) {
-  if (d == 128) return B == 128 ? launch_main<128, 128, kWgQueries, kQPW>(m, BHq, st) : launch_main<64, 128, kWgQueries, kQPW>(m, BHq, st);
-  return B == 128 ? launch_main<128, 64, kWgQueries, kQPW>(m, BHq, st) : launch_main<64, 64, kWgQueries, kQPW>(m, BHq, st);
+  if (d == 128) return B == 128 ? launch_main<128, 128, kWgQueries, kQPW, kCausal>(m, BHq, st)
+                                : launch_main<64, 128, kWgQueries, kQPW, kCausal>(m, BHq, st);
+  return B == 128 ? launch_main<128, 64, kWgQueries, kQPW, kCausal>(m, BHq, st)
+                  : launch_main<64, 64, kWgQueries, kQPW, kCausal>(m, BHq, st);
+}
+
+// Causal variant: per 64-key tile of the ordered keys, the original index of every key (INT_MAX past
+// the end of the sequence), then the smallest and the largest of the 64.
+__global__ __launch_bounds__(64) void key_index_kernel(const int32_t* __restrict__ perm, int Lk, int tiles_per_head,
+                                                       int32_t* __restrict__ out) {
+  const int tile = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x;
+  const int pos = tile * kTileKeys + lane;
+  const int idx = pos < Lk ? perm_at(perm, (int64_t)bh * Lk, pos, Lk) : INT_MAX;
+  int lo = idx, hi = idx;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    lo = min(lo, __shfl_xor(lo, off));
+    hi = max(hi, __shfl_xor(hi, off));
+  }
+  int32_t* o = out + ((int64_t)bh * tiles_per_head + tile) * kIxStride;
+  o[lane] = idx;
+  if (lane < 4) o[kTileKeys + lane] = lane == 0 ? lo : (lane == 1 ? hi : 0);
 }
 
 // How much the lists of the query blocks that would share a 512-query workgroup have in common, on
@@ -775,7 +866,8 @@ basa_status launch_gathers(const AttnArgs& a, uint4* Kt, uint4* Vt, int BHkv, in
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B) {
   const int Nq = ceil_div(Lq, B), Nk = ceil_div(Lk, B);
   (void)BHq; (void)Nq;
-  return 2 * sz_kv(BHkv, Nk, B, d) + 256;      // + the two counters of the list-overlap probe
+  // + the two counters of the list-overlap probe + the key-index tiles of the causal variant
+  return 2 * sz_kv(BHkv, Nk, B, d) + 256 + align_up((size_t)BHkv * (Nk * B / kTileKeys) * kIxStride * 4, 256);
 }
 
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
@@ -820,6 +912,19 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.wgs_per_head = 0; m.total_wgs = 0;
   m.scale_log2e = 1.4426950408889634f / sqrtf((float)d);
   m.probe = nullptr; m.run_if_solo = 0;
+  m.kix = nullptr; m.causal_off = a.causal_off;
+  if (a.causal) {
+    int32_t* kix = reinterpret_cast<int32_t*>(ws + 2 * sz_kv(BHkv, Nk, B, d) + 256);
+    const int tiles_per_head = Nk * B / kTileKeys;
+    {
+      ProfScope prof(K_GATHER, st);
+      hipLaunchKernelGGL(key_index_kernel, dim3(tiles_per_head, BHkv), dim3(64), 0, st, a.perm_k, a.k.L, tiles_per_head, kix);
+      BASA_HIP_CHECK_LAUNCH("key_index_kernel");
+    }
+    m.kix = kix;
+    ProfScope prof(K_ATTN, st);
+    return launch_shape<kSoloQueries, 32, true>(m, B, d, BHq, st);
+  }
 
   // Which shape of workgroup: asked for, or (B = d = 128, block lists given, enough work to pay for
   // three tiny launches) decided on the device from how much neighbouring lists overlap.

@@ -4,6 +4,7 @@
 // 16 keys at a time, softmax is the online (running max / running sum) form.
 // This is the exact-arithmetic path for f32 tensors (bf16 tensors always take the matrix-core
 // kernel); it is not tuned for speed.
+#include <climits>
 #include "common.hpp"
 
 namespace basa {
@@ -18,6 +19,7 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
   constexpr int E = Chunk16<kBf16>::kElems;
   __shared__ __attribute__((aligned(16))) float Ks[kTK][kD];
   __shared__ __attribute__((aligned(16))) float Vs[kTK][kD];
+  __shared__ int Kidx[kTK];      // original index of every staged key (causal variant)
 
   const int gq = blockIdx.x, bhq = blockIdx.y;
   const int group = a.q.heads / a.k.heads;
@@ -28,6 +30,8 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
   const int32_t* pq = a.perm_q ? a.perm_q + (int64_t)bhq * Lq : nullptr;
   const int32_t* pk = a.perm_k ? a.perm_k + (int64_t)bhk * Lk : nullptr;
   const int qrow = active ? perm_at(pq, 0, pos, Lq) : 0;
+  // causal variant: keys whose original index exceeds q_lim are invisible to this query
+  const int q_lim = a.causal ? qrow + a.causal_off : INT_MAX;
 
   float q[kD], acc[kD];
   {
@@ -76,6 +80,7 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
         float* dst = which ? &Vs[j][c * E] : &Ks[j][c * E];
 #pragma unroll
         for (int e = 0; e < E; ++e) dst[e] = ch.v[e];
+        if (which == 0 && c == 0) Kidx[j] = j < nk ? perm_at(pk, 0, kstart + t0 + j, Lk) : INT_MAX;
       }
       __syncthreads();
       float s[kTK];
@@ -89,17 +94,19 @@ __global__ __launch_bounds__(kB) void attn_simple_kernel(AttnArgs a, int Nq, int
           d0 = fmaf(q[t], kv.x, d0); d0 = fmaf(q[t + 1], kv.y, d0);
           d0 = fmaf(q[t + 2], kv.z, d0); d0 = fmaf(q[t + 3], kv.w, d0);
         }
-        s[j] = (j < nk) ? d0 * scale : -INFINITY;
+        s[j] = (j < nk && Kidx[j] <= q_lim) ? d0 * scale : -INFINITY;
         tmax = fmaxf(tmax, s[j]);
       }
       const float m_new = fmaxf(m, tmax);
-      const float alpha = expf(m - m_new);      // m = -inf on the first step gives 0
+      // (nothing visible so far: subtract 0 instead of -inf, so that exp sees -inf and never inf - inf)
+      const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = expf(m - m_sub);      // m = -inf on the first step gives 0
       l *= alpha;
 #pragma unroll
       for (int t = 0; t < kD; ++t) acc[t] *= alpha;
 #pragma unroll
       for (int j = 0; j < kTK; ++j) {
-        const float p = expf(s[j] - m_new);     // masked keys: exp(-inf) = 0
+        const float p = expf(s[j] - m_sub);     // masked keys: exp(-inf) = 0
         l += p;
 #pragma unroll
         for (int t = 0; t < kD; t += 4) {

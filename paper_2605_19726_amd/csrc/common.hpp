@@ -97,10 +97,20 @@ basa_status launch_block_scores(const void* featQ, const void* featK, float* sco
 // Row softmax mass + top-kappa selection from a score map; mass_target > 0 switches to the
 // cumulative-mass count per row (floor min_keep, cap kappa).  row_cols rows are kappa apart.
 // keep_in (nullable): per-row count that replaces both rules (used after launch_budget_cap).
+// live (nullable): causal liveness of block pairs, see launch_block_index_range; a row then keeps
+// at most as many blocks as are live for it (possibly none).
+struct LiveBlocks {
+  const int32_t* q_max;       // [BHq][Nq] largest original index among the queries of a block, or null
+  const int32_t* k_min;       // [BHkv][Nk] smallest original index among the keys of a block
+  int Nq, group, offset;      // rows per head, query heads per KV head, L_k - L_q
+};
 basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
-                              float mass_target, int min_keep, const int32_t* keep_in, uint32_t* mask_bits,
-                              int32_t* row_count, int32_t* row_cols, float* row_mass,
+                              float mass_target, int min_keep, const int32_t* keep_in, const LiveBlocks& live,
+                              uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols, float* row_mass,
                               hipStream_t st);
+// Per block of a permutation: out[bh][g] = max (want_max) or min of perm[bh][g*B .. min((g+1)*B, L)).
+basa_status launch_block_index_range(const int32_t* perm, int BH, int L, int B, int want_max, int32_t* out,
+                                     hipStream_t st);
 
 // Total budget per (batch, head): keep_out[r] = min(row_count[r], t), t the largest cap in
 // [max(1, floor_keep), kappa] with sum_r min(row_count[r], t) <= budget (else the smallest cap).
@@ -125,7 +135,9 @@ struct AttnArgs {
   float* lse;                 // [BHq][Lq] or null
   void* ws;
   size_t ws_bytes;
-  int variant;                // matrix-core path: 0 = library's choice, 1 = 256 queries per workgroup, 2 = 128
+  int variant;                // matrix-core path: 0 = library's choice, 1 = 256 queries per workgroup, 2 = 128, 3 = 512
+  int causal;                 // 1: key at original index j is visible to the query at original index i iff j <= i + causal_off
+  int causal_off;             // L_k - L_q
 };
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B);
 basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st);

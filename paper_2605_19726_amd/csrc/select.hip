@@ -12,6 +12,7 @@
 // popcount per step), then the kept columns are compacted in ascending order; among
 // logits equal to the threshold the lower block indices win.  Softmax is monotone, so
 // ranking by l' is ranking by m'; the softmax is evaluated only for the kept mass.
+#include <climits>
 #include "common.hpp"
 
 namespace basa {
@@ -168,7 +169,7 @@ template <int MAXI>
 __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ scores,
                                                          int rows_total, int Nk, int kappa,
                                                          float mass_target, int min_keep,
-                                                         const int32_t* __restrict__ keep_in,
+                                                         const int32_t* __restrict__ keep_in, LiveBlocks live,
                                                          uint32_t* __restrict__ mask_bits,
                                                          int32_t* __restrict__ row_count,
                                                          int32_t* __restrict__ row_cols,
@@ -177,6 +178,10 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   const int row = blockIdx.x * 4 + wave;
   if (row >= rows_total) return;
   const float* src = scores + (int64_t)row * Nk;
+  // causal variant: a key block is live for this row iff its smallest original key index does not
+  // exceed the row's largest original query index (+ offset); dead blocks take no part below
+  const int32_t* kmin = live.q_max ? live.k_min + (int64_t)(row / live.Nq / live.group) * Nk : nullptr;
+  const int q_lim = live.q_max ? live.q_max[row] + live.offset : 0;
   float e[MAXI];                        // logits first, then exp(l - max)
   uint32_t u[MAXI];
   float mx = -INFINITY;
@@ -184,9 +189,31 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   // branch is followed by a full wait, which would serialise the MAXI loads of a lane
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) e[i] = src[min(i * 64 + lane, Nk - 1)];
+  int n_live = Nk;
+  if (kmin) {
+    int km[MAXI];
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) km[i] = kmin[min(i * 64 + lane, Nk - 1)];
+    n_live = 0;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      const bool alive = i * 64 + lane < Nk && km[i] <= q_lim;
+      n_live += __popcll(__ballot(alive));
+      if (!alive) e[i] = __uint_as_float(0x7fc00000u);      // marked; replaced below
+    }
+    if (n_live == 0) {                                      // every key lies after every query of the block
+      if (lane == 0) {
+        if (row_count) row_count[row] = 0;
+        if (row_mass) row_mass[row] = 0.f;
+      }
+      if (mask_bits)
+        for (int w = lane; w < (Nk + 31) >> 5; w += 64) mask_bits[(int64_t)row * ((Nk + 31) >> 5) + w] = 0u;
+      return;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
-    const bool in_row = i * 64 + lane < Nk;
+    const bool in_row = i * 64 + lane < Nk && !(kmin && e[i] != e[i]);
     e[i] = in_row ? e[i] + 0.0f : -INFINITY;        // -0 -> +0 so that equal values have equal images
     u[i] = in_row ? ordered_bits(e[i]) : 0u;        // 0 is below the image of every float
     mx = fmaxf(mx, e[i]);
@@ -196,12 +223,13 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   float sum_all = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
-    e[i] = (i * 64 + lane < Nk) ? expf(e[i] - mx) : 0.f;
+    e[i] = (u[i] != 0u) ? expf(e[i] - mx) : 0.f;         // image 0: past the row, or a dead block
     sum_all += e[i];
   }
   sum_all = wave_sum(sum_all);
 
   int keep = keep_in ? max(1, min(keep_in[row], kappa)) : kappa;
+  keep = min(keep, n_live);
   if (!keep_in && mass_target > 0.f) {
     const float need = mass_target * sum_all;
     // T2 = largest image T such that the logits with image >= T carry at least the target
@@ -228,7 +256,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
     for (int off = 32; off > 0; off >>= 1) e_eq = fmaxf(e_eq, __shfl_xor(e_eq, off));
     int r = n_eq;
     if (e_eq > 0.f) r = min(n_eq, max(1, (int)ceilf((need - m_gt) / e_eq)));
-    keep = min(kappa, max(max(1, min_keep), n_gt + r));
+    keep = min(min(kappa, n_live), max(max(1, min_keep), n_gt + r));
   }
 
   // T = keep-th largest image
@@ -347,16 +375,55 @@ basa_status launch_block_scores(const void* featQ, const void* featK, float* sco
   return BASA_OK;
 }
 
+namespace {
+// One wave per block of a permutation: the largest (or smallest) original index in the block.
+__global__ __launch_bounds__(256) void block_index_range_kernel(const int32_t* __restrict__ perm, int L, int B, int N,
+                                                                int64_t blocks_total, int want_max,
+                                                                int32_t* __restrict__ out) {
+  const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blk >= blocks_total) return;
+  const int lane = threadIdx.x & 63;
+  const int64_t bh = blk / N;
+  const int g = (int)(blk - bh * N);
+  const int n = min(B, L - g * B);
+  int v = want_max ? INT_MIN : INT_MAX;
+  for (int i = lane; i < n; i += 64) {
+    const int pos = g * B + i;
+    const int r = perm_at(perm, bh * L, pos, L);
+    v = want_max ? max(v, r) : min(v, r);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const int o = __shfl_xor(v, off);
+    v = want_max ? max(v, o) : min(v, o);
+  }
+  if (lane == 0) out[blk] = v;
+}
+
+}  // namespace
+
+basa_status launch_block_index_range(const int32_t* perm, int BH, int L, int B, int want_max, int32_t* out,
+                                     hipStream_t st) {
+  const int N = ceil_div(L, B);
+  const int64_t total = (int64_t)BH * N;
+  if (total == 0) return BASA_OK;
+  ProfScope prof(K_ROW_SELECT, st);
+  hipLaunchKernelGGL(block_index_range_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, st, perm, L, B, N, total,
+                     want_max, out);
+  BASA_HIP_CHECK_LAUNCH("block_index_range_kernel");
+  return BASA_OK;
+}
+
 basa_status launch_row_select(const float* scores, int rows_total, int Nk, int kappa,
-                              float mass_target, int min_keep, const int32_t* keep_in, uint32_t* mask_bits,
-                              int32_t* row_count, int32_t* row_cols, float* row_mass,
+                              float mass_target, int min_keep, const int32_t* keep_in, const LiveBlocks& live,
+                              uint32_t* mask_bits, int32_t* row_count, int32_t* row_cols, float* row_mass,
                               hipStream_t st) {
   if (rows_total == 0) return BASA_OK;
   dim3 grid(ceil_div(rows_total, 4));
   ProfScope prof(K_ROW_SELECT, st);
 #define BASA_SEL(M)                                                                            \
   hipLaunchKernelGGL((row_select_kernel<M>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
-                     kappa, mass_target, min_keep, keep_in, mask_bits, row_count, row_cols, row_mass)
+                     kappa, mass_target, min_keep, keep_in, live, mask_bits, row_count, row_cols, row_mass)
   if (Nk <= 256) BASA_SEL(4);
   else if (Nk <= 1024) BASA_SEL(16);
   else if (Nk <= 2048) BASA_SEL(32);

@@ -81,6 +81,9 @@ def test_select_argument_validation(lib):
     assert call(q, fake_tensor(L=4097 * 128), p)[0] == "BASA_ERR_UNSUPPORTED"   # more than 4096 key blocks
     assert call(q, k, bd.params(128, 0.5, mass_target=1.5))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=-0.1))[0] == "BASA_ERR_INVALID_ARG"
+    bad = bd.params(128, 0.5)
+    bad.causal = 2
+    assert call(q, k, bad)[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=0.9, min_keep=-1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, budget_total=-1))[0] == "BASA_ERR_INVALID_ARG"
     seg = lambda starts, **kw: bd.params(128, 0.5, segments=starts, **kw)
@@ -128,7 +131,9 @@ def test_workspace_sizes(lib):
     sel = lib.basa_select_workspace_size(C.byref(q), C.byref(k), C.byref(p))
     att = lib.basa_attn_workspace_size(C.byref(q), C.byref(k), C.byref(p))
     # attention workspace: tiled K and transposed V, padded to whole blocks (Q needs no copy)
-    assert (2 + 2) * 1024 * 128 * 2 <= att <= (2 + 2) * 1024 * 128 * 2 + 1024
+    # (+ 272 bytes per 64-key tile: the key indices of the causal variant; + the probe counters)
+    kv = (2 + 2) * 1024 * 128 * 2
+    assert kv + 2 * 16 * 272 <= att <= kv + 2 * 16 * 272 + 1024
     assert sel >= 2 * 4 * 1000 * 8
     assert lib.basa_select_workspace_size(C.byref(fake_tensor(d=96)), C.byref(k), C.byref(p)) == 0
 
