@@ -257,7 +257,8 @@ basa_status basa_profile_read(double* total_ms /*host*/, int32_t* launches /*hos
  * Oracle block distribution (Sec. 3.1, Eq. 3): m_hat[g_q, g_k] = mean over the query
  * tokens of block g_q of the dense attention weight (Eq. 1) that falls on the key tokens
  * of block g_k, for the ordered sequences Q[perm_q], K[perm_k] (NULL: original order).
- * bf16 tensors with d = 128 only (BASA_ERR_UNSUPPORTED otherwise).
+ * bf16 tensors run on the matrix cores (d = 64 or 128; with max_dev at most 8192 / (128 / B) key
+ * blocks, BASA_ERR_UNSUPPORTED beyond), f32 tensors on an exact-arithmetic kernel that is not tuned.
  *   base_logits  nullable [batch, heads_q, N_q, N_k] float: block logits l of Eq. 2
  *                (basa_select's `scores` with beta = 0); needed for max_dev.
  *   m_hat        out [batch, heads_q, N_q, N_k] float; every row sums to 1.

@@ -508,7 +508,8 @@ const char* basa_version(void) { return "basa 0.1 gfx950"; }
 
 size_t basa_block_mass_workspace_size(const basa_tensor* q, const basa_tensor* k) {
   if (check_qk(q, k) != BASA_OK) return 0;
-  return block_mass_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L);
+  if (q->dtype != BASA_BF16) return 256;      // the f32 kernel needs none; non-zero for callers
+  return block_mass_workspace_bytes(q->batch * q->heads, k->batch * k->heads, q->L, k->L, q->d);
 }
 
 basa_status basa_block_mass(const basa_tensor* q, const basa_tensor* k, const int32_t* perm_q,
@@ -518,10 +519,6 @@ basa_status basa_block_mass(const basa_tensor* q, const basa_tensor* k, const in
   basa_status s;
   if ((s = check_qk(q, k)) != BASA_OK) return s;
   if ((s = check_params(p, false)) != BASA_OK) return s;
-  if (q->dtype != BASA_BF16 || q->d != 128) {
-    set_error("basa_block_mass: only bf16 tensors with head dimension 128 are supported");
-    return BASA_ERR_UNSUPPORTED;
-  }
   if (!m_hat) { set_error("basa_block_mass: m_hat output is required"); return BASA_ERR_INVALID_ARG; }
   if (max_dev && !base_logits) {
     set_error("basa_block_mass: max_dev needs base_logits"); return BASA_ERR_INVALID_ARG;

@@ -143,8 +143,8 @@ size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B
 basa_status launch_attn_simple(const AttnArgs& a, hipStream_t st);
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st);
 
-// Selection-fidelity diagnostics (diag.hip).  block mass: bf16, d = 128 only.
-size_t block_mass_workspace_bytes(int BHq, int BHkv, int Lq, int Lk);
+// Selection-fidelity diagnostics (diag.hip).  block mass: bf16 on the matrix cores, f32 on a plain kernel.
+size_t block_mass_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d);
 basa_status launch_block_mass(const TensorView& q, const TensorView& k, const int32_t* perm_q,
                               const int32_t* perm_k, int B, const float* base_logits, float* m_hat,
                               float* max_dev, float* lse, void* ws, hipStream_t st);

@@ -16,6 +16,7 @@
 //   fidelity_rows_kernel    per row of the block map: sum of m_hat over the kept blocks
 //                       (recall) and || softmax(l') - m_hat ||_1
 //   pearson_sums_kernel     the six sums a Pearson correlation coefficient is made of
+#include <type_traits>
 #include "common.hpp"
 
 namespace basa {
@@ -24,14 +25,24 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kD = 128;
 constexpr int kTileKeys = 64;
-constexpr int kTileChunks = 1024;          // 16-byte chunks of one 64-key tile
 constexpr int kQueriesPerWg = 128;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+// Sizes that follow from the head dimension D (64 or 128).
+template <int D>
+struct MGeo {
+  static constexpr int kRowBytes = D * 2;
+  static constexpr int kCPR = D / 8;                          // 16-byte chunks per row
+  static constexpr int kTileBytes = kTileKeys * kRowBytes;    // 16 KB or 8 KB
+  static constexpr int kKSteps = D / 16;
+  static constexpr int kChunksPerTile = kTileBytes / 1024;    // 1 KB direct-to-LDS loads per tile
+};
 
 struct MassArgs {
-  const uint4* Qs;           // [BHq][rows_q][16 chunks]   ordered queries, zero rows past L_q
-  const uint4* Kt;           // [BHkv][tiles][64 rows][16 chunks], chunk c of row r at c ^ (r & 15)
+  const uint4* Qs;           // [BHq][rows_q][D/8 chunks]   ordered queries, zero rows past L_q
+  const char* Kt;            // [BHkv][tiles][64 rows][D/8 chunks], chunk c of row r at c ^ (r & (D/8 - 1))
   const int32_t* perm_q;     // nullable
   const float* base_logits;  // nullable [BHq][Nq][Nk]: l of Eq. 2
   float* m_hat;              // [BHq][Nq][Nk]
@@ -40,6 +51,24 @@ struct MassArgs {
   int Nq, Nk, Lq, Lk, group, rows_q, tiles;
   float scale_log2e, inv_sqrt_d;
 };
+
+// Wave-wide sum / max with the result in lane 63, by data-parallel-primitive moves between lanes
+// (no trip through the LDS crossbar): quads, half rows, rows of 16, then the row totals.
+template <int kCtrl, int kRowMask, bool kMax>
+__device__ __forceinline__ float dpp_step(float v) {
+  const float o = __int_as_float(__builtin_amdgcn_update_dpp(kMax ? (int)0xff800000 : 0, __float_as_int(v), kCtrl, kRowMask, 0xf, !kMax));
+  return kMax ? fmaxf(v, o) : v + o;
+}
+template <bool kMax>
+__device__ __forceinline__ float wave_reduce_to_lane63(float v) {
+  v = dpp_step<0xB1, 0xf, kMax>(v);     // quad_perm [1,0,3,2]
+  v = dpp_step<0x4E, 0xf, kMax>(v);     // quad_perm [2,3,0,1]
+  v = dpp_step<0x141, 0xf, kMax>(v);    // row_half_mirror
+  v = dpp_step<0x140, 0xf, kMax>(v);    // row_mirror
+  v = dpp_step<0x142, 0xa, kMax>(v);    // row_bcast:15 into rows 1 and 3
+  v = dpp_step<0x143, 0xc, kMax>(v);    // row_bcast:31 into rows 2 and 3
+  return v;
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -51,153 +80,315 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
   return v;
 }
+__device__ __forceinline__ float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-template <int kB, bool kDev>      // kDev: also the observed logit deviation (needs base_logits)
-__global__ __launch_bounds__(256) void block_mass_kernel(MassArgs a) {
+// S^T = K Q^T of one 64-key tile in LDS for this wave's 32 queries: two 32-key row blocks.
+template <int D>
+__device__ __forceinline__ void mass_scores(const char* ks, const bf16x8 (&qf)[MGeo<D>::kKSteps], int kaddr0,
+                                            floatx16& s0, floatx16& s1) {
+  s0 = floatx16{0}; s1 = floatx16{0};
+#pragma unroll
+  for (int s = 0; s < MGeo<D>::kKSteps; ++s) {
+    const int ka = kaddr0 ^ (s << 5);
+    const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + ka);
+    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + ka + 32 * MGeo<D>::kRowBytes);
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
+  }
+}
+
+// Dynamic LDS: [ring: 2 K tiles][logit rows: NQB x Nk floats (kDev)].  K tiles arrive by direct-to-LDS
+// loads one tile ahead, one workgroup barrier per tile; the ragged last tile is peeled so that the
+// masking code stays out of the loop; the running maximum of pass 0 is refreshed lazily; the tile
+// sums of pass 1 are kept per lane over the tiles of a key block and reduced once per key block.
+template <int kB, int D, bool kDev>      // kDev: also the observed logit deviation (needs base_logits)
+__global__ __launch_bounds__(256, 2) void block_mass_kernel(MassArgs a) {
+  using G = MGeo<D>;
   constexpr int NQB = kQueriesPerWg / kB;   // query blocks per workgroup: 1 or 2
   constexpr int WPG = kB / 32;              // waves per query block: 4 or 2
   constexpr int TPB = kB / kTileKeys;       // key tiles per key block: 2 or 1
-  __shared__ uint4 kbuf[2][kTileChunks];
+  constexpr int kLoadsPerWave = G::kChunksPerTile / 4;
+  constexpr float kLazyTau = 8.0f;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ float part_mass[2][4], part_dev[2][4];
+  float* lrow = reinterpret_cast<float*>(smem + 2 * G::kTileBytes);      // [NQB][Nk] (kDev)
 
   const int bhq = blockIdx.y, bhk = bhq / a.group, wg = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 31, h = lane >> 5;
-  const int gq = wg * NQB + wave / WPG;                 // may be >= Nq in the last workgroup
-  const int qpos = wg * kQueriesPerWg + wave * 32 + li; // ordered position of this lane's query
+  const int grp = wave / WPG;                            // query block of this wave inside the workgroup
+  const int qpos = wg * kQueriesPerWg + wave * 32 + li;  // ordered position of this lane's query
   const bool q_valid = qpos < a.Lq;
 
-  // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
-  bf16x8 qf[8];
+  // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for every k-step s
+  bf16x8 qf[G::kKSteps];
   {
-    const uint4* qp = a.Qs + ((int64_t)bhq * a.rows_q + qpos) * 16;
+    const uint4* qp = a.Qs + ((int64_t)bhq * a.rows_q + qpos) * G::kCPR;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < G::kKSteps; ++s) {
       uint4 t4 = qp[2 * s + h];
       qf[s] = *reinterpret_cast<bf16x8*>(&t4);
     }
   }
-  const uint4* Kh = a.Kt + (int64_t)bhk * a.tiles * kTileChunks;
-  const int kaddr0 = li * 256 + ((h ^ (li & 15)) << 4);
+  if (kDev) {
+    for (int i = tid; i < NQB * a.Nk; i += 256) {
+      const int gqb = min(wg * NQB + i / a.Nk, a.Nq - 1);
+      lrow[i] = a.base_logits[((int64_t)bhq * a.Nq + gqb) * a.Nk + i % a.Nk];
+    }
+  }
+  const char* Kh = a.Kt + (int64_t)bhk * a.tiles * G::kTileBytes;
+  const int kaddr0 = li * G::kRowBytes + ((h ^ (li & (G::kCPR - 1))) << 4);
   const float c = a.scale_log2e;
   const int T = a.tiles;
+  auto issue_tile = [&](int tile, int stage) {
+#pragma unroll
+    for (int j = 0; j < kLoadsPerWave; ++j) {
+      const int cb = j * 4 + wave;
+      const char* src = Kh + (int64_t)tile * G::kTileBytes + cb * 1024 + (uint32_t)(lane * 16);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(smem + stage * G::kTileBytes + cb * 1024), 16, 0, 0);
+    }
+  };
 
-  float m_run = -INFINITY, l_run = 0.f, lse2 = 0.f;
-  for (int pass = 0; pass < 2; ++pass) {
-    uint4 r[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) kbuf[0][i * 256 + tid] = Kh[i * 256 + tid];
-    __syncthreads();
-    float acc_mass = 0.f, acc_dev = 0.f;     // used by threads tid < NQB in pass 1
-    for (int t = 0; t < T; ++t) {
-      // next tile into registers (past the end: the last tile again, stored but never used;
-      // kept unconditional so that r stays in registers and the loads stay in flight)
-      {
-        const int tn = min(t + 1, T - 1);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[i] = Kh[(int64_t)tn * kTileChunks + i * 256 + tid];
-      }
-      const char* ks = reinterpret_cast<const char*>(kbuf[t & 1]);
-      floatx16 s0 = {0}, s1 = {0};
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const int ka = kaddr0 ^ (s << 5);
-        const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(ks + ka);
-        const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(ks + ka + 32 * 256);
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], s1, 0, 0, 0);
-      }
-      // register r of lane half h holds key 8*(r/4) + 4h + r%4 of its 32-key half
+  // ---- pass 0: log-sum-exp of every query over all keys (online softmax, lazy running maximum)
+  float m_run = -INFINITY, l_run = 0.f;
+  auto lse_tile = [&](auto masked, int t) {
+    floatx16 s0, s1;
+    mass_scores<D>(smem + (t & 1) * G::kTileBytes, qf, kaddr0, s0, s1);
+    if (decltype(masked)::value) {
       const int nvalid = a.Lk - t * kTileKeys;          // >= 1
-      if (pass == 0) {
-        float mx = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const int kk = 8 * (q >> 2) + 4 * h + (q & 3);
-          if (kk >= nvalid) s0[q] = -INFINITY;
-          if (32 + kk >= nvalid) s1[q] = -INFINITY;
-          mx = fmaxf(mx, fmaxf(s0[q], s1[q]));
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * c);
-        float sum = 0.f;
-#pragma unroll
-        for (int q = 0; q < 16; ++q)
-          sum += __builtin_amdgcn_exp2f(fmaf(s0[q], c, -m_new)) + __builtin_amdgcn_exp2f(fmaf(s1[q], c, -m_new));
-        l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + sum;
-        m_run = m_new;
-      } else {
-        float lblk = 0.f;
-        if (kDev && gq < a.Nq) lblk = a.base_logits[((int64_t)bhq * a.Nq + gq) * a.Nk + t / TPB];
-        float sum = 0.f, dev = 0.f;
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const int kk = 8 * (q >> 2) + 4 * h + (q & 3);
-          if (kk < nvalid) {
-            sum += __builtin_amdgcn_exp2f(fmaf(s0[q], c, -lse2));
-            if (kDev) dev = fmaxf(dev, fabsf(s0[q] * a.inv_sqrt_d - lblk));
-          }
-          if (32 + kk < nvalid) {
-            sum += __builtin_amdgcn_exp2f(fmaf(s1[q], c, -lse2));
-            if (kDev) dev = fmaxf(dev, fabsf(s1[q] * a.inv_sqrt_d - lblk));
-          }
-        }
-        if (!q_valid) { sum = 0.f; dev = 0.f; }
-        sum = wave_sum(sum);
-        if (kDev) dev = wave_max(dev);
-        if (lane == 0) { part_mass[t & 1][wave] = sum; part_dev[t & 1][wave] = dev; }
+      for (int q = 0; q < 16; ++q) {
+        const int kk = 8 * (q >> 2) + 4 * h + (q & 3);
+        if (kk >= nvalid) s0[q] = -INFINITY;
+        if (32 + kk >= nvalid) s1[q] = -INFINITY;
       }
+    }
+    float mx = max3f(s0[0], s1[0], s0[1]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) kbuf[(t + 1) & 1][i * 256 + tid] = r[i];
-      __syncthreads();
-      if (pass == 1 && tid < NQB) {
-        // thread b adds up, in a fixed order, the waves of query block b and the tiles of a key block
-        const int gqb = wg * NQB + tid;
-        if (gqb < a.Nq) {
+    for (int q = 1; q < 15; ++q) mx = max3f(mx, s1[q], s0[q + 1]);
+    mx = fmaxf(mx, s1[15]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mc = mx * c;
+    if (__builtin_amdgcn_ballot_w64(mc > m_run + kLazyTau) != 0) {
+      const float m_new = fmaxf(m_run, mc);
+      l_run *= __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+    }
+    float sum = 0.f;
 #pragma unroll
-          for (int w = 0; w < WPG; ++w) {
-            acc_mass += part_mass[t & 1][tid * WPG + w];
-            acc_dev = fmaxf(acc_dev, part_dev[t & 1][tid * WPG + w]);
+    for (int q = 0; q < 16; ++q)
+      sum += __builtin_amdgcn_exp2f(fmaf(s0[q], c, -m_run)) + __builtin_amdgcn_exp2f(fmaf(s1[q], c, -m_run));
+    l_run += sum;
+  };
+  issue_tile(0, 0);
+  for (int t = 0; t + 1 < T; ++t) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    issue_tile(t + 1, (t + 1) & 1);
+    lse_tile(std::false_type{}, t);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  lse_tile(std::true_type{}, T - 1);
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float lse2 = m_run + __log2f(l_tot);
+  if (a.lse && q_valid && h == 0) {
+    const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq);
+    a.lse[(int64_t)bhq * a.Lq + orow] = lse2 * 0.6931471805599453f;
+  }
+  __syncthreads();               // every wave is done with the ring before tile 0 lands in it again
+
+  // ---- pass 1: exponentiate against the log-sum-exp, add up every key block
+  float acc_sum = 0.f, acc_dev = 0.f;      // this lane's share of the current key block
+  auto mass_tile = [&](auto masked, int t) {
+    floatx16 s0, s1;
+    mass_scores<D>(smem + (t & 1) * G::kTileBytes, qf, kaddr0, s0, s1);
+    float lblk = 0.f;
+    if (kDev) lblk = lrow[grp * a.Nk + t / TPB];
+    float sum = 0.f, dev = 0.f;
+    if (decltype(masked)::value) {
+      const int nvalid = a.Lk - t * kTileKeys;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int kk = 8 * (q >> 2) + 4 * h + (q & 3);
+        if (kk < nvalid) {
+          sum += __builtin_amdgcn_exp2f(fmaf(s0[q], c, -lse2));
+          if (kDev) dev = fmaxf(dev, fabsf(fmaf(s0[q], a.inv_sqrt_d, -lblk)));
+        }
+        if (32 + kk < nvalid) {
+          sum += __builtin_amdgcn_exp2f(fmaf(s1[q], c, -lse2));
+          if (kDev) dev = fmaxf(dev, fabsf(fmaf(s1[q], a.inv_sqrt_d, -lblk)));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        sum += __builtin_amdgcn_exp2f(fmaf(s0[q], c, -lse2)) + __builtin_amdgcn_exp2f(fmaf(s1[q], c, -lse2));
+        if (kDev) dev = max3f(dev, fabsf(fmaf(s0[q], a.inv_sqrt_d, -lblk)), fabsf(fmaf(s1[q], a.inv_sqrt_d, -lblk)));
+      }
+    }
+    if (q_valid) { acc_sum += sum; acc_dev = fmaxf(acc_dev, dev); }
+    if ((t % TPB) == TPB - 1 || t == T - 1) {
+      // end of a key block: this wave's total to LDS (lane 63 holds it); combined after the next barrier
+      const float ws = wave_reduce_to_lane63<false>(acc_sum);
+      const float wd = kDev ? wave_reduce_to_lane63<true>(acc_dev) : 0.f;
+      if (lane == 63) { part_mass[(t / TPB) & 1][wave] = ws; part_dev[(t / TPB) & 1][wave] = wd; }
+      acc_sum = 0.f; acc_dev = 0.f;
+    }
+  };
+  // thread b < NQB adds up, in a fixed order, the waves of query block b for key block kb
+  auto combine = [&](int kb) {
+    if (tid < NQB) {
+      const int gqb = wg * NQB + tid;
+      if (gqb < a.Nq) {
+        float m = 0.f, dv = 0.f;
+#pragma unroll
+        for (int w = 0; w < WPG; ++w) {
+          m += part_mass[kb & 1][tid * WPG + w];
+          dv = fmaxf(dv, part_dev[kb & 1][tid * WPG + w]);
+        }
+        const int n_q = min(kB, a.Lq - gqb * kB);
+        const int64_t o = ((int64_t)bhq * a.Nq + gqb) * a.Nk + kb;
+        a.m_hat[o] = m / (float)n_q;
+        if (kDev) a.max_dev[o] = dv;
+      }
+    }
+  };
+  issue_tile(0, 0);
+  for (int t = 0; t + 1 < T; ++t) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t > 0 && (t % TPB) == 0) combine(t / TPB - 1);      // the key block that ended with tile t-1
+    issue_tile(t + 1, (t + 1) & 1);
+    mass_tile(std::false_type{}, t);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (T > 1 && ((T - 1) % TPB) == 0) combine((T - 1) / TPB - 1);
+  mass_tile(std::true_type{}, T - 1);
+  __syncthreads();
+  combine((T - 1) / TPB);
+}
+
+// Exact-arithmetic variant for f32 tensors (any supported d and B): one thread per query of a query
+// block, keys staged through LDS 16 at a time; pass 0 the log-sum-exp, pass 1 the block masses and
+// deviations, reduced over the block's threads in a fixed order.  Not tuned: fp32 inputs are the
+// small parity workloads.
+template <int kDim, int kB>
+__global__ __launch_bounds__(kB) void block_mass_simple_kernel(TensorView q, TensorView k, const int32_t* __restrict__ perm_q,
+                                                               const int32_t* __restrict__ perm_k,
+                                                               const float* __restrict__ base_logits,
+                                                               float* __restrict__ m_hat, float* __restrict__ max_dev,
+                                                               float* __restrict__ lse_out, int Nq, int Nk) {
+  constexpr int kTK = 16;
+  __shared__ __attribute__((aligned(16))) float Ks[kTK][kDim];
+  __shared__ float red_s[kB], red_d[kB];
+  const int gq = blockIdx.x, bhq = blockIdx.y, bhk = bhq / (q.heads / k.heads);
+  const int Lq = q.L, Lk = k.L;
+  const int pos = gq * kB + threadIdx.x;
+  const bool active = pos < Lq;
+  const int qrow = active ? perm_at(perm_q, (int64_t)bhq * Lq, pos, Lq) : 0;
+  float qv[kDim];
+  {
+    const float4* qp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(q.ptr) + q.head_offset(bhq) +
+                                                       (int64_t)qrow * q.stride_l);
+#pragma unroll
+    for (int t = 0; t < kDim / 4; ++t) {
+      const float4 v = qp[t];
+      qv[4 * t] = v.x; qv[4 * t + 1] = v.y; qv[4 * t + 2] = v.z; qv[4 * t + 3] = v.w;
+    }
+  }
+  const float* kbase = reinterpret_cast<const float*>(k.ptr) + k.head_offset(bhk);
+  const float scale = 1.0f / sqrtf((float)kDim);
+  const int n_q = min(kB, Lq - gq * kB);
+  float m = -INFINITY, l = 0.f, lse = 0.f;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int gk = 0; gk < Nk; ++gk) {
+      const int kvalid = min(kB, Lk - gk * kB);
+      float bsum = 0.f, bdev = 0.f;
+      const float lblk = (pass == 1 && max_dev) ? base_logits[((int64_t)bhq * Nq + gq) * Nk + gk] : 0.f;
+      for (int t0 = 0; t0 < kvalid; t0 += kTK) {
+        const int nk = min(kTK, kvalid - t0);
+        __syncthreads();
+        for (int w = threadIdx.x; w < kTK * (kDim / 4); w += kB) {
+          const int j = w / (kDim / 4), c4 = w - j * (kDim / 4);
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (j < nk) {
+            const int krow = perm_at(perm_k, (int64_t)bhk * Lk, gk * kB + t0 + j, Lk);
+            v = reinterpret_cast<const float4*>(kbase + (int64_t)krow * k.stride_l)[c4];
           }
-          if ((t % TPB) == TPB - 1 || t == T - 1) {
-            const int n_q = min(kB, a.Lq - gqb * kB);
-            const int64_t o = ((int64_t)bhq * a.Nq + gqb) * a.Nk + t / TPB;
-            a.m_hat[o] = acc_mass / (float)n_q;
-            if (kDev) a.max_dev[o] = acc_dev;
-            acc_mass = 0.f;
-            acc_dev = 0.f;
+          *reinterpret_cast<float4*>(&Ks[j][4 * c4]) = v;
+        }
+        __syncthreads();
+        float s[kTK], tmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < kTK; ++j) {
+          float d0 = 0.f;
+#pragma unroll
+          for (int t = 0; t < kDim; ++t) d0 = fmaf(qv[t], Ks[j][t], d0);
+          s[j] = (j < nk) ? d0 * scale : -INFINITY;
+          tmax = fmaxf(tmax, s[j]);
+        }
+        if (pass == 0) {
+          const float m_new = fmaxf(m, tmax);
+          l *= expf(m - m_new);
+#pragma unroll
+          for (int j = 0; j < kTK; ++j) l += expf(s[j] - m_new);
+          m = m_new;
+        } else {
+#pragma unroll
+          for (int j = 0; j < kTK; ++j) {
+            bsum += expf(s[j] - lse);                         // keys past the block: exp(-inf) = 0
+            if (j < nk) bdev = fmaxf(bdev, fabsf(s[j] - lblk));
           }
+        }
+      }
+      if (pass == 1) {
+        // the block's queries added up in a fixed order (tree over the threads)
+        __syncthreads();
+        red_s[threadIdx.x] = active ? bsum : 0.f;
+        red_d[threadIdx.x] = active ? bdev : 0.f;
+        __syncthreads();
+        for (int off = kB / 2; off > 0; off >>= 1) {
+          if ((int)threadIdx.x < off) {
+            red_s[threadIdx.x] += red_s[threadIdx.x + off];
+            red_d[threadIdx.x] = fmaxf(red_d[threadIdx.x], red_d[threadIdx.x + off]);
+          }
+          __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+          const int64_t o = ((int64_t)bhq * Nq + gq) * Nk + gk;
+          m_hat[o] = red_s[0] / (float)n_q;
+          if (max_dev) max_dev[o] = red_d[0];
         }
       }
     }
     if (pass == 0) {
-      const float l_tot = l_run + __shfl_xor(l_run, 32);
-      lse2 = m_run + __log2f(l_tot);
-      if (a.lse && q_valid && h == 0) {
-        const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq);
-        a.lse[(int64_t)bhq * a.Lq + orow] = lse2 * 0.6931471805599453f;
-      }
+      lse = m + logf(l);
+      if (lse_out && active) lse_out[(int64_t)bhq * Lq + qrow] = lse;
     }
-    // the last iteration ended with a barrier: kbuf[0] may be refilled
   }
 }
 
 // Rows of a bf16 tensor in the given order, zero rows up to rows_padded; swizzle = 1 writes
-// the K-tile image (chunk c of row r at chunk position c ^ (r & 15)).
+// the K-tile image (chunk c of row r at chunk position c ^ (r & (chunks per row - 1))).
+template <int D>
 __global__ __launch_bounds__(256) void diag_gather_rows_kernel(TensorView x, const int32_t* __restrict__ perm,
                                                                uint4* __restrict__ dst, int rows_padded,
                                                                int swizzle) {
+  constexpr int CPR = D / 8, RPI = 256 / CPR, ITERS = 64 / RPI;
   const int bh = blockIdx.y;
-  const int sub = threadIdx.x & 15, rig = threadIdx.x >> 4;
+  const int sub = threadIdx.x % CPR, rig = threadIdx.x / CPR;
   const int32_t* pm = perm ? perm + (int64_t)bh * x.L : nullptr;
   const char* base = reinterpret_cast<const char*>(x.ptr) + x.head_offset(bh) * 2;
-  uint4 v[4];
-  gather_chunks<4>(v, pm, base, x.L, (int64_t)x.stride_l * 2, blockIdx.x * 64 + rig, 16, sub);
+  uint4 v[ITERS];
+  gather_chunks<ITERS>(v, pm, base, x.L, (int64_t)x.stride_l * 2, blockIdx.x * 64 + rig, RPI, sub);
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int pos = blockIdx.x * 64 + it * 16 + rig;
-    const int cpos = swizzle ? (sub ^ (pos & 15)) : sub;
-    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * 16 + cpos] = v[it];
+  for (int it = 0; it < ITERS; ++it) {
+    const int pos = blockIdx.x * 64 + it * RPI + rig;
+    const int cpos = swizzle ? (sub ^ (pos & (CPR - 1))) : sub;
+    if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * CPR + cpos] = v[it];
   }
 }
 
@@ -351,43 +542,83 @@ __global__ void zero_doubles_kernel(double* p, int n) {
   if ((int)threadIdx.x < n) p[threadIdx.x] = 0.0;
 }
 
-size_t q_bytes(int BHq, int Lq) { return align_up((size_t)BHq * ceil_div(Lq, kQueriesPerWg) * kQueriesPerWg * kD * 2, 256); }
-size_t k_bytes(int BHkv, int Lk) { return align_up((size_t)BHkv * ceil_div(Lk, kTileKeys) * kTileKeys * kD * 2, 256); }
+size_t q_bytes(int BHq, int Lq, int d) { return align_up((size_t)BHq * ceil_div(Lq, kQueriesPerWg) * kQueriesPerWg * d * 2, 256); }
+size_t k_bytes(int BHkv, int Lk, int d) { return align_up((size_t)BHkv * ceil_div(Lk, kTileKeys) * kTileKeys * d * 2, 256); }
+
+template <int D>
+basa_status launch_block_mass_mfma(const TensorView& q, const TensorView& k, const int32_t* perm_q,
+                                   const int32_t* perm_k, int B, const float* base_logits, float* m_hat,
+                                   float* max_dev, float* lse, void* ws, hipStream_t st) {
+  const int BHq = q.batch * q.heads, BHkv = k.batch * k.heads;
+  const int rows_q = ceil_div(q.L, kQueriesPerWg) * kQueriesPerWg, tiles = ceil_div(k.L, kTileKeys);
+  uint4* Qs = reinterpret_cast<uint4*>(ws);
+  uint4* Kt = reinterpret_cast<uint4*>(reinterpret_cast<char*>(ws) + q_bytes(BHq, q.L, D));
+  {
+    ProfScope prof(K_GATHER, st);
+    hipLaunchKernelGGL(diag_gather_rows_kernel<D>, dim3(rows_q / 64, BHq), dim3(256), 0, st, q, perm_q, Qs, rows_q, 0);
+    BASA_HIP_CHECK_LAUNCH("diag_gather_rows_kernel(Q)");
+    hipLaunchKernelGGL(diag_gather_rows_kernel<D>, dim3(tiles, BHkv), dim3(256), 0, st, k, perm_k, Kt, tiles * kTileKeys, 1);
+    BASA_HIP_CHECK_LAUNCH("diag_gather_rows_kernel(K)");
+  }
+  MassArgs a;
+  a.Qs = Qs; a.Kt = reinterpret_cast<const char*>(Kt); a.perm_q = perm_q; a.base_logits = base_logits;
+  a.m_hat = m_hat; a.max_dev = max_dev; a.lse = lse;
+  a.Nq = ceil_div(q.L, B); a.Nk = ceil_div(k.L, B); a.Lq = q.L; a.Lk = k.L;
+  a.group = q.heads / k.heads; a.rows_q = rows_q; a.tiles = tiles;
+  a.scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  a.inv_sqrt_d = 1.0f / sqrtf((float)D);
+  const bool want_dev = max_dev != nullptr && base_logits != nullptr;
+  const size_t lds = 2 * MGeo<D>::kTileBytes + (want_dev ? (size_t)(kQueriesPerWg / B) * a.Nk * sizeof(float) : 0);
+  if (lds > 64 * 1024) {
+    set_error("block mass: %d key blocks need %zu bytes of LDS per workgroup (limit 65536)", a.Nk, lds);
+    return BASA_ERR_UNSUPPORTED;
+  }
+  ProfScope prof(K_BLOCK_MASS, st);
+  const dim3 grid(rows_q / kQueriesPerWg, BHq);
+#define BASA_MASS(BB, DEV)                                                                                     \
+  do {                                                                                                         \
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_mass_kernel<BB, D, DEV>),    \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");                               \
+    hipLaunchKernelGGL((block_mass_kernel<BB, D, DEV>), grid, dim3(256), lds, st, a);                          \
+  } while (0)
+  if (B == 128 && want_dev) BASA_MASS(128, true);
+  else if (B == 128) BASA_MASS(128, false);
+  else if (want_dev) BASA_MASS(64, true);
+  else BASA_MASS(64, false);
+#undef BASA_MASS
+  BASA_HIP_CHECK_LAUNCH("block_mass_kernel");
+  return BASA_OK;
+}
 
 }  // namespace
 
-size_t block_mass_workspace_bytes(int BHq, int BHkv, int Lq, int Lk) { return q_bytes(BHq, Lq) + k_bytes(BHkv, Lk); }
+size_t block_mass_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d) {
+  return q_bytes(BHq, Lq, d) + k_bytes(BHkv, Lk, d);
+}
 
 basa_status launch_block_mass(const TensorView& q, const TensorView& k, const int32_t* perm_q,
                               const int32_t* perm_k, int B, const float* base_logits, float* m_hat,
                               float* max_dev, float* lse, void* ws, hipStream_t st) {
-  const int BHq = q.batch * q.heads, BHkv = k.batch * k.heads;
+  const int BHq = q.batch * q.heads;
   if (BHq == 0 || q.L == 0 || k.L == 0) return BASA_OK;
-  const int rows_q = ceil_div(q.L, kQueriesPerWg) * kQueriesPerWg, tiles = ceil_div(k.L, kTileKeys);
-  uint4* Qs = reinterpret_cast<uint4*>(ws);
-  uint4* Kt = reinterpret_cast<uint4*>(reinterpret_cast<char*>(ws) + q_bytes(BHq, q.L));
-  {
-    ProfScope prof(K_GATHER, st);
-    hipLaunchKernelGGL(diag_gather_rows_kernel, dim3(rows_q / 64, BHq), dim3(256), 0, st, q, perm_q, Qs, rows_q, 0);
-    BASA_HIP_CHECK_LAUNCH("diag_gather_rows_kernel(Q)");
-    hipLaunchKernelGGL(diag_gather_rows_kernel, dim3(tiles, BHkv), dim3(256), 0, st, k, perm_k, Kt, tiles * kTileKeys, 1);
-    BASA_HIP_CHECK_LAUNCH("diag_gather_rows_kernel(K)");
+  if (q.dtype == BASA_BF16) {
+    return q.d == 128 ? launch_block_mass_mfma<128>(q, k, perm_q, perm_k, B, base_logits, m_hat, max_dev, lse, ws, st)
+                      : launch_block_mass_mfma<64>(q, k, perm_q, perm_k, B, base_logits, m_hat, max_dev, lse, ws, st);
   }
-  MassArgs a;
-  a.Qs = Qs; a.Kt = Kt; a.perm_q = perm_q; a.base_logits = base_logits;
-  a.m_hat = m_hat; a.max_dev = max_dev; a.lse = lse;
-  a.Nq = ceil_div(q.L, B); a.Nk = ceil_div(k.L, B); a.Lq = q.L; a.Lk = k.L;
-  a.group = q.heads / k.heads; a.rows_q = rows_q; a.tiles = tiles;
-  a.scale_log2e = 1.4426950408889634f / sqrtf((float)kD);
-  a.inv_sqrt_d = 1.0f / sqrtf((float)kD);
+  // f32 tensors: the exact-arithmetic kernel, no workspace
+  const int Nq = ceil_div(q.L, B), Nk = ceil_div(k.L, B);
+  float* dev_out = (max_dev && base_logits) ? max_dev : nullptr;
   ProfScope prof(K_BLOCK_MASS, st);
-  const dim3 grid(rows_q / kQueriesPerWg, BHq);
-  const bool want_dev = max_dev != nullptr && base_logits != nullptr;
-  if (B == 128 && want_dev) hipLaunchKernelGGL((block_mass_kernel<128, true>), grid, dim3(256), 0, st, a);
-  else if (B == 128) hipLaunchKernelGGL((block_mass_kernel<128, false>), grid, dim3(256), 0, st, a);
-  else if (want_dev) hipLaunchKernelGGL((block_mass_kernel<64, true>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((block_mass_kernel<64, false>), grid, dim3(256), 0, st, a);
-  BASA_HIP_CHECK_LAUNCH("block_mass_kernel");
+  const dim3 grid(Nq, BHq);
+#define BASA_MS(DD, BB) \
+  hipLaunchKernelGGL((block_mass_simple_kernel<DD, BB>), grid, dim3(BB), 0, st, q, k, perm_q, perm_k, base_logits, m_hat, dev_out, lse, Nq, Nk)
+  if (q.d == 128 && B == 128) BASA_MS(128, 128);
+  else if (q.d == 128) BASA_MS(128, 64);
+  else if (B == 128) BASA_MS(64, 128);
+  else BASA_MS(64, 64);
+#undef BASA_MS
+  BASA_HIP_CHECK_LAUNCH("block_mass_simple_kernel");
   return BASA_OK;
 }
 

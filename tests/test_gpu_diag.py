@@ -14,12 +14,17 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 C = synth.CONFIGS
 
-# bf16, d = 128 workloads (what the matrix-core kernel supports), ragged and GQA cases included
+# bf16 workloads on the matrix-core kernel (d = 128 and d = 64), ragged and GQA cases included, and the
+# f32 configuration on the exact-arithmetic kernel
 CASES = [
     C[1].scaled("lowrank_b64", heads_q=2, heads_kv=2, L=1536 + 64 * 3 + 17, salient_frac=0.05),
     C[4].scaled("lowrank_b128", heads_q=2, heads_kv=2, L=2048 + 128 + 5, salient_frac=0.05),
     C[2].scaled("multimodal_gqa", heads_q=4, heads_kv=2, L=2048, image_side=16),
     C[3].scaled("video_ragged", heads_q=2, heads_kv=2, L=4 * 20 * 21, video_thw=(4, 20, 21)),
+    C[0].scaled("tiny_bf16_d64", dtype="bf16", L=900),
+    C[1].scaled("lowrank_d64_b128", heads_q=2, heads_kv=1, d=64, block=128, L=1024 + 128 + 77, salient_frac=0.05),
+    C[0],
+    C[0].scaled("tiny_f32_d128_ragged", L=700, d=128, block=128, heads_q=2, heads_kv=1),
 ]
 
 
@@ -97,9 +102,19 @@ def test_selection_fidelity_and_pearson():
                                rtol=1e-12)
 
 
-def test_block_mass_rejects_unsupported_types():
-    w = C[0]                              # fp32, d = 64
+def test_block_mass_without_deviation_output_and_its_limit():
+    w = CASES[4]
     Q, K, _ = synth.make_qkv(w, device=DEV)
+    m_hat, dev, lse = bd.basa_block_mass(Q, K, w.block)
+    torch.cuda.synchronize()
+    assert dev is None and lse is None
+    want = o.oracle_block_mass(np64(Q[0, 0]), np64(K[0, 0]), w.block)
+    np.testing.assert_allclose(m_hat[0, 0].cpu().numpy(), want, rtol=2e-4, atol=1e-7)
+    # the deviation output keeps a row of block logits per query block in LDS: B = 64 allows 4096 key blocks
+    L = 64 * 4097
+    q = torch.zeros((1, 1, 64, 128), dtype=torch.bfloat16, device=DEV)
+    k = torch.zeros((1, 1, L, 128), dtype=torch.bfloat16, device=DEV)
+    base = torch.zeros((1, 1, 1, 4097), dtype=torch.float32, device=DEV)
     with pytest.raises(bd.BasaError) as e:
-        bd.basa_block_mass(Q, K, w.block)
+        bd.basa_block_mass(q, k, 64, base_logits=base, want_dev=True)
     assert e.value.status_name == "BASA_ERR_UNSUPPORTED"
