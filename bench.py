@@ -383,8 +383,6 @@ def main():
     if args.fidelity:
         table = []
         for c in synth.CONFIGS:
-            if c.dtype != "bf16" or c.d != 128:
-                continue
             q2, k2, _ = synth.make_qkv(c, device=dev)
             table += fidelity_report(c, q2, k2, c.sparsities if 0.5 in c.sparsities else (0.5,) + tuple(c.sparsities))
             del q2, k2
@@ -460,8 +458,9 @@ def main():
                         | {"variant": f"cumulative mass {p_mass}"})
         del Q, K, V
         torch.cuda.empty_cache()
-        for c in synth.CONFIGS:
-            if c.index == w.index:
+        # the headline workload with head dimension 64 (same generator), then the other configurations
+        for c in [w.scaled(w.name + "_d64", d=64)] + list(synth.CONFIGS):
+            if c.index == w.index and c.d == w.d:
                 continue
             q2, k2, v2 = synth.make_qkv(c, device=dev)
             for s in c.sparsities:

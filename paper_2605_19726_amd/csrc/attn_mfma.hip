@@ -431,10 +431,12 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4 (SOLO: 1 or 2)
   if (a.probe) {
     // the other shape of workgroup is launched too; exactly one of the two does the work.  A
-    // 512-query workgroup walks the union of its 512 / B lists, a 128-query one its own list at
-    // about 1.16x the time per tile, so it wins when the union exceeds 1.16 average lists.
-    const int uni = a.probe[0], listed = a.probe[1];
-    const bool little_overlap = 100 * (int64_t)uni * (kWideQueries / kB) > 116 * (int64_t)listed;
+    // 512-query workgroup walks the union of its 512 / B lists; four 128-query ones walk the
+    // unions of their own 128 / B lists.  Measured break-even (wide 26.4 against 27.1 ms at a
+    // ratio of 1.29, 157.7 against 143.6 ms at 1.64): the narrow shape wins once the wide union
+    // exceeds about 1.35 times the average narrow one.
+    const int uni = a.probe[0], uni_sub = a.probe[1];
+    const bool little_overlap = 100 * (int64_t)uni * 4 > 135 * (int64_t)uni_sub;
     if ((int)little_overlap != a.run_if_solo) return;
   }
   constexpr int TPB = kB / kTileKeys;        // key tiles per key block: 2 or 1
@@ -810,41 +812,54 @@ __global__ __launch_bounds__(64) void key_index_kernel(const int32_t* __restrict
 
 // How much the lists of the query blocks that would share a 512-query workgroup have in common, on
 // every kProbeStride-th such group of gsz = 512 / B neighbouring blocks: probe[0] += blocks in the
-// union of the group's lists, probe[1] += blocks in its lists.  One wave per group: the lists are
-// or-ed into a bitmap in LDS, whose set bits are the union.
+// union of the group's lists (what a 512-query workgroup walks), probe[1] += the same for each of
+// the group's four 128-query subgroups, added up (what four 128-query workgroups walk; for B = 128
+// simply the blocks in the four lists).  One wave per group: the lists are or-ed into bitmaps in LDS.
 constexpr int kProbeStride = 8, kProbeMaxBlocks = 8192;
 __global__ __launch_bounds__(256) void list_overlap_kernel(const int32_t* __restrict__ row_count,
                                                            const int32_t* __restrict__ row_cols, int cols_stride,
                                                            int Nq, int Nk, int gsz, int groups_total,
                                                            int32_t* __restrict__ probe) {
-  __shared__ uint32_t bits[4][kProbeMaxBlocks / 32];
+  __shared__ uint32_t bits[4][kProbeMaxBlocks / 32], sub[4][kProbeMaxBlocks / 32];
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int group = (blockIdx.x * 4 + wv) * kProbeStride;
   const bool active = group < groups_total;             // no early exit: every wave meets the barriers
   const int groups_per_head = Nq / gsz;
   const int bh = active ? group / groups_per_head : 0, g0 = active ? (group - bh * groups_per_head) * gsz : 0;
   const unsigned limit = (unsigned)min(Nk, kProbeMaxBlocks);
-  for (int w = lane; w < kProbeMaxBlocks / 32; w += 64) bits[wv][w] = 0u;
-  __syncthreads();
-  int listed = 0;
-  for (int r = 0; r < gsz; ++r) {
-    const int64_t row = (int64_t)bh * Nq + g0 + r;
-    const int n = active ? max(0, min(row_count[row], cols_stride)) : 0;
-    const int32_t* A = row_cols + row * cols_stride;
-    for (int i = lane; i < n; i += 64) {
-      const unsigned v = (unsigned)A[i];
-      if (v < limit) atomicOr(&bits[wv][v >> 5], 1u << (v & 31));
+  const int words = (int)((limit + 31) >> 5);
+  const int rows_per_sub = gsz / 4;                     // query blocks of a 128-query subgroup: 1 or 2
+  for (int w = lane; w < words; w += 64) bits[wv][w] = 0u;
+  int uni_sub = 0;
+  for (int sg = 0; sg < 4; ++sg) {
+    for (int w = lane; w < words; w += 64) sub[wv][w] = 0u;
+    __syncthreads();
+    for (int r = 0; r < rows_per_sub; ++r) {
+      const int64_t row = (int64_t)bh * Nq + g0 + sg * rows_per_sub + r;
+      const int n = active ? max(0, min(row_count[row], cols_stride)) : 0;
+      const int32_t* A = row_cols + row * cols_stride;
+      for (int i = lane; i < n; i += 64) {
+        const unsigned v = (unsigned)A[i];
+        if (v < limit) atomicOr(&sub[wv][v >> 5], 1u << (v & 31));
+      }
     }
-    listed += n;
+    __syncthreads();
+    for (int w = lane; w < words; w += 64) {
+      const uint32_t x = sub[wv][w];
+      uni_sub += __popc(x);
+      bits[wv][w] |= x;                                  // word w belongs to this lane in every round
+    }
   }
-  __syncthreads();
   int uni = 0;
-  for (int w = lane; w < kProbeMaxBlocks / 32; w += 64) uni += __popc(bits[wv][w]);
+  for (int w = lane; w < words; w += 64) uni += __popc(bits[wv][w]);
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) uni += __shfl_xor(uni, off);
+  for (int off = 32; off > 0; off >>= 1) {
+    uni += __shfl_xor(uni, off);
+    uni_sub += __shfl_xor(uni_sub, off);
+  }
   if (active && lane == 0) {
     atomicAdd(&probe[0], uni);
-    atomicAdd(&probe[1], listed);
+    atomicAdd(&probe[1], uni_sub);
   }
 }
 __global__ void zero_probe_kernel(int32_t* probe) {
