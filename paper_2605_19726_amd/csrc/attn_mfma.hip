@@ -891,6 +891,15 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   const int Nq = ceil_div(a.q.L, B), Nk = ceil_div(a.k.L, B);
   if (BHq == 0 || Nq == 0) return BASA_OK;
   const int d = a.q.d;
+  // While a workgroup builds its union list, one membership word per key block lives in the ring
+  // area, whose smallest form is two stages: more key blocks than that cannot be listed.
+  {
+    const size_t cap = (d == 128 ? (size_t)2 * Geo<128>::kStageBytes : (size_t)2 * Geo<64>::kStageBytes) / 4;
+    if ((size_t)Nk > cap) {
+      set_error("attention: %d key blocks per head exceed the %zu this kernel can list (head dimension %d)", Nk, cap, d);
+      return BASA_ERR_UNSUPPORTED;
+    }
+  }
   // the largest LDS request among the shapes that may be launched
   const size_t lds = d == 128 ? std::max(lds_bytes<128>(512, 32, Nk), lds_bytes<128>(512, 64, Nk))
                               : std::max(lds_bytes<64>(512, 32, Nk), lds_bytes<64>(512, 64, Nk));

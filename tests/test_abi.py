@@ -115,6 +115,10 @@ def test_attention_argument_validation(lib):
     assert call(q, k, v, out=None)[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, v, out=C.c_void_p(0x2004))[0] == "BASA_ERR_INVALID_ARG"            # misaligned
     assert call(q, k, v)[0] == "BASA_ERR_WORKSPACE"
+    # more key blocks than a workgroup can list: refused on the host, before any device call
+    big = fake_tensor(L=128 * 16385)
+    name, why = call(q, big, big, wsb=1 << 50)
+    assert name == "BASA_ERR_UNSUPPORTED" and "key blocks per head exceed" in why
     for bad in (-1, 4):
         assert call(q, k, v, wsb=1 << 40, p_=bd.params(128, attn_shape=bad))[0] == "BASA_ERR_INVALID_ARG"
     # output strides: token-major is fine (and reaches the workspace check), the rest is refused
