@@ -165,7 +165,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // its largest m' that sum to at least mass_target, at least min_keep and at most kappa; the
 // count is found first (a second bisection, on "mass of the logits >= T"), then the same
 // top-count machinery runs with the row's own count.
-template <int MAXI>
+template <int MAXI, bool kLive>
 __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ scores,
                                                          int rows_total, int Nk, int kappa,
                                                          float mass_target, int min_keep,
@@ -180,8 +180,8 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   const float* src = scores + (int64_t)row * Nk;
   // causal variant: a key block is live for this row iff its smallest original key index does not
   // exceed the row's largest original query index (+ offset); dead blocks take no part below
-  const int32_t* kmin = live.q_max ? live.k_min + (int64_t)(row / live.Nq / live.group) * Nk : nullptr;
-  const int q_lim = live.q_max ? live.q_max[row] + live.offset : 0;
+  const int32_t* kmin = kLive ? live.k_min + (int64_t)(row / live.Nq / live.group) * Nk : nullptr;
+  const int q_lim = kLive ? live.q_max[row] + live.offset : 0;
   float e[MAXI];                        // logits first, then exp(l - max)
   uint32_t u[MAXI];
   float mx = -INFINITY;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) e[i] = src[min(i * 64 + lane, Nk - 1)];
   int n_live = Nk;
-  if (kmin) {
+  if constexpr (kLive) {
     int km[MAXI];
 #pragma unroll
     for (int i = 0; i < MAXI; ++i) km[i] = kmin[min(i * 64 + lane, Nk - 1)];
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   }
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
-    const bool in_row = i * 64 + lane < Nk && !(kmin && e[i] != e[i]);
+    const bool in_row = i * 64 + lane < Nk && !(kLive && e[i] != e[i]);
     e[i] = in_row ? e[i] + 0.0f : -INFINITY;        // -0 -> +0 so that equal values have equal images
     u[i] = in_row ? ordered_bits(e[i]) : 0u;        // 0 is below the image of every float
     mx = fmaxf(mx, e[i]);
@@ -223,13 +223,14 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   float sum_all = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
-    e[i] = (u[i] != 0u) ? expf(e[i] - mx) : 0.f;         // image 0: past the row, or a dead block
+    // (image 0: past the row, or a dead block)
+    e[i] = (kLive ? u[i] != 0u : i * 64 + lane < Nk) ? expf(e[i] - mx) : 0.f;
     sum_all += e[i];
   }
   sum_all = wave_sum(sum_all);
 
   int keep = keep_in ? max(1, min(keep_in[row], kappa)) : kappa;
-  keep = min(keep, n_live);
+  if (kLive) keep = min(keep, n_live);
   if (!keep_in && mass_target > 0.f) {
     const float need = mass_target * sum_all;
     // T2 = largest image T such that the logits with image >= T carry at least the target
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
     for (int off = 32; off > 0; off >>= 1) e_eq = fmaxf(e_eq, __shfl_xor(e_eq, off));
     int r = n_eq;
     if (e_eq > 0.f) r = min(n_eq, max(1, (int)ceilf((need - m_gt) / e_eq)));
-    keep = min(min(kappa, n_live), max(max(1, min_keep), n_gt + r));
+    keep = min(kLive ? min(kappa, n_live) : kappa, max(max(1, min_keep), n_gt + r));
   }
 
   // T = keep-th largest image
@@ -421,9 +422,15 @@ basa_status launch_row_select(const float* scores, int rows_total, int Nk, int k
   if (rows_total == 0) return BASA_OK;
   dim3 grid(ceil_div(rows_total, 4));
   ProfScope prof(K_ROW_SELECT, st);
-#define BASA_SEL(M)                                                                            \
-  hipLaunchKernelGGL((row_select_kernel<M>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
-                     kappa, mass_target, min_keep, keep_in, live, mask_bits, row_count, row_cols, row_mass)
+#define BASA_SEL(M)                                                                                      \
+  do {                                                                                                   \
+    if (live.q_max)                                                                                      \
+      hipLaunchKernelGGL((row_select_kernel<M, true>), grid, dim3(256), 0, st, scores, rows_total, Nk,   \
+                         kappa, mass_target, min_keep, keep_in, live, mask_bits, row_count, row_cols, row_mass); \
+    else                                                                                                 \
+      hipLaunchKernelGGL((row_select_kernel<M, false>), grid, dim3(256), 0, st, scores, rows_total, Nk,  \
+                         kappa, mass_target, min_keep, keep_in, live, mask_bits, row_count, row_cols, row_mass); \
+  } while (0)
   if (Nk <= 256) BASA_SEL(4);
   else if (Nk <= 1024) BASA_SEL(16);
   else if (Nk <= 2048) BASA_SEL(32);
