@@ -118,3 +118,40 @@ def test_causal_end_to_end_at_zero_sparsity_equals_dense_causal_for_sorted_and_u
     cnt = sel.row_count[0, 0].cpu().numpy()
     n = sel.n_k
     assert list(cnt[:4]) == [1, 2, 3, 4] and (cnt == np.minimum(np.arange(1, n + 1), sel.kappa)).all()
+
+
+@pytest.mark.parametrize("Lq,Lk", [(300, 1000), (1000, 300)])
+@pytest.mark.parametrize("dtype,d,block", [(torch.bfloat16, 128, 64), (torch.float32, 64, 64)])
+def test_causal_cross_lengths_through_selection(Lq, Lk, dtype, d, block):
+    """Ends aligned: with L_q < L_k every query sees a long prefix; with L_q > L_k the first query blocks
+    precede every key (no live block: count 0, zero rows)."""
+    g = torch.Generator().manual_seed(5 + Lq)
+    mk = lambda L: (torch.randn((1, 2, L, d), generator=g) * 1.1).to(dtype).to(DEV)
+    Q, K, V = mk(Lq), mk(Lk), mk(Lk)
+    for sort, mass in ((bd.SORT_NONE, 0.0), (bd.SORT_QK, 0.0), (bd.SORT_QK, 0.6)):
+        sel = bd.basa_select(Q, K, block, 0.5, sort=sort, causal=True, mass_target=mass, min_keep=2)
+        out, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k,
+                                       want_lse=True, causal=True)
+        torch.cuda.synchronize()
+        bf16 = dtype == torch.bfloat16
+        for h in range(2):
+            q, k, v = np64(Q[0, h]), np64(K[0, h]), np64(V[0, h])
+            ref = o.select_causal(q, k, block, 0.5, sort=sort)
+            cnt = sel.row_count[0, h].cpu().numpy()
+            cols = sel.row_cols[0, h].cpu().numpy().astype(np.int64)
+            lists = [cols[r, :cnt[r]] for r in range(cols.shape[0])]
+            n_live = ref["live"].sum(axis=1)
+            if mass == 0.0:
+                assert np.array_equal(cnt, ref["count"])
+            else:                                # a mass budget keeps at most the fixed budget's count, at least min_keep
+                assert (cnt <= ref["count"]).all() and (cnt >= np.minimum(2, n_live)).all()
+            for r, c in enumerate(lists):
+                assert ref["live"][r, c].all(), "a dead block was kept"
+            if sort == bd.SORT_NONE and Lq > Lk:
+                assert (cnt[:(Lq - Lk) // block] == 0).all()
+            # attention over the GPU's own lists against the oracle on the same lists
+            O_ref, lse_ref = o.sparse_attention_causal(q, k, v, ref["perm_q"], ref["perm_k"], lists, block, return_lse=True)
+            check_output(np64(out[0, h]), O_ref, bf16, f"cross {Lq}x{Lk} sort {sort} mass {mass} head {h}")
+            blind = np.isinf(lse_ref)
+            assert np.array_equal(np.isinf(lse[0, h].cpu().numpy()), blind)
+            assert np.abs(np64(out[0, h])[blind]).max(initial=0.0) == 0.0
