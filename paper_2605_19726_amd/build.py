@@ -18,6 +18,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
+    "-save-temps=obj",        # keeps the device assembly next to the objects (read by lds_wait_audit)
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

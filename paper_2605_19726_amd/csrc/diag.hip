@@ -257,16 +257,21 @@ __global__ __launch_bounds__(256, 2) void block_mass_kernel(MassArgs a) {
   };
   issue_tile(0, 0);
   for (int t = 0; t + 1 < T; ++t) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // lgkmcnt too: the wave's own store of its block total (end of the tile before) has to be in LDS
+    // before the barrier lets another wave read it.  The fence inside __syncthreads() is supposed to
+    // see to that, but in this loop the compiler's wait-count pass was found to drop the LDS part
+    // (rare stale totals, different from run to run), so the wait is spelt out.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
     if (t > 0 && (t % TPB) == 0) combine(t / TPB - 1);      // the key block that ended with tile t-1
     issue_tile(t + 1, (t + 1) & 1);
     mass_tile(std::false_type{}, t);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   __syncthreads();
   if (T > 1 && ((T - 1) % TPB) == 0) combine((T - 1) / TPB - 1);
   mass_tile(std::true_type{}, T - 1);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __syncthreads();
   combine((T - 1) / TPB);
 }

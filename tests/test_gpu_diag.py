@@ -118,3 +118,22 @@ def test_block_mass_without_deviation_output_and_its_limit():
     with pytest.raises(bd.BasaError) as e:
         bd.basa_block_mass(q, k, 64, base_logits=base, want_dev=True)
     assert e.value.status_name == "BASA_ERR_UNSUPPORTED"
+
+
+@pytest.mark.parametrize("block", [128, 64])
+def test_block_mass_is_the_same_bits_on_every_run_at_a_size_with_many_key_tiles(block):
+    """Eq. 3 at 64K tokens, two heads, three runs: identical bits, and rows that sum to one.  (The block
+    totals travel through LDS between the waves of a workgroup once per key block; a wait missing
+    there showed as a few stale totals per ten thousand entries, different from run to run, and only
+    at sizes like this one.)"""
+    w = synth.CONFIGS[4].scaled("det", heads_q=2, heads_kv=2, L=65536, block=block)
+    Q, K, _ = synth.make_qkv(w, device=DEV)
+    perm_q, perm_k = bd.basa_norm_sort(Q, block), bd.basa_norm_sort(K, block)
+    runs = []
+    for _ in range(3):
+        m_hat, _, lse = bd.basa_block_mass(Q, K, block, perm_q, perm_k, want_lse=True)
+        torch.cuda.synchronize()
+        runs.append((m_hat, lse))
+    for m_hat, lse in runs[1:]:
+        assert torch.equal(m_hat, runs[0][0]) and torch.equal(lse, runs[0][1])
+    np.testing.assert_allclose(runs[0][0].sum(-1).cpu().numpy(), 1.0, atol=5e-5)
