@@ -104,6 +104,15 @@ typedef struct {
                                 by token, and a query none of whose visible keys lie in the listed
                                 blocks gets a zero output row and lse = -inf.  The `scores` output
                                 of basa_select stays unmasked                                   */
+  int32_t select_path;       /* basa_select: how the score map of Eq. 2 / Eq. 14 reaches the row
+                                selection of Alg. 1 steps 9-11.  0 = chosen by the library: in one
+                                kernel that keeps the map on chip whenever nobody needs it in
+                                memory (fixed count per row, no `scores` output, no total budget,
+                                not causal, at most 1024 key blocks per row), else through the map
+                                in the workspace; 1 = always through the workspace; 2 = the
+                                on-chip kernel or BASA_ERR_UNSUPPORTED.  Logits, kept sets and
+                                lists are the same either way; row_mass may differ in its last
+                                bits (another order of summation)                               */
 } basa_params;
 #define BASA_MAX_SEGMENTS 63
 

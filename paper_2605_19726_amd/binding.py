@@ -43,7 +43,8 @@ class BasaParams(C.Structure):
                 ("beta", C.c_float), ("sparsity", C.c_double), ("mass_target", C.c_double),
                 ("min_keep", C.c_int32), ("attn_shape", C.c_int32),
                 ("n_segments", C.c_int32), ("budget_total", C.c_int32),
-                ("segment_starts", C.POINTER(C.c_int32)), ("causal", C.c_int32)]
+                ("segment_starts", C.POINTER(C.c_int32)), ("causal", C.c_int32),
+                ("select_path", C.c_int32)]
 
 
 class BasaError(RuntimeError):
@@ -150,11 +151,11 @@ def tensor_desc(x: torch.Tensor) -> BasaTensor:
 
 def params(block: int, sparsity: float = 0.0, beta: float = 1.0, sort: int = SORT_QK,
            window: int = 0, mass_target: float = 0.0, min_keep: int = 0, attn_shape: int = 0,
-           segments=None, budget_total: int = 0, causal: bool = False) -> BasaParams:
+           segments=None, budget_total: int = 0, causal: bool = False, select_path: int = 0) -> BasaParams:
     """segments: host sequence of segment start tokens ([0, s1, s2, ...]) for a segment-aware sort."""
     p = BasaParams(int(block), int(sort), int(window), float(beta), float(sparsity),
                    float(mass_target), int(min_keep), int(attn_shape), 0, int(budget_total), None,
-                   1 if causal else 0)
+                   1 if causal else 0, int(select_path))
     if segments is not None:
         arr = (C.c_int32 * len(segments))(*[int(v) for v in segments])
         p.n_segments = len(segments)
@@ -253,11 +254,11 @@ def basa_select(q: torch.Tensor, k: torch.Tensor, block: int, sparsity: float, b
                 sort: int = SORT_QK, window: int = 0, want_mask: bool = True,
                 want_mass: bool = True, want_scores: bool = False, ws=None, out: Selection = None,
                 mass_target: float = 0.0, min_keep: int = 0, segments=None, budget_total: int = 0,
-                causal: bool = False):
+                causal: bool = False, select_path: int = 0):
     lib = load()
     qd, kd = tensor_desc(q), tensor_desc(k)
     p = params(block, sparsity, beta, sort, window, mass_target, min_keep, segments=segments,
-               budget_total=budget_total, causal=causal)
+               budget_total=budget_total, causal=causal, select_path=select_path)
     b, hq, Lq, _ = q.shape
     hk, Lk = k.shape[1], k.shape[2]
     n_q, n_k = n_blocks(Lq, block), n_blocks(Lk, block)

@@ -34,7 +34,7 @@ std::vector<ProfRec> g_prof_recs;
 const char* const kKernelNames[K_COUNT] = {
     "norm_tile_sort_kernel", "merge_pass_kernel", "block_stats_kernel",
     "block_scores_kernel", "row_select_kernel", "gather_kernels", "attn_mfma_kernel",
-    "attn_simple_kernel", "block_mass_kernel", "diagnostic_small_kernels"};
+    "attn_simple_kernel", "block_mass_kernel", "diagnostic_small_kernels", "scores_select_kernel"};
 }  // namespace
 
 ProfScope::ProfScope(int id, hipStream_t st) : slot_(-1), st_(st) {
@@ -132,6 +132,7 @@ basa_status check_params(const basa_params* p, bool need_sparsity) {
     set_error("min_keep %d is negative", p->min_keep); return BASA_ERR_INVALID_ARG;
   }
   if (p->causal != 0 && p->causal != 1) { set_error("causal must be 0 or 1"); return BASA_ERR_INVALID_ARG; }
+  if (p->select_path < 0 || p->select_path > 2) { set_error("select_path must be 0, 1 or 2"); return BASA_ERR_INVALID_ARG; }
   return BASA_OK;
 }
 
@@ -341,6 +342,17 @@ basa_status basa_select(const basa_tensor* q, const basa_tensor* k, const basa_p
     if ((s = launch_block_stats(kv, pk, B, nullptr, nullptr, featk, 0, p->beta, nullptr, st)) != BASA_OK) return s;
   }
   const int kdim = (p->beta == 0.f) ? q->d : 3 * q->d;
+  // fixed count per row, nobody asks for the map, no second pass over it: the map stays on chip
+  const bool fusable = !scores && !p->causal && p->mass_target == 0.0 && p->budget_total == 0 &&
+                       scores_select_supported(Nk, kdim, 3 * q->d);
+  if (p->select_path == 2 && !fusable) {
+    set_error("select_path = 2 needs a fixed count per row, no scores output, no causal mask, no total budget "
+              "and at most 1024 key blocks per row");
+    return BASA_ERR_UNSUPPORTED;
+  }
+  if (fusable && p->select_path != 1)
+    return launch_scores_select(featq, featk, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, kappa, mask_bits,
+                                row_count, row_cols, row_mass, st);
   if ((s = launch_block_scores(featq, featk, sc, BHq, q->heads / k->heads, Nq, Nk, kdim, 3 * q->d, st)) != BASA_OK) return s;
   LiveBlocks live{nullptr, nullptr, Nq, q->heads / k->heads, k->L - q->L};
   if (p->causal) {

@@ -42,7 +42,7 @@ basa_status hip_fail(hipError_t e, const char* what);
 // with a pair of HIP events on the launch stream when profiling is enabled.
 enum KernelId {
   K_NORM_TILE_SORT = 0, K_MERGE, K_STATS, K_SCORES, K_ROW_SELECT, K_GATHER, K_ATTN,
-  K_ATTN_SIMPLE, K_BLOCK_MASS, K_DIAG_SMALL, K_COUNT
+  K_ATTN_SIMPLE, K_BLOCK_MASS, K_DIAG_SMALL, K_SCORES_SELECT, K_COUNT
 };
 struct ProfScope {
   ProfScope(int id, hipStream_t st);
@@ -93,6 +93,14 @@ inline size_t feat_bytes_per_block(int d) { return (size_t)3 * 3 * d * 2; }
 basa_status launch_block_scores(const void* featQ, const void* featK, float* scores, int BHq,
                                 int group, int Nq, int Nk, int kdim_used, int feat_stride,
                                 hipStream_t st);
+
+// Score map and fixed-count selection in one launch, the map kept on chip (at most 1024 key blocks
+// per row, whole k-steps of 16): same logits, same kept sets and lists as launch_block_scores followed by
+// launch_row_select with mass_target = 0.  scores_select_supported says whether a shape qualifies.
+bool scores_select_supported(int Nk, int kdim_used, int feat_stride);
+basa_status launch_scores_select(const void* featQ, const void* featK, int BHq, int group, int Nq, int Nk,
+                                 int kdim_used, int feat_stride, int kappa, uint32_t* mask_bits,
+                                 int32_t* row_count, int32_t* row_cols, float* row_mass, hipStream_t st);
 
 // Row softmax mass + top-kappa selection from a score map; mass_target > 0 switches to the
 // cumulative-mass count per row (floor min_keep, cap kappa).  row_cols rows are kappa apart.

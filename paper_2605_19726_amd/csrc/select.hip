@@ -121,9 +121,9 @@ __global__ __launch_bounds__(256, 2) void block_scores_kernel(const uint4* __res
         b[part][t] = __builtin_bit_cast(bf16x8, v);
       }
     }
-    // the smallest products first
-    constexpr int PQ[6] = {2, 1, 0, 1, 0, 0};
-    constexpr int PK[6] = {0, 1, 2, 0, 1, 0};
+    // by key part, the smallest first (the order in which the fused kernel below receives them)
+    constexpr int PQ[6] = {0, 1, 0, 2, 1, 0};
+    constexpr int PK[6] = {2, 1, 1, 0, 0, 0};
 #pragma unroll
     for (int pr = 0; pr < 6; ++pr) {
 #pragma unroll
@@ -159,6 +159,10 @@ __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   return v;
+}
+
+__device__ __forceinline__ float float_of_ordered(uint32_t u) {
+  return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
 }
 
 // mass_target == 0: every row keeps `kappa` blocks.  mass_target > 0: a row keeps the fewest of
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
     // (image 0: past the row, or a dead block)
-    e[i] = (kLive ? u[i] != 0u : i * 64 + lane < Nk) ? expf(e[i] - mx) : 0.f;
+    e[i] = (kLive ? u[i] != 0u : i * 64 + lane < Nk) ? __expf(e[i] - mx) : 0.f;
     sum_all += e[i];
   }
   sum_all = wave_sum(sum_all);
@@ -309,6 +313,284 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------------------------
+// Score map and fixed-count row selection in ONE kernel: the map never leaves the chip
+// (Alg. 1 steps 5-11 with the logits kept where they are produced).
+//
+// A workgroup of eight waves owns 64 rows of a head's map and ALL its columns (at most 128 NT):
+// wave (rh, cq) holds rows 32 rh .. +31 against columns 32 NT cq .. +32 NT - 1 as NT transposed
+// 32x32 accumulators (A = key features, B = query features), so lane (j, h) owns row j: register r
+// of accumulator t is column 32 t + 8 (r / 4) + 4 h + r % 4 of the wave's range, and the lane and
+// its partner (h ^ 1) together hold the wave's whole share of that row.  The same six part
+// products as block_scores_kernel are accumulated in the same order, so the logits are the same
+// bits.  Features stream through a ring of four LDS buffers in units of one k-step of ONE key
+// part (all columns, both k-halves) plus the matching query part; a unit is requested three
+// units before its use, and the unit of key part kp is multiplied with the query parts 0 .. 2-kp,
+// which are in registers by then.
+//
+// Selection works on the accumulators in place (as order-preserving integer images): the
+// bisection of row_select_kernel with per-lane counts, summed over the 8 lanes of a row through
+// LDS, one barrier per step.  The kept set goes through per-row bitmaps in LDS (one word per
+// accumulator: no atomics), from which one wave per row writes the bitmap, the ascending column
+// list and the kept mass.
+// ---------------------------------------------------------------------------------
+constexpr int kFR = 64;                    // rows of the map per workgroup
+template <int NT>
+struct FusedGeo {
+  static constexpr int kCols = 128 * NT;               // columns covered: 4 column waves x NT blocks of 32
+  static constexpr int kUnit = 2 * kCols + 2 * kFR;    // 16-byte groups per unit: K [k-half][column], Q [k-half][row]
+  static constexpr int kLoads = 2 * kCols / 64 / 8;    // direct-to-LDS loads of K groups per wave and unit
+  static constexpr int kWords = 4 * NT;                // bitmap words per row
+  static constexpr int kWStride = kWords + 1;          // padded: the lanes of a wave write one word of 32 rows at once
+  static constexpr int kRingBytes = 4 * kUnit * 16;
+  // after the map is complete the ring is reused: counters, partial sums, bitmaps, one list per wave
+  static constexpr int kPostBytes = (3 * 64 + 4 + 64 * 4 + 2 * 4 * 64 + 2 * 64 * kWStride + 8 * kCols) * 4;
+  static_assert(kPostBytes <= kRingBytes, "the selection scratch must fit into the ring");
+};
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(v, off);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+template <int NT>
+__global__ __launch_bounds__(512, 1) void scores_select_kernel(const uint4* __restrict__ featQ,
+                                                               const uint4* __restrict__ featK, int group,
+                                                               int Nq, int Nk, int K, int S, int kappa,
+                                                               uint32_t* __restrict__ mask_bits,
+                                                               int32_t* __restrict__ row_count,
+                                                               int32_t* __restrict__ row_cols,
+                                                               float* __restrict__ row_mass) {
+  using G = FusedGeo<NT>;
+  extern __shared__ __attribute__((aligned(16))) uint4 fbuf[];
+  const int strips = (Nq + kFR - 1) / kFR, total = gridDim.x;
+  int logical = blockIdx.x;
+  if ((total & 7) == 0) logical = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);   // one XCD, one range of heads
+  const int bhq = logical / strips, strip = logical - bhq * strips;
+  const int bhk = bhq / group;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 31, h = lane >> 5;
+  const int rh = wave >> 2, cq = wave & 3;
+  const int row_local = rh * 32 + li;
+  const int n_steps = K >> 4, groups = S >> 3, units = 3 * n_steps;
+  const uint4* fq = featQ + (int64_t)bhq * 3 * groups * Nq;
+  const uint4* fk = featK + (int64_t)bhk * 3 * groups * Nk;
+
+  // unit v = (k-step v / 3, key part 2 - v % 3, query part v % 3) into ring buffer v % 4; rows and
+  // columns past the end of the map read the last one (their results are never used).  Every
+  // wave issues kLoads + 1 loads per unit (the 2 x 64 query groups are requested by four waves
+  // each, same bytes to the same place), so that one wait count fits all.
+  auto issue_unit = [&](int v, int buf) {
+    const int s = v / 3, j = v - 3 * s, kp = 2 - j;
+    uint4* dst = fbuf + buf * G::kUnit;
+#pragma unroll
+    for (int i = 0; i < G::kLoads; ++i) {
+      const int c = i * 8 + wave;                            // wave-uniform chunk of 64 columns
+      const int kh = c / (G::kCols / 64), sub = c - kh * (G::kCols / 64);
+      const uint4* src = fk + ((int64_t)kp * groups + 2 * s + kh) * Nk + min(sub * 64 + lane, Nk - 1);
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + kh * G::kCols + sub * 64), 16, 0, 0);
+    }
+    const int kh = wave & 1;
+    const uint4* src = fq + ((int64_t)j * groups + 2 * s + kh) * Nq + min(strip * kFR + lane, Nq - 1);
+    __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + 2 * G::kCols + kh * kFR), 16, 0, 0);
+  };
+
+  floatx16 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) acc[t] = floatx16{0};
+  issue_unit(0, 0);
+  issue_unit(1, 1);
+  issue_unit(2, 2);
+#pragma nounroll
+  for (int s = 0; s < n_steps; ++s) {
+    bf16x8 qreg[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int v = 3 * s + j;
+      // all but my two youngest batches have landed: unit v is among them.  After the barrier
+      // everyone's part of it has, and everyone is done with unit v - 1, whose buffer the next
+      // request overwrites (past the last unit: the last one again, into that same dead buffer,
+      // so that the count of outstanding loads stays what the wait assumes).
+      if (G::kLoads == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      else if (G::kLoads == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+      __syncthreads();
+      issue_unit(min(v + 3, units - 1), (v + 3) & 3);
+      const uint4* U = fbuf + (v & 3) * G::kUnit;
+      qreg[j] = __builtin_bit_cast(bf16x8, U[2 * G::kCols + h * kFR + row_local]);
+      bf16x8 a[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) a[t] = __builtin_bit_cast(bf16x8, U[h * G::kCols + cq * 32 * NT + 32 * t + li]);
+      // (query parts outermost: neighbouring matrix instructions are independent; every accumulator
+      //  still receives its products in the order stated above)
+#pragma unroll
+      for (int qp = j; qp >= 0; --qp)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], qreg[qp], acc[t], 0, 0, 0);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the trailing requests still write into the ring
+  __syncthreads();
+
+  // ---------------- selection, on the accumulators in place
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(fbuf);            // [3][64] counts of one bisection step
+  uint32_t* nd = cnt + 3 * 64;                                  // [3] (+1): "a row is still searching"
+  uint32_t* mximg = nd + 4;                                     // [64] image of the row maximum
+  uint32_t* cgt = mximg + 64;                                   // [64] entries above the threshold
+  int32_t* needeq = reinterpret_cast<int32_t*>(cgt + 64);       // [64] ties to keep
+  float* e_thr = reinterpret_cast<float*>(needeq + 64);         // [64] exp(threshold - max)
+  float* part = e_thr + 64;                                     // [2][4][64] partial sums per column wave
+  uint32_t* gtw = reinterpret_cast<uint32_t*>(part + 2 * 4 * 64);   // [64][kWStride] bits above the threshold
+  uint32_t* eqw = gtw + 64 * G::kWStride;                       // [64][kWStride] bits equal to it
+  int32_t* stage = reinterpret_cast<int32_t*>(eqw + 64 * G::kWStride);   // [8][kCols] one column list per wave
+  if (tid < 3 * 64) cnt[tid] = 0u;
+  if (tid < 4) nd[tid] = 0u;
+  if (tid < 64) { mximg[tid] = 0u; cgt[tid] = 0u; }
+
+  uint32_t u[NT][16];
+  uint32_t mxl = 0u;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int col = cq * 32 * NT + 32 * t + 8 * (r >> 2) + 4 * h + (r & 3);
+      u[t][r] = col < Nk ? ordered_bits(acc[t][r] + 0.0f) : 0u;      // -0 -> +0; 0 is below the image of every float
+      mxl = max(mxl, u[t][r]);
+    }
+  __syncthreads();
+  const int keep = kappa;
+  float mx = 0.f;
+  if (row_mass) {
+    mxl = max(mxl, (uint32_t)__shfl_xor((int)mxl, 32));
+    if (h == 0) atomicMax(&mximg[row_local], mxl);
+    __syncthreads();
+    mx = float_of_ordered(mximg[row_local]);
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += __expf(u[t][r] != 0u ? float_of_ordered(u[t][r]) - mx : -INFINITY);
+    sum += __shfl_xor(sum, 32);
+    if (h == 0) part[cq * 64 + row_local] = sum;
+  }
+
+  // T = keep-th largest image of the row
+  uint32_t T = 0u;
+  bool done = false;
+  for (int k = 0; k < 32; ++k) {
+    const int b0 = k % 3;
+    const uint32_t cand = T | (0x80000000u >> k);
+    int c = 0;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) c += u[t][r] >= cand ? 1 : 0;
+    c += __shfl_xor(c, 32);
+    if (h == 0 && !done) atomicAdd(&cnt[b0 * 64 + row_local], (uint32_t)c);
+    __syncthreads();
+    if (k > 0 && nd[(k - 1) % 3] == 0u) break;          // no row was still searching after the step before
+    const int tot = (int)cnt[b0 * 64 + row_local];
+    if (!done) {
+      if (tot >= keep) T = cand;
+      // exactly `keep` images at or above cand: they are the kept set, whatever the lower bits are
+      if (tot == keep) done = true;
+    }
+    if (!done) nd[b0] = 1u;
+    if (tid < 64) cnt[((k + 2) % 3) * 64 + tid] = 0u;
+    if (tid == 0) nd[(k + 1) % 3] = 0u;
+  }
+  {
+    int c = 0;
+    float sg = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) c += u[t][r] > T ? 1 : 0;
+    if (row_mass) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sg += __expf(u[t][r] > T ? float_of_ordered(u[t][r]) - mx : -INFINITY);
+    }
+    c += __shfl_xor(c, 32);
+    sg += __shfl_xor(sg, 32);
+    if (h == 0) {
+      atomicAdd(&cgt[row_local], (uint32_t)c);
+      if (row_mass) part[(4 + cq) * 64 + row_local] = sg;
+    }
+  }
+  // one bitmap word per accumulator: the lane's 16 columns and its partner's interleave in fours
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    uint32_t g = 0u, e = 0u;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const uint32_t bit = 1u << (8 * (r >> 2) + (r & 3));
+      g |= u[t][r] > T ? bit : 0u;
+      e |= u[t][r] == T ? bit : 0u;
+    }
+    g <<= 4 * h; e <<= 4 * h;
+    g |= (uint32_t)__shfl_xor((int)g, 32);
+    e |= (uint32_t)__shfl_xor((int)e, 32);
+    if (h == 0) gtw[row_local * G::kWStride + cq * NT + t] = g;
+    else eqw[row_local * G::kWStride + cq * NT + t] = e;
+  }
+  __syncthreads();
+  if (cq == 0 && h == 0) {
+    needeq[row_local] = keep - (int)cgt[row_local];
+    e_thr[row_local] = row_mass ? __expf(float_of_ordered(T) - mx) : 0.f;
+  }
+  __syncthreads();
+
+  // ---------------- one wave per row: bitmap, ascending column list, count, mass
+  const int words = (Nk + 31) >> 5;
+  const int wd = lane >> 1, half = lane & 1;
+  int32_t* stg = stage + wave * G::kCols;
+  for (int i = 0; i < 8; ++i) {
+    const int rl = wave * 8 + i;
+    const int64_t grow = (int64_t)bhq * Nq + strip * kFR + rl;
+    if (strip * kFR + rl >= Nq) break;                  // wave-uniform: the rows of a wave ascend
+    const uint32_t g = wd < G::kWords ? gtw[rl * G::kWStride + wd] : 0u;
+    const uint32_t e = wd < G::kWords ? eqw[rl * G::kWStride + wd] : 0u;
+    const int ne = needeq[rl];
+    // of the entries equal to the threshold the lowest columns are kept
+    const int pe = __popc(e);
+    const int eq_before = wave_incl_scan(half == 0 ? pe : 0, lane) - pe;     // both lanes of a word: words below it
+    const int take = min(max(ne - eq_before, 0), pe);
+    uint32_t ek = e;
+    while (__popc(ek) > take) ek &= ~(0x80000000u >> __clz(ek));
+    const uint32_t f = g | ek;
+    if (mask_bits && half == 0 && wd < words) mask_bits[grow * words + wd] = f;
+    const int pf = __popc(f);
+    const int incl = wave_incl_scan(half == 0 ? pf : 0, lane);
+    const int n_kept = __builtin_amdgcn_readlane(incl, 63);
+    int start = incl - pf + (half ? __popc(f & 0xffffu) : 0);
+    uint32_t my = (f >> (16 * half)) & 0xffffu;
+    while (my) {
+      stg[start++] = wd * 32 + 16 * half + (__ffs(my) - 1);
+      my &= my - 1u;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own LDS writes, before its reads
+    if (row_cols)
+      for (int k = lane; k < n_kept; k += 64) row_cols[grow * kappa + k] = stg[k];
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and the reads before the next row's writes
+    if (lane == 0) {
+      if (row_count) row_count[grow] = n_kept;
+      if (row_mass) {
+        const float sa = (part[0 * 64 + rl] + part[1 * 64 + rl]) + (part[2 * 64 + rl] + part[3 * 64 + rl]);
+        const float sg = (part[4 * 64 + rl] + part[5 * 64 + rl]) + (part[6 * 64 + rl] + part[7 * 64 + rl]);
+        row_mass[grow] = (sg + (ne > 0 ? (float)ne * e_thr[rl] : 0.f)) / sa;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // Total budget of kept blocks per (batch, head): one workgroup per head builds the histogram of
 // the rows' counts and walks the caps t = lo .. kappa: total(t) = sum_{c <= t} c*hist[c] +
 // t * #{rows with c > t} never decreases with t, so the last t that fits is the answer.
@@ -373,6 +655,40 @@ basa_status launch_block_scores(const void* featQ, const void* featK, float* sco
   hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), kScoresLdsBytes, st, reinterpret_cast<const uint4*>(featQ),
                      reinterpret_cast<const uint4*>(featK), scores, group, Nq, Nk, kdim_used, feat_stride);
   BASA_HIP_CHECK_LAUNCH("block_scores_kernel");
+  return BASA_OK;
+}
+
+bool scores_select_supported(int Nk, int kdim_used, int feat_stride) {
+  return Nk >= 1 && Nk <= 1024 && kdim_used >= 16 && kdim_used % 16 == 0 && feat_stride % 8 == 0;
+}
+
+basa_status launch_scores_select(const void* featQ, const void* featK, int BHq, int group, int Nq, int Nk,
+                                 int kdim_used, int feat_stride, int kappa, uint32_t* mask_bits,
+                                 int32_t* row_count, int32_t* row_cols, float* row_mass, hipStream_t st) {
+  if (BHq == 0 || Nq == 0 || Nk == 0) return BASA_OK;
+  if (!scores_select_supported(Nk, kdim_used, feat_stride)) {
+    set_error("fused score map and selection: %d key blocks per row (at most 1024), contraction length %d "
+              "(a multiple of 16)", Nk, kdim_used);
+    return BASA_ERR_UNSUPPORTED;
+  }
+  dim3 grid(ceil_div(Nq, kFR) * BHq);
+  ProfScope prof(K_SCORES_SELECT, st);
+#define BASA_FUSED(NT)                                                                                    \
+  do {                                                                                                    \
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scores_select_kernel<NT>),    \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,                  \
+                                             FusedGeo<NT>::kRingBytes);                                   \
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");                          \
+    hipLaunchKernelGGL((scores_select_kernel<NT>), grid, dim3(512), FusedGeo<NT>::kRingBytes, st,         \
+                       reinterpret_cast<const uint4*>(featQ), reinterpret_cast<const uint4*>(featK),      \
+                       group, Nq, Nk, kdim_used, feat_stride, kappa, mask_bits, row_count, row_cols,      \
+                       row_mass);                                                                         \
+  } while (0)
+  if (Nk <= 256) BASA_FUSED(2);
+  else if (Nk <= 512) BASA_FUSED(4);
+  else BASA_FUSED(8);
+#undef BASA_FUSED
+  BASA_HIP_CHECK_LAUNCH("scores_select_kernel");
   return BASA_OK;
 }
 

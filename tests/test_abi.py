@@ -84,6 +84,8 @@ def test_select_argument_validation(lib):
     bad = bd.params(128, 0.5)
     bad.causal = 2
     assert call(q, k, bad)[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, select_path=3))[0] == "BASA_ERR_INVALID_ARG"
+    assert call(q, k, bd.params(128, 0.5, select_path=-1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, mass_target=0.9, min_keep=-1))[0] == "BASA_ERR_INVALID_ARG"
     assert call(q, k, bd.params(128, 0.5, budget_total=-1))[0] == "BASA_ERR_INVALID_ARG"
     seg = lambda starts, **kw: bd.params(128, 0.5, segments=starts, **kw)

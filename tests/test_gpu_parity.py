@@ -173,8 +173,9 @@ def test_downsample_matches_oracle(w):
 
 
 # ------------------------------------------------------------------ selection
-def _check_selection(w, Q, K, s, beta, sort, window=0):
-    sel = bd.basa_select(Q, K, w.block, s, beta, sort, window, want_scores=True)
+def _check_selection(w, Q, K, s, beta, sort, window=0, select_path=1):
+    # select_path 2: the kernel that keeps the score map on chip (it has no `scores` output)
+    sel = bd.basa_select(Q, K, w.block, s, beta, sort, window, want_scores=select_path != 2, select_path=select_path)
     torch.cuda.synchronize()
     n_k = sel.n_k
     gpu_mask = unpack_mask(sel.mask_bits, n_k)
@@ -185,10 +186,11 @@ def _check_selection(w, Q, K, s, beta, sort, window=0):
         assert sel.kappa == ref["kappa"]
         assert np.array_equal(sel.perm_q[0, h].cpu().numpy(), ref["perm_q"]), "perm_q"
         assert np.array_equal(sel.perm_k[0, hk].cpu().numpy(), ref["perm_k"]), "perm_k"
-        sc = sel.scores[0, h].cpu().numpy().astype(np.float64)
-        scale = max(1.0, np.abs(ref["logits"]).max())
-        assert np.abs(sc - ref["logits"]).max() <= 1e-5 * scale, \
-            f"logits off by {np.abs(sc - ref['logits']).max():.3e}"
+        if sel.scores is not None:
+            sc = sel.scores[0, h].cpu().numpy().astype(np.float64)
+            scale = max(1.0, np.abs(ref["logits"]).max())
+            assert np.abs(sc - ref["logits"]).max() <= 1e-5 * scale, \
+                f"logits off by {np.abs(sc - ref['logits']).max():.3e}"
         bad, dc = mask_report(gpu_mask[0, h], ref)
         total_dc += dc - ref["mask"].shape[0]          # every row's threshold block is in the band
         assert bad == 0, f"{bad} mask mismatches outside the don't-care band (head {h})"
@@ -208,6 +210,33 @@ def test_select_matches_oracle(w):
     Q, K, _ = gen(w)
     for s in w.sparsities:
         _check_selection(w, Q, K, s, 1.0, o.SORT_QK)
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_select_with_the_map_on_chip_matches_oracle_and_the_two_kernel_path(w):
+    """Eq. 2 / Eq. 14 and Alg. 1 steps 9-11 in one kernel: same parity bar against the oracle, and the
+    same bits (bitmap, counts, lists) as the path through the score map in memory."""
+    Q, K, _ = gen(w)
+    for s in w.sparsities:
+        for beta in (1.0, 0.0):
+            _check_selection(w, Q, K, s, beta, o.SORT_QK, select_path=2)
+            a = bd.basa_select(Q, K, w.block, s, beta, select_path=1)
+            b = bd.basa_select(Q, K, w.block, s, beta, select_path=2)
+            for name in ("mask_bits", "row_count", "row_cols", "perm_q", "perm_k"):
+                assert torch.equal(getattr(a, name), getattr(b, name)), name
+            assert (a.row_mass - b.row_mass).abs().max().item() <= 2e-6
+
+
+def test_select_path_that_cannot_keep_the_map_on_chip_is_refused():
+    w = SMALL[0]
+    Q, K, _ = gen(w)
+    for kw in (dict(want_scores=True), dict(mass_target=0.9), dict(budget_total=8), dict(causal=True)):
+        with pytest.raises(bd.BasaError) as e:
+            bd.basa_select(Q, K, w.block, 0.5, select_path=2, **kw)
+        assert e.value.status_name == "BASA_ERR_UNSUPPORTED"
+        # ... and the default takes the other path for them
+        bd.basa_select(Q, K, w.block, 0.5, **kw)
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("sort", [o.SORT_NONE, o.SORT_Q, o.SORT_K, o.SORT_QK])
