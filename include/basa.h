@@ -105,14 +105,15 @@ typedef struct {
                                 blocks gets a zero output row and lse = -inf.  The `scores` output
                                 of basa_select stays unmasked                                   */
   int32_t select_path;       /* basa_select: how the score map of Eq. 2 / Eq. 14 reaches the row
-                                selection of Alg. 1 steps 9-11.  0 = chosen by the library: in one
-                                kernel that keeps the map on chip whenever nobody needs it in
+                                selection of Alg. 1 steps 9-11.  1 = through the map in the workspace
+                                (one kernel writes it, one reads it).  2 = in one kernel that
+                                keeps the map on chip; possible when nobody needs the map in
                                 memory (fixed count per row, no `scores` output, no total budget,
-                                not causal, at most 1024 key blocks per row), else through the map
-                                in the workspace; 1 = always through the workspace; 2 = the
-                                on-chip kernel or BASA_ERR_UNSUPPORTED.  Logits, kept sets and
-                                lists are the same either way; row_mass may differ in its last
-                                bits (another order of summation)                               */
+                                not causal, at most 1024 key blocks per row), else
+                                BASA_ERR_UNSUPPORTED.  0 = the library's choice: the faster of the
+                                two where both apply, which on MI355X is 1.  Logits, kept sets
+                                and lists are the same either way; row_mass may differ in its
+                                last bits (another order of summation)                          */
 } basa_params;
 #define BASA_MAX_SEGMENTS 63
 
