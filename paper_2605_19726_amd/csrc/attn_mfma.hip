@@ -84,7 +84,11 @@ struct Geo {
 #endif
 constexpr int stages_of(int threads, int qpw) { return threads == 512 ? (qpw == 32 ? 4 : BASA_ATTN_ST64) : 2; }
 // k-steps of Q^T a wave of 64 queries keeps in registers (the rest is parked in LDS): all for D = 64
-constexpr int q_reg_steps(int d, int qpw) { return (qpw == 64 && d == 128) ? BASA_ATTN_QR : d / 16; }
+// (the causal variant of the 64-queries-per-wave kernel carries the two visibility limits and the
+//  key indices of the half-tile on top: one more k-step of Q^T is parked)
+constexpr int q_reg_steps(int d, int qpw, bool causal = false) {
+  return (qpw == 64 && d == 128) ? BASA_ATTN_QR - (causal ? 1 : 0) : d / 16;
+}
 
 // ---------------------------------------------------------------------------------
 // Gather kernels
@@ -179,13 +183,9 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 
 // One 64-key tile: S^T, softmax, O^T update, reading the LDS stage at `stage`.  kMasked:
 // keys at tile positions >= nvalid do not exist (ragged end of the sequence) and get -inf.
-// kCausal: kix holds the original index of each of the tile's 64 keys (INT_MAX where the sequence
-// has ended, which subsumes the ragged mask); a key is visible to this lane's query iff its index
-// does not exceed q_lim.
-template <bool kMasked, int D, bool kCausal = false>
+template <bool kMasked, int D>
 __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf)[Geo<D>::kKSteps], const char* stage,
-                                             int kaddr0, int vaddr0, float c, int nvalid, int h,
-                                             const int* kix = nullptr, int q_lim = 0) {
+                                             int kaddr0, int vaddr0, float c, int nvalid, int h) {
   const char* ks = stage;
   const char* vs = stage + Geo<D>::kTileBytes;
 
@@ -207,19 +207,6 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
       if (32 + kk >= nvalid) s1[r] = -INFINITY;
     }
   }
-  if constexpr (kCausal) {
-#pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      const int4 i0 = *reinterpret_cast<const int4*>(kix + 8 * g4 + 4 * h);
-      const int4 i1 = *reinterpret_cast<const int4*>(kix + 32 + 8 * g4 + 4 * h);
-      const int a0[4] = {i0.x, i0.y, i0.z, i0.w}, a1[4] = {i1.x, i1.y, i1.z, i1.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (a0[e] > q_lim) s0[4 * g4 + e] = -INFINITY;
-        if (a1[e] > q_lim) s1[4 * g4 + e] = -INFINITY;
-      }
-    }
-  }
   // ---- online softmax in the log2 domain, lazy running max
   float mx = max3(s0[0], s1[0], s0[1]);
 #pragma unroll
@@ -228,8 +215,7 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
   const float mc = mx * c;
   if (__builtin_amdgcn_ballot_w64(mc > st.m_run + kLazyTau) != 0) {
     const float m_new = fmaxf(st.m_run, mc);
-    // (causal: a lane whose query still sees nothing has -inf on both sides; its state stays as it is)
-    const float alpha = (kCausal && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);
     st.m_run = m_new;
     st.l_run *= alpha;
 #pragma unroll
@@ -237,8 +223,7 @@ __device__ __forceinline__ void process_tile(WaveState<D>& st, const bf16x8 (&qf
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[i][r] *= alpha;
   }
-  // (causal: a query that has seen no key yet subtracts 0, so that exp2 sees -inf, never inf - inf)
-  const float m_use = (kCausal && st.m_run == -INFINITY) ? 0.f : st.m_run;
+  const float m_use = st.m_run;
   bf16x8 pb[4];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -287,10 +272,13 @@ struct WaveState2 {
 // kQR of the k-steps take their Q^T fragments from registers; the others are read back from the
 // wave's lane-private LDS area at `qs` ([group 2][k-step][lane] 16 bytes): O (128 registers) and all
 // of Q (64) would leave the compiler too few of the 256 registers a wave has at two waves per SIMD.
-template <bool kMasked, int D, int kQR>
+// kCausal: kix4 points at the lane's four key indices of the tile's first group of eight keys
+// (original positions, INT_MAX past the end of the sequence, which also covers the ragged tile); a
+// key is visible to the query of group a / b iff its index does not exceed qla / qlb.
+template <bool kMasked, int D, int kQR, bool kCausal = false>
 __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&qa)[kQR], const bf16x8 (&qb)[kQR],
                                               const char* qs, const char* stage, int kaddr0, int vaddr0, float c,
-                                              int nvalid, int h) {
+                                              int nvalid, int h, const int* kix4 = nullptr, int qla = 0, int qlb = 0) {
   constexpr int kQL = Geo<D>::kKSteps - kQR;               // k-steps whose Q^T fragments live in LDS
   // One LDS address per operand and tile; the k-step (group) is folded in by an xor at the point of
   // use (ring stages start at multiples of 32 KB, so the xor of bits 5-8 commutes with adding the
@@ -319,11 +307,23 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
         sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, fb, sb, 0, 0, 0);
       }
     }
-    if (kMasked && nvalid < kTileKeys) {
+    if (!kCausal && kMasked && nvalid < kTileKeys) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int kk = 32 * half + 8 * (r >> 2) + 4 * h + (r & 3);
         if (kk >= nvalid) { sa[r] = -INFINITY; sb[r] = -INFINITY; }
+      }
+    }
+    if constexpr (kCausal) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int4 ix = *reinterpret_cast<const int4*>(kix4 + 32 * half + 8 * g4);
+        const int ia[4] = {ix.x, ix.y, ix.z, ix.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (ia[e] > qla) sa[4 * g4 + e] = -INFINITY;
+          if (ia[e] > qlb) sb[4 * g4 + e] = -INFINITY;
+        }
       }
     }
     float mxa = max3(sa[0], sa[1], sa[2]), mxb = max3(sb[0], sb[1], sb[2]);
@@ -335,7 +335,9 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
     const float mca = mxa * c, mcb = mxb * c;
     if (__builtin_amdgcn_ballot_w64(mca > st.m_run[0] + kLazyTau || mcb > st.m_run[1] + kLazyTau) != 0) {
       const float na = fmaxf(st.m_run[0], mca), nb = fmaxf(st.m_run[1], mcb);
-      const float aa = __builtin_amdgcn_exp2f(st.m_run[0] - na), ab = __builtin_amdgcn_exp2f(st.m_run[1] - nb);
+      // (causal: a query that still sees nothing has -inf on both sides; its state stays as it is)
+      const float aa = (kCausal && na == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run[0] - na);
+      const float ab = (kCausal && nb == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run[1] - nb);
       st.m_run[0] = na; st.m_run[1] = nb;
       st.l_run[0] *= aa; st.l_run[1] *= ab;
 #pragma unroll
@@ -343,7 +345,9 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
 #pragma unroll
         for (int r = 0; r < 16; ++r) { st.o[0][i][r] *= aa; st.o[1][i][r] *= ab; }
     }
-    const float ma = st.m_run[0], mb = st.m_run[1];
+    // (causal: a query that has seen no key yet subtracts 0, so that exp2 sees -inf, never inf - inf)
+    const float ma = (kCausal && st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];
+    const float mb = (kCausal && st.m_run[1] == -INFINITY) ? 0.f : st.m_run[1];
     bf16x8 pa[2], pb[2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -413,18 +417,17 @@ __device__ __forceinline__ int64_t out_off(const MfmaArgs& a, int bhq, int row) 
 // seq[i] = key block of the i-th entry of the union list | (bit 24+g set iff query block g of
 // this workgroup lists it).  While seq is being built the ring area holds the per-key-block
 // membership flags.
-// kCausal (128-query shape only): the ring is followed by the original key indices of each stage's
-// tile, every score is masked by original position, and a tile is skipped (no key visible to any
-// query of the wave) or takes the unmasked code (every key visible to every query) where its
-// index range allows.
+// kCausal (512-query shape only): the ring is followed by the original key indices of each stage's
+// tile (with their minimum), every score is masked by original position, and a wave skips a tile
+// none of whose keys is visible to any of its queries.
 template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false>
 __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 : 2) void attn_mfma_kernel(MfmaArgs a) {
   using G = Geo<D>;
-  static_assert(!kCausal || (kQPW == 32 && kWgQueries == kSoloQueries), "the causal path is built on the 128-query shape");
+  static_assert(!kCausal || (kQPW == 64 && kWgQueries == kWideQueries), "the causal path is built on the 512-query shape");
   constexpr int kWaves = kWgQueries / kQPW, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
   constexpr int kNG = kQPW / 32;             // 32-query groups per wave: 1 or 2
   constexpr int kStages = stages_of(kThreads, kQPW);
-  constexpr int kQR = q_reg_steps(D, kQPW), kQL = G::kKSteps - kQR;
+  constexpr int kQR = q_reg_steps(D, kQPW, kCausal), kQL = G::kKSteps - kQR;
   constexpr int kQParkBytes = kWaves * kNG * kQL * 1024;
   constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = kStages * kStageBytes;
   constexpr int kLoadsPerWave = 2 * G::kChunksPerTile / kWaves;
@@ -552,7 +555,9 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
   bf16x8 qf[kNG][kQR];
-  int q_lim = INT_MIN;          // kCausal: the largest original key index this lane's query may see
+  int q_lim[kNG];               // kCausal: the largest original key index the lane's query of each group may see
+#pragma unroll
+  for (int r = 0; r < kNG; ++r) q_lim[r] = INT_MIN;
   char* qpark = smem + kRingBytes + (wave * kNG * kQL) * 1024 + lane * 16;    // this lane's parked fragments
 #pragma unroll
   for (int r = 0; r < kNG; ++r) {
@@ -560,7 +565,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
     // (padding of the last block, or a query block that does not exist) read row 0 and are never stored
     const int qpos = pos0 + 32 * r;
     const int qrow = qpos < a.Lq ? perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq) : 0;
-    if (kCausal && qpos < a.Lq) q_lim = qrow + a.causal_off;
+    if (kCausal && qpos < a.Lq) q_lim[r] = qrow + a.causal_off;
     const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q.ptr) +
                                                      (a.q.head_offset(bhq) + (int64_t)qrow * a.q.stride_l) * 2);
 #pragma unroll
@@ -580,19 +585,34 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   init_state<D>(st);
   const float c = a.scale_log2e;
   // one 64-key tile of the ring, for the one or two query groups of this wave
-  auto tile = [&](auto masked, const char* stage, int nvalid) {
+  auto tile = [&](auto masked, int stage_no, int nvalid) {
+    const char* stage = smem + stage_no * kStageBytes;
     if constexpr (kNG == 1) process_tile<decltype(masked)::value, D>(st, qf[0], stage, kaddr, vaddr, c, nvalid, h);
     else {
-      // the lane half is needed by the masking code of the ragged tile only: taken from the thread
-      // index there, it does not occupy a register through the main loop
+      // the lane half is needed by the masking code only (ragged tile, causal mask): taken from the
+      // thread index there, it does not occupy a register through the main loop
       int h2 = 0;
-      if (decltype(masked)::value) {
+      if (decltype(masked)::value || kCausal) {
         int t2 = threadIdx.x;
         asm volatile("" : "+v"(t2));
         h2 = (t2 >> 5) & 1;
       }
-      process_tile2<decltype(masked)::value, D, kQR>(st, qf[0], qf[kNG - 1], qpark, stage, kaddr, vaddr, c, nvalid, h2);
+      process_tile2<decltype(masked)::value, D, kQR, kCausal>(st, qf[0], qf[kNG - 1], qpark, stage, kaddr, vaddr, c, nvalid, h2,
+                                                              kix_lds + stage_no * kIxStride + 4 * h2, q_lim[0], q_lim[kNG - 1]);
     }
+  };
+  // causal: the largest limit among this wave's queries (lanes without a query ask for nothing); a tile
+  // whose smallest key index lies beyond it has nothing for the wave
+  int wq_max = INT_MIN;
+  if constexpr (kCausal) {
+    wq_max = max(q_lim[0], q_lim[kNG - 1]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) wq_max = max(wq_max, __shfl_xor(wq_max, off));
+    wq_max = __builtin_amdgcn_readfirstlane(wq_max);
+  }
+  auto tile_has_visible_keys = [&](int stage_no) -> bool {
+    if constexpr (!kCausal) return true;
+    return __builtin_amdgcn_readfirstlane(kix_lds[stage_no * kIxStride + kTileKeys]) <= wq_max;
   };
   constexpr std::false_type kFull{};
   constexpr std::true_type kRagged{};
@@ -609,39 +629,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   // slot; their loads are issued right after the barrier, which also says that every wave is
   // done with that other slot (pair p-1).  The union entries of later tiles are read from LDS
   // early and turned into scalars late, so their latency hides behind the arithmetic.
-  if constexpr (kCausal) {
-    // the visible range of this wave's queries (lanes without a query see nothing and ask for nothing)
-    int wq_min = q_lim == INT_MIN ? INT_MAX : q_lim, wq_max = q_lim;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      wq_min = min(wq_min, __shfl_xor(wq_min, off));
-      wq_max = max(wq_max, __shfl_xor(wq_max, off));
-    }
-    wq_min = __builtin_amdgcn_readfirstlane(wq_min);
-    wq_max = __builtin_amdgcn_readfirstlane(wq_max);
-    uint32_t e_cur = entry_of(0);
-#pragma nounroll
-    for (int t = 0; t < n_tiles; ++t) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      uint32_t e_nxt = e_cur;
-      if (t + 1 < n_tiles) {
-        e_nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)seq[(t + 1) / TPB]);
-        issue_tile((int)(e_nxt & 0xffffffu) * TPB + ((t + 1) % TPB), (t + 1) & 1);
-      }
-      if (e_cur & my_bit) {
-        const int* kx = kix_lds + (t & 1) * kIxStride;
-        const int t_min = __builtin_amdgcn_readfirstlane(kx[kTileKeys]);
-        const int t_max = __builtin_amdgcn_readfirstlane(kx[kTileKeys + 1]);      // INT_MAX if the tile is ragged
-        const char* stage = smem + (t & 1) * kStageBytes;
-        if (t_min <= wq_max) {
-          if (t_max <= wq_min) process_tile<false, D>(st, qf[0], stage, kaddr, vaddr, c, kTileKeys, h);
-          else process_tile<false, D, true>(st, qf[0], stage, kaddr, vaddr, c, kTileKeys, h, kx, q_lim);
-        }
-      }
-      e_cur = e_nxt;
-    }
-  } else if constexpr (kNG == 2) {
+  if constexpr (kNG == 2) {
     // 64 queries per wave: ONE call site for full tiles (a second inlined copy of the tile code
     // costs the register allocator its footing).  Tiles travel in rounds of R = kStages / 2; the
     // workgroup meets once per round, and round p + 1 lands in the other half of the ring while
@@ -659,7 +647,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
         for (int j = 0; j < R; ++j) issue_tile(tile_of(t + R + j), half_next * R + j);
       }
       const uint32_t raw_n = seq[(t + 1) / TPB];
-      if (e_cur & my_bit) tile(kFull, smem + (((t / R) & 1) * R + t % R) * kStageBytes, kTileKeys);
+      if ((e_cur & my_bit) && tile_has_visible_keys(((t / R) & 1) * R + t % R)) tile(kFull, ((t / R) & 1) * R + t % R, kTileKeys);
       e_cur = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_n);
     }
     if (t % R == 0) {
@@ -667,7 +655,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
       __syncthreads();
     }
     const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
-    if (e_cur & my_bit) tile(kRagged, smem + (((t / R) & 1) * R + t % R) * kStageBytes, nvalid);
+    if ((e_cur & my_bit) && tile_has_visible_keys(((t / R) & 1) * R + t % R)) tile(kRagged, ((t / R) & 1) * R + t % R, nvalid);
   } else if constexpr (kStages == 4) {
   uint32_t e_a = entry_of(0);
   uint32_t e_b = entry_of(min(1, n_tiles - 1));
@@ -684,9 +672,9 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
       issue_tile(b0 * TPB + (tf0 % TPB), 2 * slot_next);
       issue_tile(b1 * TPB + (tf1 % TPB), 2 * slot_next + 1);
     }
-    const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
+    const int slot = ((t >> 1) & 1) * 2;            // first ring stage of the pair
     if (e_a & my_bit) tile(kFull, slot, kTileKeys);
-    if (e_b & my_bit) tile(kFull, slot + kStageBytes, kTileKeys);
+    if (e_b & my_bit) tile(kFull, slot + 1, kTileKeys);
     e_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f0);
     e_b = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_f1);
   }
@@ -694,11 +682,11 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
     // the last pair: one or two tiles, the very last one possibly ragged
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    const char* slot = smem + ((t >> 1) & 1) * (2 * kStageBytes);
+    const int slot = ((t >> 1) & 1) * 2;
     if (t + 1 < n_tiles) {
       if (e_a & my_bit) tile(kFull, slot, kTileKeys);
       const int nvalid = a.Lk - ((int)(e_b & 0xffffffu) * TPB + ((t + 1) % TPB)) * kTileKeys;
-      if (e_b & my_bit) tile(kRagged, slot + kStageBytes, nvalid);
+      if (e_b & my_bit) tile(kRagged, slot + 1, nvalid);
     } else {
       const int nvalid = a.Lk - ((int)(e_a & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
       if (e_a & my_bit) tile(kRagged, slot, nvalid);
@@ -714,13 +702,13 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
       const uint32_t raw_n = seq[(t + 1) / TPB];
       const uint32_t e_nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)raw_n);
       issue_tile((int)(e_nxt & 0xffffffu) * TPB + ((t + 1) % TPB), (t + 1) & 1);
-      if (e_cur & my_bit) tile(kFull, smem + (t & 1) * kStageBytes, kTileKeys);
+      if (e_cur & my_bit) tile(kFull, t & 1, kTileKeys);
       e_cur = e_nxt;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int nvalid = a.Lk - ((int)(e_cur & 0xffffffu) * TPB + (t % TPB)) * kTileKeys;
-    if (e_cur & my_bit) tile(kRagged, smem + (t & 1) * kStageBytes, nvalid);
+    if (e_cur & my_bit) tile(kRagged, t & 1, nvalid);
   }
 
   // ---- epilogue: normalise, scatter rows to their original positions
@@ -759,7 +747,7 @@ size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk
 
 template <int D>
 size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false) {
-  const size_t park = (size_t)(threads / 64) * (qpw / 32) * (D / 16 - q_reg_steps(D, qpw)) * 1024;
+  const size_t park = (size_t)(threads / 64) * (qpw / 32) * (D / 16 - q_reg_steps(D, qpw, causal)) * 1024;
   const size_t base = (size_t)stages_of(threads, qpw) * Geo<D>::kStageBytes + park + (size_t)Nk * 4 + (threads / 64) * 4;
   return causal ? ((base + 15) & ~(size_t)15) + (size_t)stages_of(threads, qpw) * kIxStride * 4 : base;
 }
@@ -947,7 +935,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
     }
     m.kix = kix;
     ProfScope prof(K_ATTN, st);
-    return launch_shape<kSoloQueries, 32, true>(m, B, d, BHq, st);
+    return launch_shape<kWideQueries, 64, true>(m, B, d, BHq, st);
   }
 
   // Which shape of workgroup: asked for, or (B = d = 128, block lists given, enough work to pay for
