@@ -81,27 +81,29 @@ def selection_bytes(w):
 class Pipeline:
     """Preallocated buffers for repeated select + attention calls on one workload."""
 
-    def __init__(self, w, sparsity, Q, K, V, beta=1.0, sort=bd.SORT_QK, mass_target=0.0):
+    def __init__(self, w, sparsity, Q, K, V, beta=1.0, sort=bd.SORT_QK, mass_target=0.0, causal=False):
         self.w, self.s, self.beta, self.sort, self.mass_target = w, sparsity, beta, sort, mass_target
+        self.causal = causal
         self.Q, self.K, self.V = Q, K, V
         dev = Q.device
-        p = bd.params(w.block, sparsity, beta, sort)
+        p = bd.params(w.block, sparsity, beta, sort, causal=causal)
         self.ws_sel = torch.empty(bd.select_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
         self.ws_att = torch.empty(bd.attn_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
-        self.sel = bd.basa_select(Q, K, w.block, sparsity, beta, sort, ws=self.ws_sel, mass_target=mass_target)
+        self.sel = bd.basa_select(Q, K, w.block, sparsity, beta, sort, ws=self.ws_sel, mass_target=mass_target,
+                                  causal=causal)
         self.out = torch.empty_like(Q)
 
     def select(self):
         bd.basa_select(self.Q, self.K, self.w.block, self.s, self.beta, self.sort, ws=self.ws_sel,
-                       out=self.sel, mass_target=self.mass_target)
+                       out=self.sel, mass_target=self.mass_target, causal=self.causal)
 
     def attn(self):
         s = self.sel
         bd.basa_sparse_attn(self.Q, self.K, self.V, s.row_count, s.row_cols, self.w.block, s.perm_q,
-                            s.perm_k, ws=self.ws_att, out=self.out)
+                            s.perm_k, ws=self.ws_att, out=self.out, causal=self.causal)
 
     def dense(self):
-        bd.basa_dense_attn(self.Q, self.K, self.V, self.w.block, ws=self.ws_att, out=self.out)
+        bd.basa_dense_attn(self.Q, self.K, self.V, self.w.block, ws=self.ws_att, out=self.out, causal=self.causal)
 
     def step(self):
         self.select()
@@ -208,8 +210,9 @@ def graph_step_ms(pipe, reps=20):
     return timed(graph.replay, reps) * 1e3
 
 
-def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK, mass_target=0.0):
-    pipe = Pipeline(w, sparsity, Q, K, V, beta, sort, mass_target)
+def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK, mass_target=0.0,
+            causal=False):
+    pipe = Pipeline(w, sparsity, Q, K, V, beta, sort, mass_target, causal)
     for _ in range(warmup):
         pipe.step()
     torch.cuda.synchronize()
@@ -237,10 +240,12 @@ def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd
     kappa = pipe.sel.kappa
     fl_exec = executed_flops(w, kappa)
     kept_mean = float(kappa)
-    if mass_target > 0.0:       # rows keep different numbers of blocks: count the executed pairs
+    if mass_target > 0.0 or causal:       # rows keep different numbers of blocks: count the listed pairs
         kept_mean = float(pipe.sel.row_count.double().mean())
         fl_exec = 4.0 * w.block * float(pipe.sel.row_count.sum()) * min(w.block, w.L) * w.d
     fl_dense = 4.0 * w.heads_q * float(w.L) ** 2 * w.d
+    if causal:                  # the token pairs a causal mask leaves: L (L + 1) / 2 per head
+        fl_dense = 4.0 * w.heads_q * (float(w.L) * (w.L + 1) / 2) * w.d
     attn_kernel_s = kern_ms.get("attn_mfma_kernel", 0.0) * 1e-3
     sb = selection_bytes(w)
     res = dict(
@@ -456,6 +461,11 @@ def main():
         for p_mass in (0.5, 0.9):
             rows.append(measure(w, 0.0, Q, K, V, 2, 1, dense_reps=0, mass_target=p_mass)[0]
                         | {"variant": f"cumulative mass {p_mass}"})
+        # the causal variant (visibility on original positions): listed block pairs are all computed and
+        # masked score by score, so `executed` counts listed pairs and `effective` the visible token pairs
+        rows.append(measure(w, args.sparsity, Q, K, V, 2, 1, dense_reps=1, causal=True)[0] | {"variant": "causal"})
+        rows.append(measure(w, args.sparsity, Q, K, V, 2, 1, dense_reps=0, sort=bd.SORT_NONE, causal=True)[0]
+                    | {"variant": "causal, sort=none"})
         del Q, K, V
         torch.cuda.empty_cache()
         # the headline workload with head dimension 64 (same generator), then the other configurations
