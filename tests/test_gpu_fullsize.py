@@ -160,3 +160,44 @@ def test_full_size_block_mass_sampled():
             l_blk = (qb.mean(0) @ k_mean.T) / np.sqrt(w.d)
             want_dev = np.abs(l_tok.reshape(B, n, B) - l_blk[None, :, None]).max(axis=(0, 2))
             np.testing.assert_allclose(dev[0, h, g].cpu().numpy(), want_dev, rtol=1e-4, atol=1e-4)
+
+
+@pytest.mark.parametrize("sort", [o.SORT_QK, o.SORT_NONE])
+def test_full_size_causal_attention_sampled(sort):
+    """The causal variant at the largest configuration: the permutations are the oracle's, every sampled
+    query block attends to its listed key blocks under the original-position mask (oracle, block by
+    block, on the lists the GPU selection produced), the dense causal entry on sampled blocks too."""
+    w = synth.CONFIGS[4]
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    sel = bd.basa_select(Q, K, w.block, 0.5, sort=sort, causal=True)
+    out, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k,
+                                   causal=True, want_lse=True)
+    torch.cuda.synchronize()
+    n = w.n_blocks
+    rng = np.random.default_rng(77)
+    worst = 0.0
+    for h in (0, 13, w.heads_q - 1):
+        q, k, v = np64(Q[0, h]), np64(K[0, h]), np64(V[0, h])
+        perm_q, perm_k = sel.perm_q[0, h].cpu().numpy(), sel.perm_k[0, h].cpu().numpy()
+        if sort == o.SORT_QK:
+            assert np.array_equal(perm_q, o.norm_sort(q)) and np.array_equal(perm_k, o.norm_sort(k))
+        cnt = sel.row_count[0, h].cpu().numpy()
+        cols = sel.row_cols[0, h].cpu().numpy().astype(np.int64)
+        out_h, lse_h = np64(out[0, h]), lse[0, h].cpu().numpy().astype(np.float64)
+        for g in [0, 1, n - 1] + rng.integers(n, size=4).tolist():
+            rows, O_ref, lse_ref = o.sparse_attention_causal_block(q, k, v, perm_q, perm_k, g, cols[g, :cnt[g]], w.block)
+            ma, _ = check_output(out_h[rows], O_ref, True, f"causal sort={sort} unit ({h},{g})")
+            worst = max(worst, ma)
+            seen = np.isfinite(lse_ref)
+            assert np.array_equal(np.isfinite(lse_h[rows]), seen)
+            np.testing.assert_allclose(lse_h[rows][seen], lse_ref[seen], rtol=0, atol=2e-3)
+    print(f"\n[cfg4 causal sort={sort}] kept per row mean {float(sel.row_count.float().mean()):.1f}, out_max_abs={worst:.2e}")
+    if sort == o.SORT_NONE:
+        dense = bd.basa_dense_attn(Q, K, V, w.block, causal=True)
+        torch.cuda.synchronize()
+        h = 5
+        q, k, v = np64(Q[0, h]), np64(K[0, h]), np64(V[0, h])
+        # rows a .. b-1 of the causal map are the oracle's suffix-aligned case with the keys cut at b
+        for a, b in ((0, 128), (65536 - 64, 65536 + 64), (w.L - 128, w.L)):
+            ref = o.dense_causal_attention(q[a:b], k[:b], v[:b])
+            check_output(np64(dense[0, h, a:b]), ref, True, f"dense causal rows {a}..{b}")
