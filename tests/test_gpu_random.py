@@ -53,6 +53,12 @@ def test_random_case(i):
     out, lse = bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, B, sel.perm_q, sel.perm_k, want_lse=True,
                                     attn_shape=i % 4)
     torch.cuda.synchronize()
+    if c["mass"] == 0:
+        # the kernel that keeps the score map on chip: same bitmap, counts and lists
+        chip = bd.basa_select(Q, K, B, c["s"], c["beta"], c["sort"], c["window"], segments=c["segments"], select_path=2)
+        for name in ("mask_bits", "row_count", "row_cols", "perm_q", "perm_k"):
+            assert torch.equal(getattr(chip, name), getattr(sel, name)), f"select_path 2, {name}: {c}"
+        assert (chip.row_mass - sel.row_mass).abs().max().item() <= 2e-6, str(c)
     gpu_mask = unpack_mask(sel.mask_bits, sel.n_k)
     group = c["hq"] // c["hk"]
     what = str(c)
