@@ -337,6 +337,96 @@ __global__ __launch_bounds__(kSortThreads) void merge_pass_kernel(const uint64_t
   }
 }
 
+// ---------------------------------------------------------------------------------
+// The first two merge passes in one: four neighbouring sorted tiles (16384 words, 128 KB) are
+// brought into LDS, merged pairwise and then into one run, and written out once, so the words
+// cross the memory system one time less.  1024 threads, 16 words each: a thread finds the start
+// of its 16 consecutive outputs with a merge-path search in LDS, merges them into registers, and
+// the workgroup puts the registers back into LDS between the two levels.  Slots past the end of
+// the segment hold the all-ones word, which sorts last (no packed word has segment field 63).
+// ---------------------------------------------------------------------------------
+constexpr int kQuadThreads = 1024, kQuadItems = 16, kQuadWords = 4 * kTile;
+static_assert(kQuadThreads * kQuadItems == kQuadWords, "one word per thread and item");
+
+__global__ __launch_bounds__(kQuadThreads) void merge_quads_kernel(const uint64_t* __restrict__ in,
+                                                                   uint64_t* __restrict__ out,
+                                                                   int32_t* __restrict__ perm0,
+                                                                   int32_t* __restrict__ perm1, int BH0, SegGeom g,
+                                                                   int quads_per_seg, int quads_total) {
+  extern __shared__ __attribute__((aligned(16))) uint64_t quad[];       // kQuadWords
+  const int t = threadIdx.x;
+  // A workgroup takes quads blockIdx.x, blockIdx.x + gridDim.x, ... (two of them as launched): the words
+  // of the next one are requested into registers before this one is merged, so the memory system is
+  // not idle while the workgroup works in LDS.
+  struct Where { const uint64_t* src; int64_t obase; int n; int32_t* perm_out; };
+  auto locate = [&](int id) -> Where {
+    const int per_bh = g.segs * quads_per_seg;
+    const int bh = id / per_bh, r = id - bh * per_bh;
+    const int seg = r / quads_per_seg, q = r - seg * quads_per_seg;
+    const int seg_end = min((seg + 1) * g.W, g.L);
+    const int a0 = seg * g.W + q * kQuadWords;
+    const int64_t hb = (int64_t)bh * g.L;
+    Where w;
+    w.n = max(0, min(kQuadWords, seg_end - a0));       // 0: the segment ends before this quad
+    w.src = in + hb + a0;
+    w.obase = hb + a0;
+    w.perm_out = bh < BH0 ? perm0 : (perm1 ? perm1 - (int64_t)BH0 * g.L : nullptr);
+    return w;
+  };
+  auto request = [&](const Where& w, uint64_t (&v)[kQuadItems]) {
+    // all sixteen loads of a thread in flight together: index clamped, padding applied at the store to LDS
+    if (w.n == 0) return;                        // workgroup-uniform: nothing of this quad exists
+#pragma unroll
+    for (int e = 0; e < kQuadItems; ++e) v[e] = w.src[min(e * kQuadThreads + t, w.n - 1)];
+  };
+  int id = blockIdx.x;
+  if (id >= quads_total) return;
+  Where cur = locate(id);
+  uint64_t v[kQuadItems];
+  request(cur, v);
+  for (;;) {
+    const int n = cur.n;
+#pragma unroll
+    for (int e = 0; e < kQuadItems; ++e) quad[e * kQuadThreads + t] = e * kQuadThreads + t < n ? v[e] : ~0ull;
+    const int id_next = id + (int)gridDim.x;
+    Where nxt = cur;
+    if (id_next < quads_total) {               // workgroup-uniform
+      nxt = locate(id_next);
+      request(nxt, v);
+    }
+    __syncthreads();
+    const int d0 = t * kQuadItems;               // this thread's outputs d0 .. d0 + 15 at both levels
+#pragma unroll
+    for (int run = kTile; run <= 2 * kTile; run *= 2) {
+      const int pb = d0 & ~(2 * run - 1);        // first word of the pair of runs these outputs belong to
+      const uint64_t* A = quad + pb;
+      const uint64_t* Bv = quad + pb + run;
+      int ia = merge_path(A, run, Bv, run, d0 - pb);
+      int ib = d0 - pb - ia;
+      uint64_t res[kQuadItems];
+#pragma unroll
+      for (int e = 0; e < kQuadItems; ++e) {
+        const uint64_t va = ia < run ? A[ia] : ~0ull;
+        const uint64_t vb = ib < run ? Bv[ib] : ~0ull;
+        if (va <= vb) { res[e] = va; ++ia; } else { res[e] = vb; ++ib; }
+      }
+      __syncthreads();                           // everyone is done reading the runs
+#pragma unroll
+      for (int e = 0; e < kQuadItems; ++e) quad[d0 + e] = res[e];
+      __syncthreads();
+    }
+    if (cur.perm_out) {
+      for (int i = t; i < n; i += kQuadThreads) cur.perm_out[cur.obase + i] = idx_of_word(quad[i]);
+    } else {
+      for (int i = t; i < n; i += kQuadThreads) out[cur.obase + i] = quad[i];
+    }
+    if (id_next >= quads_total) break;
+    __syncthreads();                             // the stores above read LDS; the next quad overwrites it
+    id = id_next;
+    cur = nxt;
+  }
+}
+
 __global__ void iota_kernel(int32_t* perm, int L, int64_t total) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < total) perm[i] = (int32_t)(i % L);
@@ -392,7 +482,23 @@ static basa_status norm_sort_impl(const TensorView& x0, const TensorView* x1, in
 
   uint64_t* src = buf1;
   uint64_t* dst = buf0;
-  for (int run = kTile; run < g.W; run *= 2) {
+  int run0 = kTile;
+  if (g.W > 2 * kTile) {
+    // more than two tiles per segment: the first two passes in one launch
+    const bool last = kQuadWords >= g.W;
+    const int quads_per_seg = ceil_div(g.W, kQuadWords);
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&merge_quads_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kQuadWords * 8);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
+    ProfScope prof(K_MERGE, st);
+    const int quads_total = BH * g.segs * quads_per_seg;
+    hipLaunchKernelGGL(merge_quads_kernel, dim3(ceil_div(quads_total, 2)), dim3(kQuadThreads), kQuadWords * 8, st,
+                       src, dst, last ? perm0 : nullptr, last ? perm1 : nullptr, BH0, g, quads_per_seg, quads_total);
+    BASA_HIP_CHECK_LAUNCH("merge_quads_kernel");
+    uint64_t* t = src; src = dst; dst = t;
+    run0 = kQuadWords;
+  }
+  for (int run = run0; run < g.W; run *= 2) {
     const bool last = run * 2 >= g.W;
     const int pairs_per_seg = ceil_div(ceil_div(g.W, run), 2);
     const int chunks_per_pair = ceil_div(2 * run, kMergeChunk);

@@ -59,6 +59,23 @@ def test_norm_sort_windowed_and_ties():
             assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), want), f"window={window}"
 
 
+def test_norm_sort_with_runs_of_three_to_eighteen_tiles():
+    """Segments longer than two sort tiles go through the kernel that merges four tiles in LDS: a ragged
+    quad that is also the last pass (window of 3.03 tiles), whole quads followed by ordinary passes
+    (10 tiles per window, the last window cut short), one run of 17.1 tiles, and a segment list."""
+    w = C[1].scaled("quads", heads_q=2, heads_kv=2, L=70000 + 64)
+    Q, _, _ = gen(w)
+    for window in (12416, 40960, 16384, 0):
+        perm = bd.basa_norm_sort(Q, w.block, window=window)
+        for h in range(2):
+            want = o.norm_sort(np64(Q[0, h]), window)
+            assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), want), f"window={window}"
+    segs = [0, 9000, 30001, 50000]
+    perm = bd.basa_norm_sort(Q, w.block, segments=segs)
+    for h in range(2):
+        assert np.array_equal(perm[0, h].cpu().numpy().astype(np.int64), o.norm_sort(np64(Q[0, h]), 0, segs))
+
+
 @pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
 def test_norm_sort_segments(dtype, d):
     L = 20000 + 37
