@@ -74,10 +74,13 @@ typedef struct {
                                 as a mass budget), at least min_keep and at most kappa    */
   int32_t min_keep;          /* floor on the per-row count when mass_target > 0; 0 means 1 */
   int32_t attn_shape;        /* basa_sparse_attn, bf16 only: shape of the attention workgroup.
-                              * 0 = chosen by the library (on the device, from how much the
-                              * lists of neighbouring query blocks overlap), 1 = 256 queries
-                              * sharing every K/V tile, 2 = 128 queries.  The shapes give
-                              * identical results; other entry points ignore it.            */
+                              * 0 = chosen by the library (on the device, between 3 and 2, from
+                              * how much the lists of neighbouring query blocks overlap),
+                              * 1 = 256 queries sharing every K/V tile, 2 = 128 queries,
+                              * 3 = 512 queries (64 per wave).  1 and 2 give identical bits;
+                              * 3 refreshes the running maximum every 32 keys instead of every
+                              * 64 and agrees with them within the output tolerance.  The causal
+                              * variant always runs shape 3; other entry points ignore the field */
   int32_t n_segments;        /* 0: none.  1..BASA_MAX_SEGMENTS: the sort is segment-aware (the
                                 windowed sort of Alg. 1 step 1 with runs of unequal length, e.g.
                                 one run per modality or frame): tokens segment_starts[j] ..
