@@ -201,3 +201,28 @@ def test_full_size_causal_attention_sampled(sort):
         for a, b in ((0, 128), (65536 - 64, 65536 + 64), (w.L - 128, w.L)):
             ref = o.dense_causal_attention(q[a:b], k[:b], v[:b])
             check_output(np64(dense[0, h, a:b]), ref, True, f"dense causal rows {a}..{b}")
+
+
+def test_full_size_results_are_the_same_bits_on_every_run():
+    """Selection and attention at the largest configuration, three runs into separate buffers: every
+    output identical (both attention shapes the library chooses between, and the causal variant)."""
+    w = synth.CONFIGS[4]
+    Q, K, V = synth.make_qkv(w, device=DEV)
+    first = None
+    for _ in range(3):
+        sel = bd.basa_select(Q, K, w.block, 0.5)
+        outs = [bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, w.block, sel.perm_q, sel.perm_k,
+                                    attn_shape=shape, want_lse=True) for shape in (3, 2)]
+        selc = bd.basa_select(Q, K, w.block, 0.75, causal=True)
+        outs.append(bd.basa_sparse_attn(Q, K, V, selc.row_count, selc.row_cols, w.block, selc.perm_q, selc.perm_k,
+                                        causal=True, want_lse=True))
+        torch.cuda.synchronize()
+        got = [sel.mask_bits, sel.row_cols, sel.row_mass, sel.perm_q, sel.perm_k, selc.row_count, selc.row_cols]
+        for o_, l_ in outs:
+            got += [o_, l_]
+        if first is None:
+            first = got
+        else:
+            for i, (a, b) in enumerate(zip(first, got)):
+                # (-inf == -inf in the log-sum-exp of blind causal rows; NaN nowhere)
+                assert torch.equal(a, b), f"output {i} differs between runs"
