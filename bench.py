@@ -85,6 +85,15 @@ class Pipeline:
         self.w, self.s, self.beta, self.sort, self.mass_target = w, sparsity, beta, sort, mass_target
         self.causal = causal
         self.Q, self.K, self.V = Q, K, V
+        # Inputs that fit the 256 MB Infinity Cache would be served from it on every step after the
+        # first: rotate over enough copies (same values, other addresses) that each step finds its
+        # inputs in HBM only.
+        nbytes = sum(t.numel() * t.element_size() for t in (Q, K, V))
+        self.copies = [(Q, K, V)]
+        if nbytes < 512e6:
+            for _ in range(min(7, int(1.0e9 // nbytes))):
+                self.copies.append((Q.clone(), K.clone(), V.clone()))
+        self.turn = 0
         dev = Q.device
         p = bd.params(w.block, sparsity, beta, sort, causal=causal)
         self.ws_sel = torch.empty(bd.select_workspace_size(Q, K, p), dtype=torch.uint8, device=dev)
@@ -93,21 +102,31 @@ class Pipeline:
                                   causal=causal)
         self.out = torch.empty_like(Q)
 
-    def select(self):
+    def _next(self):
+        self.turn = (self.turn + 1) % len(self.copies)
+        self.Q, self.K, self.V = self.copies[self.turn]
+
+    def select(self, rotate=True):
+        if rotate:
+            self._next()
         bd.basa_select(self.Q, self.K, self.w.block, self.s, self.beta, self.sort, ws=self.ws_sel,
                        out=self.sel, mass_target=self.mass_target, causal=self.causal)
 
-    def attn(self):
+    def attn(self, rotate=True):
+        if rotate:
+            self._next()
         s = self.sel
         bd.basa_sparse_attn(self.Q, self.K, self.V, s.row_count, s.row_cols, self.w.block, s.perm_q,
                             s.perm_k, ws=self.ws_att, out=self.out, causal=self.causal)
 
     def dense(self):
+        self._next()
         bd.basa_dense_attn(self.Q, self.K, self.V, self.w.block, ws=self.ws_att, out=self.out, causal=self.causal)
 
     def step(self):
-        self.select()
-        self.attn()
+        self._next()
+        self.select(rotate=False)
+        self.attn(rotate=False)
 
 
 def timed(fn, reps):
@@ -204,10 +223,12 @@ def graph_step_ms(pipe, reps=20):
         pipe.step()
     torch.cuda.current_stream().wait_stream(side)
     graph = torch.cuda.CUDAGraph()
+    n = len(pipe.copies)          # one step per input copy in the graph, so that replays stay HBM-fed too
     with torch.cuda.graph(graph, stream=side):
-        pipe.step()
+        for _ in range(n):
+            pipe.step()
     graph.replay()
-    return timed(graph.replay, reps) * 1e3
+    return timed(graph.replay, max(2, reps // n)) * 1e3 / n
 
 
 def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd.SORT_QK, mass_target=0.0,
@@ -250,6 +271,7 @@ def measure(w, sparsity, Q, K, V, steps, warmup, dense_reps=1, beta=1.0, sort=bd
     sb = selection_bytes(w)
     res = dict(
         workload=w.name, sparsity=sparsity, kappa=kappa, n_blocks=w.n_blocks, mass_target=mass_target,
+        input_copies=len(pipe.copies),
         step_ms_median=per_step[len(per_step) // 2], step_ms_min=per_step[0],
         kept_blocks_per_row_mean=kept_mean,
         t_e2e_ms=t_step * 1e3, t_select_ms=t_sel * 1e3, t_attn_ms=t_att * 1e3,
