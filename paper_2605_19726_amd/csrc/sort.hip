@@ -174,10 +174,7 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
       raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)(start + loc) * x.stride_l * kElem)[sub];
     }
   };
-  uint4 cur[kIters], nxt[kIters];
-  load_pass(0, cur);
-  for (int pass = 0; pass < passes; ++pass) {
-    load_pass(pass + 1, nxt);
+  auto keys_of_pass = [&](int pass, const uint4 (&cur)[kIters]) {
     // per-lane partial sums of the kIters rows this lane contributes to
     double acc[kIters];
 #pragma unroll
@@ -231,8 +228,19 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
       buf[tile_slot(loc)] = pack_word(sg, key, start + loc);
       if (keys_out) keys_out[hb + start + loc] = key;
     }
-#pragma unroll
-    for (int it = 0; it < kIters; ++it) cur[it] = nxt[it];
+  };
+  // three batches of rows: two are in flight while the third is turned into keys (a pass past the last
+  // re-reads the last one and writes nothing: its positions lie beyond n)
+  uint4 b0[kIters], b1[kIters], b2[kIters];
+  load_pass(0, b0);
+  load_pass(1, b1);
+  for (int pass = 0; pass < passes; pass += 3) {
+    load_pass(pass + 2, b2);
+    keys_of_pass(pass, b0);
+    load_pass(pass + 3, b0);
+    keys_of_pass(pass + 1, b1);
+    load_pass(pass + 4, b1);
+    keys_of_pass(pass + 2, b2);
   }
   for (int i = n + threadIdx.x; i < kTile; i += kSortThreads) buf[tile_slot(i)] = ~0ull;
   __syncthreads();
