@@ -222,10 +222,9 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
     const int loc = pass * kRowsPerPass + it_mine * kRowsPerIter + rig;
     if (sub < 8 && loc < n) {
       const float key = (float)acc[0];
-      int sg = seg_lo;
-      if (!one_segment)
-        for (int j = seg_lo + 1; j < sl.n; ++j) sg += (start + loc >= sl.bound[j]) ? 1 : 0;
-      buf[tile_slot(loc)] = pack_word(sg, key, start + loc);
+      // (the segment of the tile's first token; a tile that straddles a boundary is put right below,
+      //  outside this loop, whose loads the compiler can then count exactly)
+      buf[tile_slot(loc)] = pack_word(seg_lo, key, start + loc);
       if (keys_out) keys_out[hb + start + loc] = key;
     }
   };
@@ -234,13 +233,25 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
   uint4 b0[kIters], b1[kIters], b2[kIters];
   load_pass(0, b0);
   load_pass(1, b1);
+  load_pass(2, b2);
   for (int pass = 0; pass < passes; pass += 3) {
-    load_pass(pass + 2, b2);
     keys_of_pass(pass, b0);
     load_pass(pass + 3, b0);
     keys_of_pass(pass + 1, b1);
     load_pass(pass + 4, b1);
     keys_of_pass(pass + 2, b2);
+    load_pass(pass + 5, b2);
+  }
+  if (!one_segment) {              // workgroup-uniform and rare: some tokens belong to later segments
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kSortThreads) {
+      int sg = seg_lo;
+      for (int j = seg_lo + 1; j < sl.n; ++j) sg += (start + i >= sl.bound[j]) ? 1 : 0;
+      if (sg != seg_lo) {
+        const uint64_t w = buf[tile_slot(i)];
+        buf[tile_slot(i)] = (w & ((1ull << 58) - 1ull)) | ((uint64_t)(uint32_t)sg << 58);
+      }
+    }
   }
   for (int i = n + threadIdx.x; i < kTile; i += kSortThreads) buf[tile_slot(i)] = ~0ull;
   __syncthreads();
