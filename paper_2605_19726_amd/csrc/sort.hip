@@ -243,6 +243,9 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
     load_pass(pass + 5, b2);
   }
   if (!one_segment) {              // workgroup-uniform and rare: some tokens belong to later segments
+    // (the keys stored in the loop above have to be in LDS before the barrier; the compiler's own wait
+    //  was found missing on this path by lds_wait_audit, so it is spelt out)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __syncthreads();
     for (int i = threadIdx.x; i < n; i += kSortThreads) {
       int sg = seg_lo;
@@ -254,6 +257,7 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
     }
   }
   for (int i = n + threadIdx.x; i < kTile; i += kSortThreads) buf[tile_slot(i)] = ~0ull;
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __syncthreads();
 
   // ---- phase 2: bitonic network over the kTile words
