@@ -1,12 +1,14 @@
-"""Check of the compiled kernels: no workgroup barrier may be reachable from an LDS store or LDS atomic
-of the same wave without an `s_waitcnt` that brings lgkmcnt to 0 in between.
+"""Check of the compiled kernels: no workgroup barrier may be reachable from an LDS instruction of the
+same wave (store, atomic, and load or permute as well) without an `s_waitcnt` that brings lgkmcnt to 0
+in between.
 
 Why it exists: a wave that stores to LDS and then meets its workgroup at `s_barrier` has to wait for
 that store first, or another wave can pass the barrier and read the old value.  The fence inside
 `__syncthreads()` asks for this wait, but the compiler's wait-count pass was found to drop the LDS
 part in one loop of the block-mass diagnostic kernel (a store in a conditional tail of the loop body,
 the barrier at the top of the next iteration): rare stale partial sums, different from run to run.
-The source now spells the wait out there; this audit reads the assembly the build keeps
+The same gap came back once more, in the key pass, when a barrier was added after its loop, and was
+caught here before any test saw it.  The source spells the wait out in both places; this audit reads the assembly the build keeps
 (`_build/*-gfx950.s`, written with -save-temps) and reports every place where the pattern comes
 back, in any kernel.
 
@@ -20,7 +22,7 @@ import re
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
-_LDS_STORE = re.compile(r"^ds_(write|add|sub|or|and|xor|max|min|inc|dec|cmpst|wrxchg|append|consume)")
+_LDS_OP = re.compile(r"^ds_(?!nop)")          # loads too: an LDS load still in flight at the barrier can be overtaken by another wave's store
 _LABEL = re.compile(r"^(\.LBB\d+_\d+):")
 
 
@@ -82,7 +84,7 @@ def audit_function(body):
                     if u.startswith("s_waitcnt") and "lgkmcnt(0)" in u:
                         settled = True
                         break
-                    if _LDS_STORE.match(u):
+                    if _LDS_OP.match(u):
                         hit = (k, u, blk)
                         break
                 if settled or hit:
