@@ -78,9 +78,13 @@ typedef struct {
                               * how much the lists of neighbouring query blocks overlap),
                               * 1 = 256 queries sharing every K/V tile, 2 = 128 queries,
                               * 3 = 512 queries (64 per wave).  1 and 2 give identical bits;
-                              * 3 refreshes the running maximum every 32 keys instead of every
-                              * 64 and agrees with them within the output tolerance.  The causal
-                              * variant always runs shape 3; other entry points ignore the field */
+                              * 3 runs the online softmax against a reference that is raised only
+                              * when the row sums ask for it, not against the running maximum, and
+                              * repeats with running maxima the workgroups whose row sums left the
+                              * range in which that is exact; 4 = shape 3 with running maxima from
+                              * the start (for comparison).  3 and 4 agree with 1 and 2 within the
+                              * output tolerance.  The causal variant always runs shape 3 (4 if
+                              * asked for); other entry points ignore the field */
   int32_t n_segments;        /* 0: none.  1..BASA_MAX_SEGMENTS: the sort is segment-aware (the
                                 windowed sort of Alg. 1 step 1 with runs of unequal length, e.g.
                                 one run per modality or frame): tokens segment_starts[j] ..

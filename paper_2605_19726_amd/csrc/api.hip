@@ -385,7 +385,7 @@ basa_status basa_sparse_attn(const basa_tensor* q, const basa_tensor* k, const b
   if ((s = check_params(p, false)) != BASA_OK) return s;
   if (row_cols && !row_count) { set_error("row_cols given without row_count"); return BASA_ERR_INVALID_ARG; }
   if (row_cols && cols_stride < 1) { set_error("cols_stride must be >= 1"); return BASA_ERR_INVALID_ARG; }
-  if (p->attn_shape < 0 || p->attn_shape > 3) { set_error("attn_shape must be 0, 1, 2 or 3"); return BASA_ERR_INVALID_ARG; }
+  if (p->attn_shape < 0 || p->attn_shape > 4) { set_error("attn_shape must be 0, 1, 2, 3 or 4"); return BASA_ERR_INVALID_ARG; }
   return attn_common(q, k, v, row_count, row_cols, cols_stride, perm_q, perm_k, p->block, p->attn_shape, p->causal, out,
                      out_strides, lse, ws, ws_bytes, stream);
 }

@@ -54,6 +54,14 @@ constexpr int kIxStride = kTileKeys + 4;    // causal: ints per tile of the key-
 #define BASA_ATTN_QR 7
 #endif
 constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
+// The pass without running maxima (64 queries per wave): a query's reference moves up by kShiftLog2
+// once the probabilities of half a tile add up to more than kSafeSum; a row whose final sum lies
+// outside [kMinSum, kMaxSum] (or is not a number) has left the range in which that pass is exact.
+constexpr float kSafeSum = 1.0995116e12f;   // 2^40
+constexpr float kShiftLog2 = 40.0f;
+constexpr float kShiftMul = 9.094947e-13f;  // 2^-40
+constexpr float kMinSum = 8.6736174e-19f;   // 2^-60
+constexpr float kMaxSum = 1.2676506e30f;    // 2^100
 // Two shapes of workgroup.  SHARED: 8 waves own 256 queries = two (four) neighbouring query blocks
 // that share every K/V tile; best when their lists overlap, which they do for the full method.
 // SOLO: 4 waves own 128 queries = one query block of 128 (two of 64), two workgroups per compute
@@ -165,6 +173,8 @@ struct MfmaArgs {
   int causal_off;            // causal: L_k - L_q
   const int32_t* probe;      // nullable: {blocks in the union of a group's lists, blocks in its lists} over sampled groups
   int run_if_solo;           // with probe: this launch runs iff (lists overlap little) == run_if_solo
+  int32_t* redo;             // nullable, one word per workgroup: written by the pass without running maxima (1 = a row
+                             // sum left the safe range), read by the pass with them, which skips workgroups at 0
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -267,6 +277,7 @@ template <int D>
 struct WaveState2 {
   floatx16 o[2][Geo<D>::kDBlocks];
   float m_run[2], l_run[2];
+  float lt[2];               // kFast: the row sums of the half tile before this one
 };
 
 // kQR of the k-steps take their Q^T fragments from registers; the others are read back from the
@@ -275,7 +286,14 @@ struct WaveState2 {
 // kCausal: kix4 points at the lane's four key indices of the tile's first group of eight keys
 // (original positions, INT_MAX past the end of the sequence, which also covers the ragged tile); a
 // key is visible to the query of group a / b iff its index does not exceed qla / qlb.
-template <bool kMasked, int D, int kQR, bool kCausal = false>
+// kFast: no maximum is taken.  The reference m of a query only has to keep 2^(c s - m) inside the
+// range of the formats (bf16 and fp32 share their exponent), it need not be the maximum: it starts at
+// 0 and is raised by kShiftLog2 whenever the row sums of the half tile before, which are needed
+// anyway, exceed kSafeSum.  The caller checks the final sums (kMinSum, kMaxSum) and has the rows
+// computed again with running maxima if a sum has left the safe range.  Taking the maximum of every
+// half tile (16 v_max3, two lane exchanges, and the wait of every exponential for the last score)
+// was a quarter of the vector instructions of a tile.
+template <bool kMasked, int D, int kQR, bool kCausal = false, bool kFast = false>
 __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&qa)[kQR], const bf16x8 (&qb)[kQR],
                                               const char* qs, const char* stage, int kaddr0, int vaddr0, float c,
                                               int nvalid, int h, const int* kix4 = nullptr, int qla = 0, int qlb = 0) {
@@ -326,28 +344,43 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
         }
       }
     }
-    float mxa = max3(sa[0], sa[1], sa[2]), mxb = max3(sb[0], sb[1], sb[2]);
+    if constexpr (kFast) {
+      if (__builtin_amdgcn_ballot_w64(st.lt[0] > kSafeSum || st.lt[1] > kSafeSum) != 0) {
+        // a query's keys are split over two lanes (lane halves), which must move its reference together
+        const bool ua = st.lt[0] > kSafeSum || __shfl_xor(st.lt[0], 32) > kSafeSum;
+        const bool ub = st.lt[1] > kSafeSum || __shfl_xor(st.lt[1], 32) > kSafeSum;
+        const float aa = ua ? kShiftMul : 1.f, ab = ub ? kShiftMul : 1.f;
+        st.m_run[0] += ua ? kShiftLog2 : 0.f; st.m_run[1] += ub ? kShiftLog2 : 0.f;
+        st.l_run[0] *= aa; st.l_run[1] *= ab;
 #pragma unroll
-    for (int r = 3; r < 15; r += 2) { mxa = max3(mxa, sa[r], sa[r + 1]); mxb = max3(mxb, sb[r], sb[r + 1]); }
-    mxa = fmaxf(mxa, sa[15]); mxb = fmaxf(mxb, sb[15]);
-    // (exchanging the halves with v_permlane32_swap instead of the LDS permute measured 1 % slower)
-    mxa = fmaxf(mxa, __shfl_xor(mxa, 32)); mxb = fmaxf(mxb, __shfl_xor(mxb, 32));
-    const float mca = mxa * c, mcb = mxb * c;
-    if (__builtin_amdgcn_ballot_w64(mca > st.m_run[0] + kLazyTau || mcb > st.m_run[1] + kLazyTau) != 0) {
-      const float na = fmaxf(st.m_run[0], mca), nb = fmaxf(st.m_run[1], mcb);
-      // (causal: a query that still sees nothing has -inf on both sides; its state stays as it is)
-      const float aa = (kCausal && na == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run[0] - na);
-      const float ab = (kCausal && nb == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run[1] - nb);
-      st.m_run[0] = na; st.m_run[1] = nb;
-      st.l_run[0] *= aa; st.l_run[1] *= ab;
+        for (int i = 0; i < Geo<D>::kDBlocks; ++i)
 #pragma unroll
-      for (int i = 0; i < Geo<D>::kDBlocks; ++i)
+          for (int r = 0; r < 16; ++r) { st.o[0][i][r] *= aa; st.o[1][i][r] *= ab; }
+      }
+    } else {
+      float mxa = max3(sa[0], sa[1], sa[2]), mxb = max3(sb[0], sb[1], sb[2]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { st.o[0][i][r] *= aa; st.o[1][i][r] *= ab; }
+      for (int r = 3; r < 15; r += 2) { mxa = max3(mxa, sa[r], sa[r + 1]); mxb = max3(mxb, sb[r], sb[r + 1]); }
+      mxa = fmaxf(mxa, sa[15]); mxb = fmaxf(mxb, sb[15]);
+      // (exchanging the halves with v_permlane32_swap instead of the LDS permute measured 1 % slower)
+      mxa = fmaxf(mxa, __shfl_xor(mxa, 32)); mxb = fmaxf(mxb, __shfl_xor(mxb, 32));
+      const float mca = mxa * c, mcb = mxb * c;
+      if (__builtin_amdgcn_ballot_w64(mca > st.m_run[0] + kLazyTau || mcb > st.m_run[1] + kLazyTau) != 0) {
+        const float na = fmaxf(st.m_run[0], mca), nb = fmaxf(st.m_run[1], mcb);
+        // (causal: a query that still sees nothing has -inf on both sides; its state stays as it is)
+        const float aa = (kCausal && na == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run[0] - na);
+        const float ab = (kCausal && nb == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m_run[1] - nb);
+        st.m_run[0] = na; st.m_run[1] = nb;
+        st.l_run[0] *= aa; st.l_run[1] *= ab;
+#pragma unroll
+        for (int i = 0; i < Geo<D>::kDBlocks; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { st.o[0][i][r] *= aa; st.o[1][i][r] *= ab; }
+      }
     }
     // (causal: a query that has seen no key yet subtracts 0, so that exp2 sees -inf, never inf - inf)
-    const float ma = (kCausal && st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];
-    const float mb = (kCausal && st.m_run[1] == -INFINITY) ? 0.f : st.m_run[1];
+    const float ma = (!kFast && kCausal && st.m_run[0] == -INFINITY) ? 0.f : st.m_run[0];
+    const float mb = (!kFast && kCausal && st.m_run[1] == -INFINITY) ? 0.f : st.m_run[1];
     bf16x8 pa[2], pb[2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -355,7 +388,7 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
       pb[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sb[r], c, -mb));
     }
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    float la = st.l_run[0], lb = st.l_run[1];
+    float la = kFast ? 0.f : st.l_run[0], lb = kFast ? 0.f : st.l_run[1];
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       la = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pa[g], pa[g], 0, 1), ones, la, false);
@@ -367,7 +400,12 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
       lb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 4, 5), ones, lb, false);
       lb = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[g], pb[g], 6, 7), ones, lb, false);
     }
-    st.l_run[0] = la; st.l_run[1] = lb;
+    if constexpr (kFast) {
+      st.l_run[0] += la; st.l_run[1] += lb;
+      st.lt[0] = la; st.lt[1] = lb;
+    } else {
+      st.l_run[0] = la; st.l_run[1] = lb;
+    }
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const uint32_t va = vbase ^ (uint32_t)((2 * half + g) << 5);
@@ -385,20 +423,21 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
 template <int D, int NG> struct StateOf { typedef WaveState<D> type; };
 template <int D> struct StateOf<D, 2> { typedef WaveState2<D> type; };
 template <int D>
-__device__ __forceinline__ void init_state(WaveState<D>& st) {
+__device__ __forceinline__ void init_state(WaveState<D>& st, bool = false) {
 #pragma unroll
   for (int i = 0; i < Geo<D>::kDBlocks; ++i) st.o[i] = floatx16{0};
   st.m_run = -INFINITY;
   st.l_run = 0.f;
 }
 template <int D>
-__device__ __forceinline__ void init_state(WaveState2<D>& st) {
+__device__ __forceinline__ void init_state(WaveState2<D>& st, bool fast = false) {
 #pragma unroll
   for (int r = 0; r < 2; ++r) {
 #pragma unroll
     for (int i = 0; i < Geo<D>::kDBlocks; ++i) st.o[r][i] = floatx16{0};
-    st.m_run[r] = -INFINITY;
+    st.m_run[r] = fast ? 0.f : -INFINITY;
     st.l_run[r] = 0.f;
+    st.lt[r] = 0.f;
   }
 }
 template <int D> __device__ __forceinline__ float l_of(const WaveState<D>& st, int) { return st.l_run; }
@@ -420,10 +459,11 @@ __device__ __forceinline__ int64_t out_off(const MfmaArgs& a, int bhq, int row) 
 // kCausal (512-query shape only): the ring is followed by the original key indices of each stage's
 // tile (with their minimum), every score is masked by original position, and a wave skips a tile
 // none of whose keys is visible to any of its queries.
-template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false>
+template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false, bool kFast = false>
 __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 : 2) void attn_mfma_kernel(MfmaArgs a) {
   using G = Geo<D>;
   static_assert(!kCausal || (kQPW == 64 && kWgQueries == kWideQueries), "the causal path is built on the 512-query shape");
+  static_assert(!kFast || (kQPW == 64 && kWgQueries == kWideQueries), "the pass without running maxima is built on the 512-query shape");
   constexpr int kWaves = kWgQueries / kQPW, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
   constexpr int kNG = kQPW / 32;             // 32-query groups per wave: 1 or 2
   constexpr int kStages = stages_of(kThreads, kQPW);
@@ -453,6 +493,8 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   // XCD a contiguous range of (head, query blocks) so that its L2 sees one head at a time.
   int logical = blockIdx.x;
   if ((a.total_wgs & 7) == 0) logical = (blockIdx.x & 7) * (a.total_wgs >> 3) + (blockIdx.x >> 3);
+  // the pass with running maxima, launched behind the one without: only the workgroups that one gave up on
+  if (!kFast && a.redo && a.redo[logical] == 0) return;
   const int bhq = logical / a.wgs_per_head, wg = logical - bhq * a.wgs_per_head;
   const int bhk = bhq / a.group;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -508,6 +550,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
         if (a.lse && h == 0) a.lse[(int64_t)bhq * a.Lq + orow] = -INFINITY;
       }
     }
+    if (kFast && tid == 0) a.redo[logical] = 0;
     return;
   }
   int n_tiles = n_union * TPB;
@@ -582,7 +625,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   const int vaddr = li * 128 + ((h ^ ((li >> 1) & 7)) << 4);
 
   typename StateOf<D, kNG>::type st;
-  init_state<D>(st);
+  init_state<D>(st, kFast);
   const float c = a.scale_log2e;
   // one 64-key tile of the ring, for the one or two query groups of this wave
   auto tile = [&](auto masked, int stage_no, int nvalid) {
@@ -597,8 +640,9 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
         asm volatile("" : "+v"(t2));
         h2 = (t2 >> 5) & 1;
       }
-      process_tile2<decltype(masked)::value, D, kQR, kCausal>(st, qf[0], qf[kNG - 1], qpark, stage, kaddr, vaddr, c, nvalid, h2,
-                                                              kix_lds + stage_no * kIxStride + 4 * h2, q_lim[0], q_lim[kNG - 1]);
+      process_tile2<decltype(masked)::value, D, kQR, kCausal, kFast>(st, qf[0], qf[kNG - 1], qpark, stage, kaddr, vaddr, c, nvalid,
+                                                                     h2, kix_lds + stage_no * kIxStride + 4 * h2, q_lim[0],
+                                                                     q_lim[kNG - 1]);
     }
   };
   // causal: the largest limit among this wave's queries (lanes without a query ask for nothing); a tile
@@ -718,12 +762,14 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   asm volatile("" : "+v"(tid_e));
   const int h_e = (tid_e >> 5) & 1;
   const int pos_e = wg * kQueriesPerWg + (tid_e >> 6) * kQPW + (tid_e & 31);
+  int unsafe = 0;                // kFast: some row of this lane has a sum outside the safe range
 #pragma unroll
   for (int r = 0; r < kNG; ++r) {
     const float l_part = l_of(st, r), m_fin = m_of(st, r);
     const float l_tot = l_part + __shfl_xor(l_part, 32);
     const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;    // a query block without any valid key block: zeros
     const int pos = pos_e + 32 * r;
+    if (kFast && pos < a.Lq && !(l_tot >= kMinSum && l_tot <= kMaxSum)) unsafe = 1;
     const int h = h_e;
     if (pos < a.Lq) {
       const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
@@ -741,9 +787,15 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
         a.lse[(int64_t)bhq * a.Lq + orow] = (m_fin + __log2f(l_tot)) * 0.6931471805599453f;
     }
   }
+  if constexpr (kFast) {
+    // (a row without any visible key has the sum 0 as well and is sent round again: it comes out as zeros both times)
+    const int any = __syncthreads_or(unsafe);
+    if (threadIdx.x == 0) a.redo[logical] = any;
+  }
 }
 
 size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk * B * d * 2, 256); }
+size_t sz_kix(int BHkv, int Nk, int B) { return align_up((size_t)BHkv * (Nk * B / kTileKeys) * kIxStride * 4, 256); }
 
 template <int D>
 size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false) {
@@ -752,7 +804,7 @@ size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false) {
   return causal ? ((base + 15) & ~(size_t)15) + (size_t)stages_of(threads, qpw) * kIxStride * 4 : base;
 }
 
-template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false>
+template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false, bool kFast = false>
 basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
   constexpr int kThreads = kWgQueries / kQPW * 64;
   const size_t lds = lds_bytes<D>(kThreads, kQPW, m.Nk, kCausal);
@@ -764,20 +816,33 @@ basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
   }
   m.wgs_per_head = ceil_div(m.Nq * kB, kWgQueries);
   m.total_wgs = BHq * m.wgs_per_head;
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries, kQPW, kCausal>),
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<kB, D, kWgQueries, kQPW, kCausal, kFast>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(dynamic LDS)");
-  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries, kQPW, kCausal>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
+  hipLaunchKernelGGL((attn_mfma_kernel<kB, D, kWgQueries, kQPW, kCausal, kFast>), dim3(m.total_wgs), dim3(kThreads), lds, st, m);
   BASA_HIP_CHECK_LAUNCH("attn_mfma_kernel");
   return BASA_OK;
 }
 // dispatch on block size and head dimension
-template <int kWgQueries, int kQPW, bool kCausal = false>
+template <int kWgQueries, int kQPW, bool kCausal = false, bool kFast = false>
 basa_status launch_shape(const MfmaArgs& m, int B, int d, int BHq, hipStream_t st) {
-  if (d == 128) return B == 128 ? launch_main<128, 128, kWgQueries, kQPW, kCausal>(m, BHq, st)
-                                : launch_main<64, 128, kWgQueries, kQPW, kCausal>(m, BHq, st);
-  return B == 128 ? launch_main<128, 64, kWgQueries, kQPW, kCausal>(m, BHq, st)
-                  : launch_main<64, 64, kWgQueries, kQPW, kCausal>(m, BHq, st);
+  if (d == 128) return B == 128 ? launch_main<128, 128, kWgQueries, kQPW, kCausal, kFast>(m, BHq, st)
+                                : launch_main<64, 128, kWgQueries, kQPW, kCausal, kFast>(m, BHq, st);
+  return B == 128 ? launch_main<128, 64, kWgQueries, kQPW, kCausal, kFast>(m, BHq, st)
+                  : launch_main<64, 64, kWgQueries, kQPW, kCausal, kFast>(m, BHq, st);
+}
+// The 512-query shape in two passes: without running maxima, then, for the workgroups whose row sums
+// left the safe range (none on ordinary inputs: that launch returns at once), with them.
+template <bool kCausal>
+basa_status launch_wide(MfmaArgs m, int B, int d, int BHq, int32_t* redo, bool two_pass, hipStream_t st) {
+  if (two_pass) {
+    m.redo = redo;
+    const basa_status s = launch_shape<kWideQueries, 64, kCausal, true>(m, B, d, BHq, st);
+    if (s != BASA_OK) return s;
+  } else {
+    m.redo = nullptr;
+  }
+  return launch_shape<kWideQueries, 64, kCausal, false>(m, B, d, BHq, st);
 }
 
 // Causal variant: per 64-key tile of the ordered keys, the original index of every key (INT_MAX past
@@ -868,9 +933,9 @@ basa_status launch_gathers(const AttnArgs& a, uint4* Kt, uint4* Vt, int BHkv, in
 
 size_t attn_mfma_workspace_bytes(int BHq, int BHkv, int Lq, int Lk, int d, int B) {
   const int Nq = ceil_div(Lq, B), Nk = ceil_div(Lk, B);
-  (void)BHq; (void)Nq;
   // + the two counters of the list-overlap probe + the key-index tiles of the causal variant
-  return 2 * sz_kv(BHkv, Nk, B, d) + 256 + align_up((size_t)BHkv * (Nk * B / kTileKeys) * kIxStride * 4, 256);
+  // + one word per 512-query workgroup (which of them the pass with running maxima has to repeat)
+  return 2 * sz_kv(BHkv, Nk, B, d) + 256 + sz_kix(BHkv, Nk, B) + align_up((size_t)BHq * ceil_div(Nq * B, kWideQueries) * 4, 256);
 }
 
 basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
@@ -905,6 +970,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   uint4* Kt = reinterpret_cast<uint4*>(ws);
   uint4* Vt = reinterpret_cast<uint4*>(ws + sz_kv(BHkv, Nk, B, d));
   int32_t* probe = reinterpret_cast<int32_t*>(ws + 2 * sz_kv(BHkv, Nk, B, d));
+  int32_t* redo = reinterpret_cast<int32_t*>(ws + 2 * sz_kv(BHkv, Nk, B, d) + 256 + sz_kix(BHkv, Nk, B));
 
   {
     ProfScope prof(K_GATHER, st);
@@ -923,7 +989,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   m.group = a.q.heads / a.k.heads;
   m.wgs_per_head = 0; m.total_wgs = 0;
   m.scale_log2e = 1.4426950408889634f / sqrtf((float)d);
-  m.probe = nullptr; m.run_if_solo = 0;
+  m.probe = nullptr; m.run_if_solo = 0; m.redo = nullptr;
   m.kix = nullptr; m.causal_off = a.causal_off;
   if (a.causal) {
     int32_t* kix = reinterpret_cast<int32_t*>(ws + 2 * sz_kv(BHkv, Nk, B, d) + 256);
@@ -935,7 +1001,7 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
     }
     m.kix = kix;
     ProfScope prof(K_ATTN, st);
-    return launch_shape<kWideQueries, 64, true>(m, B, d, BHq, st);
+    return launch_wide<true>(m, B, d, BHq, redo, a.variant != 4, st);
   }
 
   // Which shape of workgroup: asked for, or (B = d = 128, block lists given, enough work to pay for
@@ -956,9 +1022,9 @@ basa_status launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   ProfScope prof(K_ATTN, st);
   basa_status s = BASA_OK;
   if (variant == 1) return launch_shape<kSharedQueries, 32>(m, B, d, BHq, st);
-  if (variant == 0 || variant == 3) {
+  if (variant == 0 || variant == 3 || variant == 4) {
     m.run_if_solo = 0;
-    if ((s = launch_shape<kWideQueries, 64>(m, B, d, BHq, st)) != BASA_OK) return s;
+    if ((s = launch_wide<false>(m, B, d, BHq, redo, variant != 4, st)) != BASA_OK) return s;
   }
   if (variant == 0 || variant == 2) {
     m.run_if_solo = 1;

@@ -121,7 +121,7 @@ def test_attention_argument_validation(lib):
     big = fake_tensor(L=128 * 16385)
     name, why = call(q, big, big, wsb=1 << 50)
     assert name == "BASA_ERR_UNSUPPORTED" and "key blocks per head exceed" in why
-    for bad in (-1, 4):
+    for bad in (-1, 5):
         assert call(q, k, v, wsb=1 << 40, p_=bd.params(128, attn_shape=bad))[0] == "BASA_ERR_INVALID_ARG"
     # output strides: token-major is fine (and reaches the workspace check), the rest is refused
     assert call(q, k, v, ostr=strides(256 * 2 * 128, 128, 2 * 128))[0] == "BASA_ERR_WORKSPACE"

@@ -313,12 +313,13 @@ def test_two_streams_with_their_own_buffers_do_not_interfere():
 @pytest.mark.parametrize("L", [1, 100, 640 + 33, 2048 + 77])
 def test_every_workgroup_shape_against_the_oracle(L, block, d):
     # the 256-query and the 128-query workgroup are two schedules of the same arithmetic; the
-    # 512-query one (64 queries per wave) refreshes the running maximum every 32 keys instead of
-    # every 64, so its bits differ while it meets the same tolerance
+    # 512-query one (64 queries per wave) exponentiates against a reference that is not the running
+    # maximum (shape 3) or against a maximum refreshed every 32 keys instead of every 64 (shape 4),
+    # so its bits differ while it meets the same tolerance
     Q, K, V = (_randn((1, 2, L, d), 600 + i, torch.bfloat16) for i in range(3))
     sel = bd.basa_select(Q, K, block, 0.5, 0.0, bd.SORT_NONE)           # lists with little in common
     outs = [bd.basa_sparse_attn(Q, K, V, sel.row_count, sel.row_cols, block, sel.perm_q, sel.perm_k,
-                                want_lse=True, attn_shape=shape) for shape in (1, 2, 3, 0)]
+                                want_lse=True, attn_shape=shape) for shape in (1, 2, 3, 0, 4)]
     torch.cuda.synchronize()
     for h in range(2):
         q, k, v = np64(Q[0, h]), np64(K[0, h]), np64(V[0, h])
@@ -327,13 +328,68 @@ def test_every_workgroup_shape_against_the_oracle(L, block, d):
         lists = [cols[r, :cnt[r]] for r in range(cols.shape[0])]
         O_ref, lse_ref = o.sparse_attention(q, k, v, sel.perm_q[0, h].cpu().numpy(), sel.perm_k[0, h].cpu().numpy(),
                                             lists, block, return_lse=True)
-        for (out, lse), name in zip(outs, ("shared", "solo", "wide", "auto")):
+        for (out, lse), name in zip(outs, ("shared", "solo", "wide", "auto", "wide with running maxima")):
             check_output(np64(out[0, h]), O_ref, True, f"{name} L={L} B={block} d={d} head {h}")
             np.testing.assert_allclose(lse[0, h].cpu().numpy(), lse_ref, rtol=0, atol=3e-2)
     # 32 queries per wave: every wave walks its own tiles in the same order in both shapes: identical bits
     assert torch.equal(outs[0][0], outs[1][0])
     # too small for the overlap probe: the library takes the 512-query shape
     assert torch.equal(outs[3][0], outs[2][0]) and torch.equal(outs[3][1], outs[2][1])
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [128, 64])
+def test_scores_outside_the_range_of_the_pass_without_running_maxima(d, causal):
+    """The 512-query shape first exponentiates against a reference that starts at 0 and only moves up
+    in steps of 2^40; a workgroup with a row sum outside [2^-60, 2^100] is computed again with running
+    maxima.  Heads whose scaled scores sit near +300, near -300, climb by hundreds from tile to tile,
+    or are ordinary, next to each other: every one must come out as the oracle's (a row that the
+    first pass overflowed or flushed to zero and that was not repeated would be NaN, inf or zero)."""
+    H, L, B = 5, 1024 + 40, 128
+    g = torch.Generator().manual_seed(910 + d)
+    u = torch.randn(d, generator=g, dtype=torch.float64)
+    u /= u.norm()
+    noise = lambda sc: sc * torch.randn(L, d, generator=g, dtype=torch.float64)
+    amp = (300.0 * (d ** 0.5) / 1.4426950408889634) ** 0.5        # (amp u) . (amp u) / sqrt(d) * log2(e) = 300
+    Q = torch.empty(1, H, L, d, dtype=torch.float64)
+    K = torch.empty(1, H, L, d, dtype=torch.float64)
+    Q[0, 0], K[0, 0] = amp * u + noise(0.5), amp * u + noise(0.5)          # every score near +300 (in log2 units)
+    Q[0, 1], K[0, 1] = amp * u + noise(0.5), -amp * u + noise(0.5)         # every score near -300
+    ramp = torch.linspace(0.0, 1.0, L, dtype=torch.float64)[:, None]
+    Q[0, 2], K[0, 2] = amp * u + noise(0.5), 2.0 * amp * ramp * u + noise(0.5)    # climbing from 0 to +600 along the keys
+    Q[0, 3], K[0, 3] = noise(1.0), noise(1.0)                               # ordinary
+    Q[0, 4], K[0, 4] = amp * u + noise(0.5), 2.0 * amp * (1.0 - ramp) * u + noise(0.5)   # falling from +600 to 0
+    V = torch.randn(1, H, L, d, generator=g, dtype=torch.float64)
+    Q, K, V = (t.to(torch.bfloat16).to(DEV) for t in (Q, K, V))
+    n = (L + B - 1) // B
+    rng = np.random.default_rng(12)
+    keep = n - 2
+    cols = np.stack([np.sort(rng.choice(n, keep, replace=False)) for _ in range(H * n)]).reshape(H, n, keep)
+    if causal:                        # every query block lists its own key block, so that no row is empty
+        for h in range(H):
+            for r in range(n):
+                if r not in cols[h, r]:
+                    cols[h, r, 0] = r
+                    cols[h, r].sort()
+    row_cols = torch.from_numpy(cols.astype(np.int32)).reshape(1, H, n, keep).contiguous().to(DEV)
+    row_count = torch.full((1, H, n), keep, dtype=torch.int32, device=DEV)
+    out3, lse3 = bd.basa_sparse_attn(Q, K, V, row_count, row_cols, B, want_lse=True, attn_shape=3, causal=causal)
+    out4, lse4 = bd.basa_sparse_attn(Q, K, V, row_count, row_cols, B, want_lse=True, attn_shape=4, causal=causal)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out3.float()).all()) and bool(torch.isfinite(lse3).all())
+    ident = np.arange(L)
+    for h in range(H):
+        q, k, v = np64(Q[0, h]), np64(K[0, h]), np64(V[0, h])
+        lists = [cols[h, r] for r in range(n)]
+        O_ref, lse_ref = (o.sparse_attention_causal if causal else o.sparse_attention)(q, k, v, ident, ident, lists, B,
+                                                                                      return_lse=True)
+        for out, lse, name in ((out3, lse3, "two passes"), (out4, lse4, "running maxima")):
+            check_output(np64(out[0, h]), O_ref, True, f"{name} head {h} d={d} causal={causal}")
+            np.testing.assert_allclose(lse[0, h].cpu().numpy(), lse_ref, rtol=1e-4, atol=3e-2)
+    # the heads that cannot but be repeated carry the bits of the pass with running maxima (the climbing
+    # head is followed by the moving reference, the ordinary one never leaves the range)
+    for h in (0, 1, 4):
+        assert torch.equal(out3[0, h], out4[0, h]), h
 
 
 @pytest.mark.parametrize("kind", ["overlapping", "disjoint", "ragged"])
