@@ -347,8 +347,11 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
     if constexpr (kFast) {
       if (__builtin_amdgcn_ballot_w64(st.lt[0] > kSafeSum || st.lt[1] > kSafeSum) != 0) {
         // a query's keys are split over two lanes (lane halves), which must move its reference together
-        const bool ua = st.lt[0] > kSafeSum || __shfl_xor(st.lt[0], 32) > kSafeSum;
-        const bool ub = st.lt[1] > kSafeSum || __shfl_xor(st.lt[1], 32) > kSafeSum;
+        // (the exchanges first, by every lane: inside a short-circuit `||` only the lanes that still have
+        //  to ask would be active, and a lane exchange reads 0 from an inactive lane)
+        const float other_a = __shfl_xor(st.lt[0], 32), other_b = __shfl_xor(st.lt[1], 32);
+        const bool ua = (st.lt[0] > kSafeSum) | (other_a > kSafeSum);
+        const bool ub = (st.lt[1] > kSafeSum) | (other_b > kSafeSum);
         const float aa = ua ? kShiftMul : 1.f, ab = ub ? kShiftMul : 1.f;
         st.m_run[0] += ua ? kShiftLog2 : 0.f; st.m_run[1] += ub ? kShiftLog2 : 0.f;
         st.l_run[0] *= aa; st.l_run[1] *= ab;
