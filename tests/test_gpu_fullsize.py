@@ -190,7 +190,10 @@ def test_full_size_causal_attention_sampled(sort):
             worst = max(worst, ma)
             seen = np.isfinite(lse_ref)
             assert np.array_equal(np.isfinite(lse_h[rows]), seen)
-            np.testing.assert_allclose(lse_h[rows][seen], lse_ref[seen], rtol=0, atol=2e-3)
+            # the row sum is taken over the bf16-rounded probabilities (relative error of each at most
+            # 2^-9, so of the sum too: 1.95e-3 in the logarithm, reached by a row that sees one key whose
+            # probability is not an exact power of two), plus the hardware exp2 / log2
+            np.testing.assert_allclose(lse_h[rows][seen], lse_ref[seen], rtol=0, atol=2.5e-3)
     print(f"\n[cfg4 causal sort={sort}] kept per row mean {float(sel.row_count.float().mean()):.1f}, out_max_abs={worst:.2e}")
     if sort == o.SORT_NONE:
         dense = bd.basa_dense_attn(Q, K, V, w.block, causal=True)

@@ -34,9 +34,11 @@ def test_static_norm_sort_equals_workspace_norm_sort_on_two_calls_in_a_row():
         want, want_keys = bd.basa_norm_sort(Q, w.block, window=window, return_keys=True)
         perm = torch.full((1, heads, L), -1, dtype=torch.int32, device=DEV)
         keys = torch.empty((1, heads, L), dtype=torch.float32, device=DEV)
-        before = torch.cuda.memory_allocated()
+        # (the number of allocations made so far, not the bytes in use: a tensor of an earlier test that
+        #  the garbage collector happens to free during the call would change the latter)
+        before = torch.cuda.memory_stats()["allocation.all.allocated"]
         bd.basa_norm_sort_static(Q, w.block, perm, window=window, keys=keys)
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
         torch.cuda.synchronize()
         assert torch.equal(perm, want), name
         assert torch.equal(keys, want_keys), name
