@@ -772,7 +772,10 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
     const float l_tot = l_part + __shfl_xor(l_part, 32);
     const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;    // a query block without any valid key block: zeros
     const int pos = pos_e + 32 * r;
-    if (kFast && pos < a.Lq && !(l_tot >= kMinSum && l_tot <= kMaxSum)) unsafe = 1;
+    // (on the bit patterns, which order like the values for positive floats and put inf, NaN and anything
+    //  negative above kMaxSum: this file is compiled without NaN semantics for float comparisons)
+    if (kFast && pos < a.Lq && __float_as_uint(l_tot) - __float_as_uint(kMinSum) > __float_as_uint(kMaxSum) - __float_as_uint(kMinSum))
+      unsafe = 1;
     const int h = h_e;
     if (pos < a.Lq) {
       const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
