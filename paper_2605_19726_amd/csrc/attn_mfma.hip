@@ -7,7 +7,7 @@
 // the global -> LDS copy is a linear 16 KB copy done with direct-to-LDS loads:
 //   (Q needs no copy: every wave reads the rows of its 32 queries once, through perm_q)
 //   Kt [BHkv][tiles][64 rows][16 chunks of 8 bf16]   rows of K in sorted order; chunk c
-//        of row r sits at chunk position c ^ k_swizzle(r)            (XOR swizzle)
+//        of row r sits at chunk position c ^ (r & 15)                (XOR swizzle)
 //   Vt [BHkv][tiles][128 d-rows][8 chunks of 8 keys] V in sorted order, transposed per
 //        tile (d major); the 8 keys of a chunk are in MFMA operand-slot order (below);
 //        chunk c of d-row r sits at chunk position c ^ ((r >> 1) & 7)
@@ -53,9 +53,6 @@ constexpr int kIxStride = kTileKeys + 4;    // causal: ints per tile of the key-
 #ifndef BASA_ATTN_QR
 #define BASA_ATTN_QR 7
 #endif
-#ifndef BASA_ATTN_M16
-#define BASA_ATTN_M16 0
-#endif
 constexpr float kLazyTau = 8.0f;            // log2 of the largest exponentiated score kept
 // The pass without running maxima (64 queries per wave): a query's reference moves up by kShiftLog2
 // once the probabilities of half a tile add up to more than kSafeSum; a row whose final sum lies
@@ -86,16 +83,6 @@ struct Geo {
   static constexpr int kDBlocks = D / 32;                    // 32-row blocks of O^T
   static constexpr int kChunksPerTile = kTileBytes / 1024;   // 1 KB direct-to-LDS loads per K (or V^T) tile
 };
-// Chunk position of a K-tile row: chunk c of row r sits at c ^ k_swizzle(r).  For D = 128 (16 chunks per
-// row, a row fills the 64 banks once) the rows 0-15 and 16-31 of a 32-row group get different halves of
-// the code space swapped, so that 16 lanes reading one chunk of rows 0..15 (32x32 MFMA operand) as well
-// as of rows {0-7, 16-23} or {8-15, 24-31} (16x16 MFMA operand with permuted rows) hit 16 distinct
-// 16-byte bank groups.
-template <int D>
-__host__ __device__ constexpr int k_swizzle(int row) {
-  return D == 128 ? ((row & 15) ^ (((row >> 4) & 1) << 3)) : (row & 7);
-}
-
 // Ring stages of a workgroup: one of 512 threads has the compute unit to itself and walks tiles in
 // pairs (two slots of two); two workgroups of 256 threads share a compute unit and walk one by one.
 // With 64 queries per wave a tile keeps the workgroup busy twice as long, and one tile of prefetch
@@ -129,7 +116,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(TensorView x, const in
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int pos = blockIdx.x * 64 + it * RPI + rig;
-    const int c = swizzle ? (sub ^ k_swizzle<D>(pos)) : sub;
+    const int c = swizzle ? (sub ^ (pos & (CPR - 1))) : sub;
     if (pos < rows_padded) dst[((int64_t)bh * rows_padded + pos) * CPR + c] = v[it];
   }
 }
@@ -435,160 +422,9 @@ __device__ __forceinline__ void process_tile2(WaveState2<D>& st, const bf16x8 (&
   }
 }
 
-// 64 queries per wave on v_mfma_f32_16x16x32_bf16 (D = 128): four query groups of 16, lane (j, g) =
-// (lane & 15, lane >> 4) owns query j of every group.  At the power limit this chip sustains about 10 %
-// more 16x16x32 than 32x32x16 matrix instructions on changing operands (1907 against 1726 TFLOP/s in a
-// bare loop on one box), and the operand traffic per flop is the same: a K fragment (16 keys x 32 d) or
-// a V^T fragment (16 d-rows x 32 keys) read from LDS feeds four MFMAs, one per query group.
-// A 32-key half is two score blocks X and Y of 16 keys whose ROWS are permuted, X = keys {0-7, 16-23}
-// and Y = keys {8-15, 24-31} of the half: the four accumulator rows of lane group g in X followed by
-// those in Y are then exactly the eight keys, in slot order, of chunk g of the V^T tile image that the
-// 32x32 kernels use, so one workspace layout serves every shape.
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-template <int D>
-struct WaveState4 {
-  floatx4 o[4][D / 16];              // [query group][16-row block of O^T]
-  float m_run[4], l_run[4];
-  float lt[4];                       // kFast: the row sums of the half tile before this one
-};
-
-template <bool kMasked, int D, int kNREG, bool kFast = false>
-__device__ __forceinline__ void process_tile4(WaveState4<D>& st, const bf16x8 (&qf)[kNREG], const char* qs,
-                                              const char* stage, int kaddr_x, int kaddr_y, int vaddr0, float c,
-                                              int nvalid, int g) {
-  constexpr int KS = D / 32;                        // k-steps of the score product
-  // one LDS address per operand and tile, opaque to the compiler (see process_tile2)
-  uint32_t kx = lds_addr(stage) + (uint32_t)kaddr_x, ky = lds_addr(stage) + (uint32_t)kaddr_y;
-  uint32_t vbase = lds_addr(stage) + (uint32_t)(Geo<D>::kTileBytes + vaddr0);
-  asm volatile("" : "+v"(kx), "+v"(ky), "+v"(vbase));
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    if (kMasked && half == 1 && nvalid <= 32) break;        // wave-uniform: no key in the second half
-    asm volatile("" ::: "memory");                          // parked fragments are read again in every half
-    floatx4 sx[4], sy[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { sx[q] = floatx4{0}; sy[q] = floatx4{0}; }
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const bf16x8 fx = lds_frag((kx ^ (uint32_t)(s << 6)) + half * 32 * Geo<D>::kRowBytes);
-      const bf16x8 fy = lds_frag((ky ^ (uint32_t)(s << 6)) + half * 32 * Geo<D>::kRowBytes);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int f = s * 4 + q;
-        bf16x8 qq;
-        if (f < kNREG) qq = qf[f < kNREG ? f : 0];
-        else qq = *reinterpret_cast<const bf16x8*>(qs + (f - kNREG) * 1024);
-        sx[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fx, qq, sx[q], 0, 0, 0);
-        sy[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fy, qq, sy[q], 0, 0, 0);
-      }
-    }
-    if (kMasked && nvalid < kTileKeys) {
-      // accumulator row 4g + r of block X is key (4 (g & 1) + r) + 16 (g >> 1) of the half, of Y 8 more
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int kk = 32 * half + 4 * (g & 1) + r + 16 * (g >> 1);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (kk >= nvalid) sx[q][r] = -INFINITY;
-          if (kk + 8 >= nvalid) sy[q][r] = -INFINITY;
-        }
-      }
-    }
-    if constexpr (kFast) {
-      // no maximum (see process_tile2): the reference of a query moves up when the row sums of the half
-      // before, over any of the four lanes that share the query, exceed kSafeSum
-      bool any = false;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) any = any | (st.lt[q] > kSafeSum);
-      if (__builtin_amdgcn_ballot_w64(any) != 0) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float t = st.lt[q];
-          t = fmaxf(t, __shfl_xor(t, 16));
-          t = fmaxf(t, __shfl_xor(t, 32));
-          const bool up = t > kSafeSum;
-          const float alpha = up ? kShiftMul : 1.f;
-          st.m_run[q] += up ? kShiftLog2 : 0.f;
-          st.l_run[q] *= alpha;
-#pragma unroll
-          for (int i = 0; i < D / 16; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) st.o[q][i][r] *= alpha;
-        }
-      }
-    } else {
-      // ---- lazy running max: the lane's own eight keys per query decide whether anything has to move;
-      //      only then are the maxima exchanged between the four lanes of a query
-      float mx[4];
-      bool grow = false;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        mx[q] = fmaxf(max3(sx[q][0], sx[q][1], sx[q][2]), max3(sx[q][3], sy[q][0], sy[q][1]));
-        mx[q] = max3(mx[q], sy[q][2], sy[q][3]);
-        grow = grow || (mx[q] * c > st.m_run[q] + kLazyTau);
-      }
-      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float m = mx[q];
-          m = fmaxf(m, __shfl_xor(m, 16));
-          m = fmaxf(m, __shfl_xor(m, 32));
-          const float m_new = fmaxf(st.m_run[q], m * c);
-          const float alpha = __builtin_amdgcn_exp2f(st.m_run[q] - m_new);
-          st.m_run[q] = m_new;
-          st.l_run[q] *= alpha;
-#pragma unroll
-          for (int i = 0; i < D / 16; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) st.o[q][i][r] *= alpha;
-        }
-      }
-    }
-    bf16x8 pb[4];
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float m = st.m_run[q];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        pb[q][r] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sx[q][r], c, -m));
-        pb[q][4 + r] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sy[q][r], c, -m));
-      }
-      float l = kFast ? 0.f : st.l_run[q];
-      l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[q], pb[q], 0, 1), ones, l, false);
-      l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[q], pb[q], 2, 3), ones, l, false);
-      l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[q], pb[q], 4, 5), ones, l, false);
-      l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pb[q], pb[q], 6, 7), ones, l, false);
-      if constexpr (kFast) { st.l_run[q] += l; st.lt[q] = l; }
-      else st.l_run[q] = l;
-    }
-    // ---- O^T += V^T P^T: chunk 4 half + g of d-row 16 db + j
-    const uint32_t va = vbase ^ (uint32_t)(half << 6);
-#pragma unroll
-    for (int db = 0; db < D / 16; ++db) {
-      const bf16x8 vv = lds_frag(va + db * 16 * 128);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        st.o[q][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, pb[q], st.o[q][db], 0, 0, 0);
-    }
-  }
-}
-
 // State of a wave by number of query groups, with uniform accessors for prologue and epilogue.
 template <int D, int NG> struct StateOf { typedef WaveState<D> type; };
 template <int D> struct StateOf<D, 2> { typedef WaveState2<D> type; };
-template <int D> struct StateOf<D, 4> { typedef WaveState4<D> type; };
-template <int D>
-__device__ __forceinline__ void init_state(WaveState4<D>& st, bool fast = false) {
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) st.o[q][i] = floatx4{0};
-    st.m_run[q] = fast ? 0.f : -INFINITY;
-    st.l_run[q] = 0.f;
-    st.lt[q] = 0.f;
-  }
-}
 template <int D>
 __device__ __forceinline__ void init_state(WaveState<D>& st, bool = false) {
 #pragma unroll
@@ -636,10 +472,6 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   constexpr int kStages = stages_of(kThreads, kQPW);
   constexpr int kQR = q_reg_steps(D, kQPW, kCausal), kQL = G::kKSteps - kQR;
   constexpr int kQParkBytes = kWaves * kNG * kQL * 1024;
-  // 64 queries per wave at D = 128 run on 16x16x32 MFMAs (process_tile4): 16 Q^T fragments (k-step of
-  // 32, query group of 16) per lane, as large as the 16 of the 32x32 form, the last 2 kQL of them parked
-  constexpr bool kM16 = kQPW == 64 && D == 128 && BASA_ATTN_M16 && kFast && !kCausal;
-  constexpr int kNREG = 2 * kQR;
   constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = kStages * kStageBytes;
   constexpr int kLoadsPerWave = 2 * G::kChunksPerTile / kWaves;
   constexpr int NQB = kQueriesPerWg / kB;    // query blocks per workgroup: 2 or 4 (SOLO: 1 or 2)
@@ -768,30 +600,11 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   if (kStages == 4) issue_tile(tile_of(1), 1);
 
   // Q^T operand: lane (query li, half h) holds Q[q][16 s + 8 h .. +7] for s = 0..7
-  bf16x8 qf[kM16 ? 1 : kNG][kM16 ? 1 : kQR];
-  bf16x8 qf16[kM16 ? kNREG : 1];
+  bf16x8 qf[kNG][kQR];
   int q_lim[kNG];               // kCausal: the largest original key index the lane's query of each group may see
 #pragma unroll
   for (int r = 0; r < kNG; ++r) q_lim[r] = INT_MIN;
   char* qpark = smem + kRingBytes + (wave * kNG * kQL) * 1024 + lane * 16;    // this lane's parked fragments
-  if constexpr (kM16) {
-    // lane (j, g): fragment (k-step s, query group q) = Q[query 16 q + j][32 s + 8 g .. +7]
-    const int j = lane & 15, g = lane >> 4;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int qpos = wg * kQueriesPerWg + wave * kQPW + 16 * q + j;
-      const int qrow = qpos < a.Lq ? perm_at(a.perm_q, (int64_t)bhq * a.Lq, qpos, a.Lq) : 0;
-      const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q.ptr) +
-                                                       (a.q.head_offset(bhq) + (int64_t)qrow * a.q.stride_l) * 2);
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s) {
-        uint4 t = qp[4 * s + g];
-        const int f = s * 4 + q;
-        if (f < kNREG) qf16[f < kNREG ? f : 0] = *reinterpret_cast<bf16x8*>(&t);
-        else *reinterpret_cast<uint4*>(qpark + (f - kNREG) * 1024) = t;        // read back by this lane only
-      }
-    }
-  } else {
 #pragma unroll
   for (int r = 0; r < kNG; ++r) {
     // the query of sorted position qpos, read from the caller's tensor; positions past L_q
@@ -808,35 +621,20 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
       else *reinterpret_cast<uint4*>(qpark + (r * kQL + s - kQR) * 1024) = t;    // read back by this lane only
     }
   }
-  }
   // LDS byte offsets inside a stage.  K: row li (+32 for the second block), chunk 2s+h at
   // position (2s+h) ^ (li & 15).  V^T: d-row li (+32 db), chunk 2g+h at (2g+h) ^ ((li>>1)&7).
   // (step s / group g are folded in by xor with s<<5 / g<<5 at the point of use)
-  const int kaddr = li * G::kRowBytes + ((h ^ k_swizzle<D>(li)) << 4);
+  const int kaddr = li * G::kRowBytes + ((h ^ (li & (G::kChunksPerRow - 1))) << 4);
   const int vaddr = li * 128 + ((h ^ ((li >> 1) & 7)) << 4);
 
-  typename StateOf<D, kM16 ? 4 : kNG>::type st;
+  typename StateOf<D, kNG>::type st;
   init_state<D>(st, kFast);
   const float c = a.scale_log2e;
-  // 16x16 form: K rows {0-7, 16-23} (block X; block Y 8 rows further) and V^T d-row j of the lane
-  const int j16 = lane & 15, g16 = lane >> 4;
-  const int row_x = (j16 & 7) + 16 * (j16 >> 3);
-  const int kaddr_x = row_x * G::kRowBytes + ((g16 ^ k_swizzle<D>(row_x)) << 4);
-  const int kaddr_y = (row_x + 8) * G::kRowBytes + ((g16 ^ k_swizzle<D>(row_x + 8)) << 4);
-  const int vaddr16 = j16 * 128 + ((g16 ^ ((j16 >> 1) & 7)) << 4);
   // one 64-key tile of the ring, for the one or two query groups of this wave
   auto tile = [&](auto masked, int stage_no, int nvalid) {
     const char* stage = smem + stage_no * kStageBytes;
     if constexpr (kNG == 1) process_tile<decltype(masked)::value, D>(st, qf[0], stage, kaddr, vaddr, c, nvalid, h);
-    else if constexpr (kM16) {
-      int g2 = 0;                       // lane group: needed by the masking code of the ragged tile only
-      if (decltype(masked)::value) {
-        int t2 = threadIdx.x;
-        asm volatile("" : "+v"(t2));
-        g2 = (t2 >> 4) & 3;
-      }
-      process_tile4<decltype(masked)::value, D, kNREG, kFast>(st, qf16, qpark, stage, kaddr_x, kaddr_y, vaddr16, c, nvalid, g2);
-    } else {
+    else {
       // the lane half is needed by the masking code only (ragged tile, causal mask): taken from the
       // thread index there, it does not occupy a register through the main loop
       int h2 = 0;
@@ -965,35 +763,9 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   // through the main loop they would take registers that the accumulators and Q^T fragments need
   int tid_e = threadIdx.x;
   asm volatile("" : "+v"(tid_e));
-  int unsafe = 0;                // kFast: some row of this lane has a sum outside the safe range
-  if constexpr (kM16) {
-    const int j = tid_e & 15, g = (tid_e >> 4) & 3;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float l_tot = st.l_run[q];
-      l_tot += __shfl_xor(l_tot, 16);
-      l_tot += __shfl_xor(l_tot, 32);
-      const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-      const int pos = wg * kQueriesPerWg + (tid_e >> 6) * kQPW + 16 * q + j;
-      if (kFast && pos < a.Lq && __float_as_uint(l_tot) - __float_as_uint(kMinSum) > __float_as_uint(kMaxSum) - __float_as_uint(kMinSum))
-        unsafe = 1;
-      if (pos < a.Lq) {
-        const int orow = perm_at(a.perm_q, (int64_t)bhq * a.Lq, pos, a.Lq);
-        __bf16* op = a.out + out_off(a, bhq, orow);
-#pragma unroll
-        for (int db = 0; db < D / 16; ++db) {
-          bf16x4 pk;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(st.o[q][db][e] * inv_l);
-          *reinterpret_cast<bf16x4*>(op + 16 * db + 4 * g) = pk;
-        }
-        if (a.lse && g == 0)
-          a.lse[(int64_t)bhq * a.Lq + orow] = (st.m_run[q] + __log2f(l_tot)) * 0.6931471805599453f;
-      }
-    }
-  } else {
   const int h_e = (tid_e >> 5) & 1;
   const int pos_e = wg * kQueriesPerWg + (tid_e >> 6) * kQPW + (tid_e & 31);
+  int unsafe = 0;                // kFast: some row of this lane has a sum outside the safe range
 #pragma unroll
   for (int r = 0; r < kNG; ++r) {
     const float l_part = l_of(st, r), m_fin = m_of(st, r);
@@ -1020,7 +792,6 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
       if (a.lse && h == 0)
         a.lse[(int64_t)bhq * a.Lq + orow] = (m_fin + __log2f(l_tot)) * 0.6931471805599453f;
     }
-  }
   }
   if constexpr (kFast) {
     // (a row without any visible key has the sum 0 as well and is sent round again: it comes out as zeros both times)
