@@ -94,8 +94,14 @@ constexpr int stages_of(int threads, int qpw) { return threads == 512 ? (qpw == 
 // k-steps of Q^T a wave of 64 queries keeps in registers (the rest is parked in LDS): all for D = 64
 // (the causal variant of the 64-queries-per-wave kernel carries the two visibility limits and the
 //  key indices of the half-tile on top: one more k-step of Q^T is parked)
-constexpr int q_reg_steps(int d, int qpw, bool causal = false) {
-  return (qpw == 64 && d == 128) ? BASA_ATTN_QR - (causal ? 1 : 0) : d / 16;
+// (the pass without running maxima needs no registers for them and keeps all of Q^T, 117.6-119.1 ms
+//  against 119.7-120.5 with one k-step parked; its causal variant does better with two parked as before:
+//  139-140 ms against 147 with one)
+#ifndef BASA_ATTN_QR_FAST
+#define BASA_ATTN_QR_FAST 8
+#endif
+constexpr int q_reg_steps(int d, int qpw, bool causal = false, bool fast = false) {
+  return (qpw == 64 && d == 128) ? (fast && !causal ? BASA_ATTN_QR_FAST : BASA_ATTN_QR - (causal ? 1 : 0)) : d / 16;
 }
 
 // ---------------------------------------------------------------------------------
@@ -470,7 +476,7 @@ __global__ __launch_bounds__(kWgQueries / kQPW * 64, kWgQueries / kQPW == 8 ? 1 
   constexpr int kWaves = kWgQueries / kQPW, kThreads = kWaves * 64, kQueriesPerWg = kWgQueries;
   constexpr int kNG = kQPW / 32;             // 32-query groups per wave: 1 or 2
   constexpr int kStages = stages_of(kThreads, kQPW);
-  constexpr int kQR = q_reg_steps(D, kQPW, kCausal), kQL = G::kKSteps - kQR;
+  constexpr int kQR = q_reg_steps(D, kQPW, kCausal, kFast), kQL = G::kKSteps - kQR;
   constexpr int kQParkBytes = kWaves * kNG * kQL * 1024;
   constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kRingBytes = kStages * kStageBytes;
   constexpr int kLoadsPerWave = 2 * G::kChunksPerTile / kWaves;
@@ -804,8 +810,8 @@ size_t sz_kv(int BHkv, int Nk, int B, int d) { return align_up((size_t)BHkv * Nk
 size_t sz_kix(int BHkv, int Nk, int B) { return align_up((size_t)BHkv * (Nk * B / kTileKeys) * kIxStride * 4, 256); }
 
 template <int D>
-size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false) {
-  const size_t park = (size_t)(threads / 64) * (qpw / 32) * (D / 16 - q_reg_steps(D, qpw, causal)) * 1024;
+size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false, bool fast = false) {
+  const size_t park = (size_t)(threads / 64) * (qpw / 32) * (D / 16 - q_reg_steps(D, qpw, causal, fast)) * 1024;
   const size_t base = (size_t)stages_of(threads, qpw) * Geo<D>::kStageBytes + park + (size_t)Nk * 4 + (threads / 64) * 4;
   return causal ? ((base + 15) & ~(size_t)15) + (size_t)stages_of(threads, qpw) * kIxStride * 4 : base;
 }
@@ -813,7 +819,7 @@ size_t lds_bytes(int threads, int qpw, int Nk, bool causal = false) {
 template <int kB, int D, int kWgQueries, int kQPW, bool kCausal = false, bool kFast = false>
 basa_status launch_main(MfmaArgs m, int BHq, hipStream_t st) {
   constexpr int kThreads = kWgQueries / kQPW * 64;
-  const size_t lds = lds_bytes<D>(kThreads, kQPW, m.Nk, kCausal);
+  const size_t lds = lds_bytes<D>(kThreads, kQPW, m.Nk, kCausal, kFast);
   // while the union list is built, the per-key-block membership flags live in the ring area
   if ((size_t)m.Nk * 4 > (size_t)stages_of(kThreads, kQPW) * Geo<D>::kStageBytes) {
     set_error("attention: %d key blocks exceed the %zu this workgroup shape can list", m.Nk,
