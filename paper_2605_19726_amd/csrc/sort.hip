@@ -162,16 +162,27 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
 
   // ---- phase 1: keys of tokens start .. start+n-1 into buf
   // Every load is unconditional, its row clamped into the tile (a row past the end reads the
-  // tile's last row, whose key is never written; the pass after the last reads the last again,
-  // from cache): loads inside branches make the compiler wait for ALL outstanding loads at the
-  // join, the prefetch of the next pass included, and the double buffering is lost.
+  // tile's last row, whose key is never written): loads inside branches make the compiler wait
+  // for ALL outstanding loads at the join, the prefetch of the next pass included, and the double
+  // buffering is lost.
   const int passes = (n + kRowsPerPass - 1) / kRowsPerPass;
   auto load_pass = [&](int pass, uint4 (&raw)[kIters]) {
-    const int p = min(pass, passes - 1);
+    // A pass past the last (the loop below asks for up to four of them) has every lane read the tile's
+    // first 16 bytes, one cache line per instruction, instead of the last pass again: the loads are
+    // streaming loads, which nothing caches, so a repeated pass would cost its 32 KB of HBM traffic
+    // again (an eighth of the tile in all).
+    const bool live = pass < passes;             // uniform over the workgroup
+    const int sub_l = live ? sub : 0;
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
-      const int loc = min(p * kRowsPerPass + it * kRowsPerIter + rig, n - 1);
-      raw[it] = reinterpret_cast<const uint4*>(base + (int64_t)(start + loc) * x.stride_l * kElem)[sub];
+      const int loc = live ? min(pass * kRowsPerPass + it * kRowsPerIter + rig, n - 1) : 0;
+      // (streaming loads: every row is read once here; with the hint the pass takes 0.416 instead of
+      //  0.431 ms at 128K, the rows no longer push the sort words being written out of the cache)
+      // (bit-cast into uint4, not held as the builtin's vector type: the compiler rotates such vectors
+      //  through the three buffers as whole registers, copies that count as uses of loads still in
+      //  flight, and every batch is then waited for at the top of the loop)
+      typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+      raw[it] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (int64_t)(start + loc) * x.stride_l * kElem) + sub_l));
     }
   };
   auto keys_of_pass = [&](int pass, const uint4 (&cur)[kIters]) {
@@ -229,7 +240,7 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
     }
   };
   // three batches of rows: two are in flight while the third is turned into keys (a pass past the last
-  // re-reads the last one and writes nothing: its positions lie beyond n)
+  // writes nothing: its positions lie beyond n)
   uint4 b0[kIters], b1[kIters], b2[kIters];
   load_pass(0, b0);
   load_pass(1, b1);
@@ -265,7 +276,8 @@ __global__ __launch_bounds__(kSortThreads) void norm_tile_sort_kernel(TensorView
   if (perm_out) {
     for (int i = threadIdx.x; i < n; i += kSortThreads) perm_out[hb + start + i] = idx_of_word(buf[tile_slot(i)]);
   } else {
-    for (int i = threadIdx.x; i < n; i += kSortThreads) out[hb + start + i] = buf[tile_slot(i)];
+    // (streaming stores, like the loads of the rows: another 3 % of this kernel)
+    for (int i = threadIdx.x; i < n; i += kSortThreads) __builtin_nontemporal_store(buf[tile_slot(i)], &out[hb + start + i]);
   }
 }
 

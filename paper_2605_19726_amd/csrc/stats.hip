@@ -73,8 +73,8 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
   const int64_t row_bytes = x.stride_l * kElem;
 
   // Token rows of block b for this thread.  Every load below is unconditional, with its index
-  // clamped into the sequence (a block past the workgroup's last one reads the last one again,
-  // from cache; a position past L reads row L-1 and is masked out where it is used): a load inside
+  // clamped into the sequence (a position past L reads row L-1 and is masked out where it is
+  // used): a load inside
   // a divergent branch is followed by a full wait, which serialises the eight loads of a thread.
   auto load_rows = [&](int b, int (&rows)[ITERS]) {             // entries as stored, checked at use
     const int p0 = (g0 + min(b, nb - 1)) * kB + rig;
@@ -88,11 +88,19 @@ __global__ __launch_bounds__(256) void block_stats_kernel(StatsJob j0, StatsJob 
   };
   auto load_chunks = [&](int b, const int (&rows)[ITERS], uint4 (&raw)[ITERS]) {
     const int p0 = (g0 + min(b, nb - 1)) * kB + rig;
+    // a block past the workgroup's last has every lane read the head's first 16 bytes instead (one
+    // cache line per instruction): streaming loads are not cached, a repeated block would be paid for
+    const bool live = b < nb;                    // uniform over the workgroup
+    const int sub_l = live ? sub : 0;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       // a malformed permutation entry falls back to the position itself
       const int row = (unsigned)rows[it] < (unsigned)L ? rows[it] : min(p0 + it * RPI, L - 1);
-      raw[it] = reinterpret_cast<const uint4*>(base + row * row_bytes)[sub];
+      // (streaming loads, as in the key pass: every row is read once)
+      // (bit-cast into uint4, not held as the builtin's vector type: the compiler moves such vectors from
+      //  buffer to buffer as whole registers, copies that count as uses of loads still in flight)
+      typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+      raw[it] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (live ? row : 0) * row_bytes) + sub_l));
     }
   };
 
